@@ -1,0 +1,203 @@
+/*
+ * raf_mi355.h - C ABI of the single-GPU mixed-precision training step of one
+ * transformer layer on MI355X (gfx950): forward, backward, fused Adam.
+ *
+ * What the calls compute follows the paper (RAF, arXiv 2303.04759):
+ *   - a training workload is forward graph + loss + backward graph + optimizer
+ *     over learnable parameters (Section 2.1, Fig. "Deep learning training
+ *     workload");
+ *   - the backward graph is the chain of adjoints of the forward operators
+ *     (Section 3.1.1);
+ *   - mixed precision keeps numerically sensitive operators in full precision
+ *     and fuses every cast into its consumer (Section 3.1.2);
+ *   - the optimizer is part of the step and updates parameters in place
+ *     (Section 3, graph-generation phase);
+ *   - elementwise / reduction operators are fused into their producers or with
+ *     each other (Section 3.2.2).
+ * The system "accepts a forward model and generates the training graph"
+ * (Section 1); here the forward model is the plain-data descriptor below.
+ *
+ * General conventions (all entry points)
+ *   - Every pointer marked [dev] is device memory owned by the caller; the
+ *     library never allocates, frees or synchronises, and keeps no pointer
+ *     after a call returns.  [host] pointers are read during the call only.
+ *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*,
+ *     NULL = the default stream).  Calls are asynchronous; they are safe to
+ *     record into a HIP graph (no memset/memcpy nodes are issued).
+ *   - Tensors are dense, row-major, 16-byte aligned (else RAF_EINVAL).
+ *   - "compute dtype" is float in RAF_F32 mode and bfloat16 (round to nearest
+ *     even) in RAF_BF16_AMP mode.  Vectors (biases, LayerNorm gamma/beta),
+ *     gradients, optimizer state and all statistics are always float.
+ *   - No C++ exception crosses the ABI; every call returns a raf_status.
+ *     After RAF_EHIP, raf_last_hip_error() names the HIP error.
+ *   - Supported shapes: hidden/heads == 64; seq, hidden, ffn multiples of 32;
+ *     seq <= 4096, hidden <= 4096; 0 <= dropout_p < 1.  Others: RAF_ENOTSUP.
+ *   - Calls on different streams may overlap only if their buffers differ.
+ */
+#ifndef RAF_MI355_H
+#define RAF_MI355_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  RAF_OK = 0,
+  RAF_EINVAL = -1,     /* null / misaligned pointer, bad field value            */
+  RAF_ENOTSUP = -2,    /* well-formed but outside the supported shapes          */
+  RAF_EWORKSPACE = -3, /* reserved                                              */
+  RAF_EHIP = -4        /* a HIP launch failed; see raf_last_hip_error()         */
+} raf_status;
+
+typedef enum { RAF_F32 = 0, RAF_BF16_AMP = 1 } raf_precision;
+
+/* The forward model: one transformer layer (plain data, no pointers).
+ *   post-LN (pre_ln=0):  h1 = LN1(x + drop2(attn(x)));  y = LN2(h1 + drop3(ffn(h1)))
+ *   pre-LN  (pre_ln=1):  h  = x + drop2(attn(LN1(x)));  y = h + drop3(ffn(LN2(h)))
+ * attn = out_proj(merge_heads(drop1(softmax(mask(Q K^T / 8))) V)), ffn = W2 gelu(W1 . + b1) + b2.
+ * Dropout sites: 1 = attention probabilities [B,heads,S,S], 2 = attention
+ * output [T,H], 3 = ffn output [T,H]; element idx of a site is kept iff word
+ * (idx & 3) of Philox4x32-10(counter = (idx>>2, step>>32, site | layer_id<<8,
+ * step & 0xffffffff), key = (seed lo, seed hi)) is >= floor(dropout_p * 2^32);
+ * kept values are scaled by 1/(1-dropout_p). */
+typedef struct {
+  int32_t batch, seq, hidden, heads, ffn;
+  int32_t pre_ln;    /* 0 = post-LN (BERT style), 1 = pre-LN (GPT style)                 */
+  int32_t causal;    /* 1: key j > query i is masked (in addition to padding)            */
+  int32_t gelu_tanh; /* 0 = erf GeLU, 1 = tanh approximation                             */
+  int32_t precision; /* raf_precision                                                     */
+  float ln_eps;      /* added to the biased variance                                      */
+  double dropout_p;  /* [0,1); the keep threshold is floor(dropout_p * 2^32) in double    */
+  uint64_t seed;     /* dropout key                                                       */
+  uint32_t layer_id; /* folded into the dropout counter (24 bits used)                    */
+  uint32_t reserved; /* must be 0                                                         */
+} raf_layer_desc;
+
+/* The twelve parameter tensors of a layer, or their gradients.
+ * Shapes ([out,in] row-major for matrices): w_qkv [3H,H] (rows: Q block, K
+ * block, V block), b_qkv [3H], w_o [H,H], b_o [H], ln1_g/ln1_b [H],
+ * w_1 [F,H], b_1 [F], w_2 [H,F], b_2 [H], ln2_g/ln2_b [H].
+ * As weights: w_* in compute dtype, all vectors float.  As gradients: all float. */
+typedef struct {
+  void *w_qkv, *b_qkv, *w_o, *b_o, *ln1_g, *ln1_b, *w_1, *b_1, *w_2, *b_2, *ln2_g, *ln2_b;
+} raf_layer_tensors;
+
+/* Sizes in bytes of the two caller-provided buffers of a layer.
+ * `saved` carries activations from raf_layer_fwd to raf_layer_bwd of the same
+ * step (opaque layout); `scratch` is dead outside a call and may be shared by
+ * all layers on one stream.  Both sizes are multiples of 256. */
+raf_status raf_layer_workspace(const raf_layer_desc *desc /*host*/, size_t *saved_bytes /*host out*/,
+                               size_t *scratch_bytes /*host out*/);
+
+/* Forward pass (Section 2.1 "forward graph"; fused operators per Section 3.2.2).
+ *   w        [host struct of dev pointers] weights, see raf_layer_tensors
+ *   x        [dev] input  [B*S, H], compute dtype
+ *   seq_lens [dev] int32 [B], valid keys per sequence (key j >= len is masked,
+ *            probability exactly 0; a row with no admissible key gives zeros);
+ *            NULL = all sequences full length
+ *   y        [dev] output [B*S, H], compute dtype
+ *   saved    [dev] >= saved_bytes,  written
+ *   scratch  [dev] >= scratch_bytes, clobbered
+ *   step     dropout step counter (use the optimizer step) */
+raf_status raf_layer_fwd(const raf_layer_desc *desc, const raf_layer_tensors *w, const void *x,
+                         const int32_t *seq_lens, void *y, void *saved, void *scratch, uint64_t step,
+                         void *hip_stream);
+
+/* Backward pass: adjoints of the forward operators in reverse order (Section
+ * 3.1.1), dropout masks recomputed from the counter, not stored.
+ *   x, seq_lens, saved, step: exactly what the matching raf_layer_fwd saw/wrote
+ *   dy     [dev] gradient w.r.t. y [B*S,H], compute dtype (already loss-scaled)
+ *   dx     [dev] gradient w.r.t. x [B*S,H], compute dtype, overwritten
+ *   grads  [host struct of dev pointers] twelve float tensors, OVERWRITTEN
+ *          with the (loss-scaled) gradients; no accumulation across calls */
+raf_status raf_layer_bwd(const raf_layer_desc *desc, const raf_layer_tensors *w, const void *x, const void *dy,
+                         const int32_t *seq_lens, const void *saved, void *dx, raf_layer_tensors *grads,
+                         void *scratch, uint64_t step, void *hip_stream);
+
+/* Loss seed of the benchmark workload: loss = sum(y * G) (float accumulate,
+ * deterministic), dy = loss_scale * G in compute dtype.
+ *   y, G [dev] [n] compute dtype; loss_out [dev] one float; dy [dev] [n];
+ *   partial [dev] float[RAF_LOSS_PARTIALS] scratch.  n must be a multiple of 8. */
+#define RAF_LOSS_PARTIALS 1024
+raf_status raf_loss_seed(int32_t precision, const void *y, const void *G, int64_t n, float loss_scale,
+                         float *loss_out, void *dy, float *partial, void *hip_stream);
+
+/* One tensor of the optimizer's list.  master/grad/m/v: [dev] float[n];
+ * lowp: [dev] bfloat16[n] copy of the updated master (the AMP cast fused into
+ * the producer, Section 3.1.2), or NULL.  n >= 0; pointers 16-byte aligned. */
+typedef struct {
+  float *master;
+  const float *grad;
+  float *m;
+  float *v;
+  void *lowp;
+  int64_t n;
+} raf_adam_tensor;
+
+/* Fused multi-tensor Adam (optimizer inside the step, in-place update; Section 3).
+ * Per element: g = grad*inv_loss_scale (+ weight_decay*w); m = b1 m + (1-b1) g;
+ * v = b2 v + (1-b2) g^2; w -= lr * (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps).
+ *   list [host] array of `count` tensors (copied into kernel arguments);
+ *   t is 1-based.  count == 0 is a no-op. */
+raf_status raf_adam_step(const raf_adam_tensor *list, int32_t count, float lr, float beta1, float beta2,
+                         float eps, float weight_decay, int64_t t, float inv_loss_scale, void *hip_stream);
+
+/* Test hook: the keep-mask of one dropout site as bytes (1 = kept).
+ *   mask_out [dev] uint8[n]; element order is the site's flat index. */
+raf_status raf_debug_dropout_mask(const raf_layer_desc *desc, int32_t site, uint64_t step, uint8_t *mask_out,
+                                  int64_t n, void *hip_stream);
+
+/* ---- single fused operators, exported for per-kernel parity tests and
+ * per-kernel roofline measurement; the layer calls above use the same kernels. */
+
+/* C[M,N] = epilogue(alpha * A.B) on the MFMA (bf16) or FMA (f32) GEMM kernel.
+ * a_kmajor=1: A element (i,k) at a[i*lda+k]; 0: at a[k*lda+i].
+ * b_kmajor=1: B element (k,j) at b[j*ldb+k]; 0: at b[k*ldb+j].
+ * epilogue: 0 none, 1 +bias[j], 2 +bias then GeLU (pre-activation stored to
+ * aux, same shape/ld as C), 3 multiply by gelu'(aux[i,j]), 4 +residual aux[i,j].
+ * out_f32=1 stores C as float regardless of precision. M,N,K multiples of 32. */
+raf_status raf_op_gemm(int32_t precision, int32_t M, int32_t N, int32_t K, const void *a, int32_t lda,
+                       int32_t a_kmajor, const void *b, int32_t ldb, int32_t b_kmajor, void *c, int32_t ldc,
+                       int32_t out_f32, float alpha, int32_t epilogue, const float *bias, void *aux,
+                       int32_t gelu_tanh, void *hip_stream);
+
+/* Masked softmax (+ dropout site 1) over the last axis of s [B,heads,S,S]:
+ * writes prob (softmax) and prob_d (after dropout), both compute dtype. */
+raf_status raf_op_softmax_fwd(const raf_layer_desc *desc, const void *s, const int32_t *seq_lens, void *prob,
+                              void *prob_d, uint64_t step, void *hip_stream);
+/* ds = scale_out * prob * (dprob - sum_j dprob*prob), dprob = dprob_d * keep/(1-p)
+ * where keep is recovered as (prob_d != 0 or prob == 0). */
+raf_status raf_op_softmax_bwd(const raf_layer_desc *desc, const void *prob, const void *prob_d,
+                              const void *dprob_d, void *ds, float scale_out, void *hip_stream);
+
+/* z = res + dropout_site(a); out = LayerNorm(z) with float statistics.
+ * a == NULL: z = res (plain LayerNorm).  gamma == NULL: no LayerNorm, out = z
+ * (z_out, mu, rstd ignored).  site in {2,3}. rows*H elements, compute dtype. */
+raf_status raf_op_dropout_residual_ln_fwd(const raf_layer_desc *desc, int32_t site, int64_t rows, const void *a,
+                                          const void *res, const float *gamma, const float *beta, void *out,
+                                          void *z_out, float *mu, float *rstd, uint64_t step, void *hip_stream);
+
+/* Adjoint of the above.  g_in = dout (+ dout2 if not NULL).
+ * gamma != NULL: dz = LN-backward(g_in; z, mu, rstd, gamma) (+ dres if not
+ * NULL), dgamma/dbeta = column sums; gamma == NULL: dz = g_in.
+ * site != 0: da = dz * keep_site/(1-p) and dbias = column sums of da.
+ * partial: [dev] float scratch of raf_op_ln_bwd_partial_floats(H) floats. */
+size_t raf_op_ln_bwd_partial_floats(int32_t hidden, int64_t rows);
+raf_status raf_op_dropout_residual_ln_bwd(const raf_layer_desc *desc, int32_t site, int64_t rows, const void *dout,
+                                          const void *dout2, const void *z, const float *mu, const float *rstd,
+                                          const float *gamma, const void *dres, void *dz, void *da, float *dgamma,
+                                          float *dbeta, float *dbias, float *partial, uint64_t step,
+                                          void *hip_stream);
+
+const char *raf_status_string(raf_status s);
+const char *raf_last_hip_error(void);
+/* Library version string, e.g. "raf_mi355 0.1 gfx950". */
+const char *raf_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RAF_MI355_H */

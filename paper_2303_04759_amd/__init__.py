@@ -1,0 +1,229 @@
+"""Thin ctypes binding of libraf_mi355.so (see include/raf_mi355.h).
+
+Argument marshalling only: every function has the name and the argument order
+of its C entry point, takes torch tensors (or None) where the C call takes
+device pointers, and raises RafError on a non-zero status.  There is no CPU
+fallback: without the built library, or without a GPU for the calls that
+launch kernels, it fails loudly.
+"""
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libraf_mi355.so")
+
+RAF_F32, RAF_BF16_AMP = 0, 1
+RAF_OK, RAF_EINVAL, RAF_ENOTSUP, RAF_EWORKSPACE, RAF_EHIP = 0, -1, -2, -3, -4
+RAF_LOSS_PARTIALS = 1024
+EPI_NONE, EPI_BIAS, EPI_BIAS_GELU, EPI_MUL_GELU_GRAD, EPI_ADD_RES = range(5)
+
+PARAM_NAMES = ("w_qkv", "b_qkv", "w_o", "b_o", "ln1_g", "ln1_b",
+               "w_1", "b_1", "w_2", "b_2", "ln2_g", "ln2_b")
+
+
+class RafError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = "%s failed: %s (%d)" % (where, status_string(status), status)
+        if status == RAF_EHIP:
+            msg += ": " + last_hip_error()
+        super().__init__(msg)
+
+
+class LayerDesc(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("seq", C.c_int32), ("hidden", C.c_int32), ("heads", C.c_int32),
+                ("ffn", C.c_int32), ("pre_ln", C.c_int32), ("causal", C.c_int32), ("gelu_tanh", C.c_int32),
+                ("precision", C.c_int32), ("ln_eps", C.c_float), ("dropout_p", C.c_double),
+                ("seed", C.c_uint64), ("layer_id", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+class LayerTensors(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in PARAM_NAMES]
+
+
+class AdamTensor(C.Structure):
+    _fields_ = [("master", C.c_void_p), ("grad", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p),
+                ("lowp", C.c_void_p), ("n", C.c_int64)]
+
+
+_lib = None
+
+_SIGNATURES = {
+    "raf_layer_workspace": (C.c_int, [C.POINTER(LayerDesc), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]),
+    "raf_layer_fwd": (C.c_int, [C.POINTER(LayerDesc), C.POINTER(LayerTensors), C.c_void_p, C.c_void_p, C.c_void_p,
+                                C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]),
+    "raf_layer_bwd": (C.c_int, [C.POINTER(LayerDesc), C.POINTER(LayerTensors), C.c_void_p, C.c_void_p, C.c_void_p,
+                                C.c_void_p, C.c_void_p, C.POINTER(LayerTensors), C.c_void_p, C.c_uint64, C.c_void_p]),
+    "raf_loss_seed": (C.c_int, [C.c_int32, C.c_void_p, C.c_void_p, C.c_int64, C.c_float, C.c_void_p, C.c_void_p,
+                                C.c_void_p, C.c_void_p]),
+    "raf_adam_step": (C.c_int, [C.POINTER(AdamTensor), C.c_int32, C.c_float, C.c_float, C.c_float, C.c_float,
+                                C.c_float, C.c_int64, C.c_float, C.c_void_p]),
+    "raf_debug_dropout_mask": (C.c_int, [C.POINTER(LayerDesc), C.c_int32, C.c_uint64, C.c_void_p, C.c_int64,
+                                         C.c_void_p]),
+    "raf_op_gemm": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_int32,
+                              C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_float,
+                              C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
+    "raf_op_softmax_fwd": (C.c_int, [C.POINTER(LayerDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_uint64, C.c_void_p]),
+    "raf_op_softmax_bwd": (C.c_int, [C.POINTER(LayerDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_float, C.c_void_p]),
+    "raf_op_dropout_residual_ln_fwd": (C.c_int, [C.POINTER(LayerDesc), C.c_int32, C.c_int64, C.c_void_p, C.c_void_p,
+                                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                 C.c_void_p, C.c_uint64, C.c_void_p]),
+    "raf_op_ln_bwd_partial_floats": (C.c_size_t, [C.c_int32, C.c_int64]),
+    "raf_op_dropout_residual_ln_bwd": (C.c_int, [C.POINTER(LayerDesc), C.c_int32, C.c_int64] + [C.c_void_p] * 13 +
+                                       [C.c_uint64, C.c_void_p]),
+    "raf_status_string": (C.c_char_p, [C.c_int]),
+    "raf_last_hip_error": (C.c_char_p, []),
+    "raf_version": (C.c_char_p, []),
+}
+EXPORTS = tuple(_SIGNATURES)
+
+
+def load_library():
+    """Load the in-tree shared library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("%s is missing: run `python __graft_entry__.py` (build()) first; "
+                           "there is no fallback path" % LIB_PATH)
+    lib = C.CDLL(LIB_PATH)
+    for name, (res, args) in _SIGNATURES.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = lib
+    return lib
+
+
+def status_string(status):
+    return load_library().raf_status_string(int(status)).decode()
+
+
+def last_hip_error():
+    return load_library().raf_last_hip_error().decode()
+
+
+def version():
+    return load_library().raf_version().decode()
+
+
+def _check(status, where):
+    if status != RAF_OK:
+        raise RafError(status, where)
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if not t.is_cuda:
+        raise ValueError("device tensor expected")
+    if not t.is_contiguous():
+        raise ValueError("contiguous tensor expected")
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def make_desc(cfg):
+    """LayerDesc from a config dict (keys as in workloads.synthetic.CONFIGS)."""
+    return LayerDesc(batch=cfg["batch"], seq=cfg["seq"], hidden=cfg["hidden"], heads=cfg["heads"], ffn=cfg["ffn"],
+                     pre_ln=cfg.get("pre_ln", 0), causal=cfg.get("causal", 0), gelu_tanh=cfg.get("gelu_tanh", 0),
+                     precision=cfg["precision"], ln_eps=cfg["ln_eps"], dropout_p=cfg["dropout_p"],
+                     seed=cfg["seed"], layer_id=cfg.get("layer_id", 0), reserved=0)
+
+
+def make_tensors(d):
+    """LayerTensors from a dict name -> tensor."""
+    t = LayerTensors()
+    for n in PARAM_NAMES:
+        setattr(t, n, _ptr(d[n]))
+    return t
+
+
+def raf_layer_workspace(desc):
+    sv, sc = C.c_size_t(0), C.c_size_t(0)
+    _check(load_library().raf_layer_workspace(C.byref(desc), C.byref(sv), C.byref(sc)), "raf_layer_workspace")
+    return sv.value, sc.value
+
+
+def raf_layer_fwd(desc, w, x, seq_lens, y, saved, scratch, step, stream=None):
+    _check(load_library().raf_layer_fwd(C.byref(desc), C.byref(w), _ptr(x), _ptr(seq_lens), _ptr(y), _ptr(saved),
+                                        _ptr(scratch), int(step), _stream(stream)), "raf_layer_fwd")
+
+
+def raf_layer_bwd(desc, w, x, dy, seq_lens, saved, dx, grads, scratch, step, stream=None):
+    _check(load_library().raf_layer_bwd(C.byref(desc), C.byref(w), _ptr(x), _ptr(dy), _ptr(seq_lens), _ptr(saved),
+                                        _ptr(dx), C.byref(grads), _ptr(scratch), int(step), _stream(stream)),
+           "raf_layer_bwd")
+
+
+def raf_loss_seed(precision, y, G, n, loss_scale, loss_out, dy, partial, stream=None):
+    _check(load_library().raf_loss_seed(int(precision), _ptr(y), _ptr(G), int(n), float(loss_scale), _ptr(loss_out),
+                                        _ptr(dy), _ptr(partial), _stream(stream)), "raf_loss_seed")
+
+
+def make_adam_list(entries):
+    """entries: iterable of (master, grad, m, v, lowp_or_None) tensors -> (ctypes array, count)."""
+    entries = list(entries)
+    arr = (AdamTensor * max(1, len(entries)))()
+    for i, (w, g, m, v, lowp) in enumerate(entries):
+        arr[i] = AdamTensor(_ptr(w), _ptr(g), _ptr(m), _ptr(v), _ptr(lowp), w.numel())
+    return arr, len(entries)
+
+
+def raf_adam_step(adam_list, count, lr, beta1, beta2, eps, weight_decay, t, inv_loss_scale, stream=None):
+    _check(load_library().raf_adam_step(adam_list, int(count), float(lr), float(beta1), float(beta2), float(eps),
+                                        float(weight_decay), int(t), float(inv_loss_scale), _stream(stream)),
+           "raf_adam_step")
+
+
+def raf_debug_dropout_mask(desc, site, step, mask_out, n, stream=None):
+    _check(load_library().raf_debug_dropout_mask(C.byref(desc), int(site), int(step), _ptr(mask_out), int(n),
+                                                 _stream(stream)), "raf_debug_dropout_mask")
+
+
+def raf_op_gemm(precision, M, N, K, a, lda, a_kmajor, b, ldb, b_kmajor, c, ldc, out_f32=0, alpha=1.0,
+                epilogue=EPI_NONE, bias=None, aux=None, gelu_tanh=0, stream=None):
+    _check(load_library().raf_op_gemm(int(precision), M, N, K, _ptr(a), lda, int(a_kmajor), _ptr(b), ldb,
+                                      int(b_kmajor), _ptr(c), ldc, int(out_f32), float(alpha), int(epilogue),
+                                      _ptr(bias), _ptr(aux), int(gelu_tanh), _stream(stream)), "raf_op_gemm")
+
+
+def raf_op_softmax_fwd(desc, s, seq_lens, prob, prob_d, step, stream=None):
+    _check(load_library().raf_op_softmax_fwd(C.byref(desc), _ptr(s), _ptr(seq_lens), _ptr(prob), _ptr(prob_d),
+                                             int(step), _stream(stream)), "raf_op_softmax_fwd")
+
+
+def raf_op_softmax_bwd(desc, prob, prob_d, dprob_d, ds, scale_out, stream=None):
+    _check(load_library().raf_op_softmax_bwd(C.byref(desc), _ptr(prob), _ptr(prob_d), _ptr(dprob_d), _ptr(ds),
+                                             float(scale_out), _stream(stream)), "raf_op_softmax_bwd")
+
+
+def raf_op_dropout_residual_ln_fwd(desc, site, rows, a, res, gamma, beta, out, z_out, mu, rstd, step, stream=None):
+    _check(load_library().raf_op_dropout_residual_ln_fwd(C.byref(desc), int(site), int(rows), _ptr(a), _ptr(res),
+                                                         _ptr(gamma), _ptr(beta), _ptr(out), _ptr(z_out), _ptr(mu),
+                                                         _ptr(rstd), int(step), _stream(stream)),
+           "raf_op_dropout_residual_ln_fwd")
+
+
+def raf_op_ln_bwd_partial_floats(hidden, rows):
+    return load_library().raf_op_ln_bwd_partial_floats(int(hidden), int(rows))
+
+
+def raf_op_dropout_residual_ln_bwd(desc, site, rows, dout, dout2, z, mu, rstd, gamma, dres, dz, da, dgamma, dbeta,
+                                   dbias, partial, step, stream=None):
+    _check(load_library().raf_op_dropout_residual_ln_bwd(
+        C.byref(desc), int(site), int(rows), _ptr(dout), _ptr(dout2), _ptr(z), _ptr(mu), _ptr(rstd), _ptr(gamma),
+        _ptr(dres), _ptr(dz), _ptr(da), _ptr(dgamma), _ptr(dbeta), _ptr(dbias), _ptr(partial), int(step),
+        _stream(stream)), "raf_op_dropout_residual_ln_bwd")

@@ -1,0 +1,218 @@
+// Shared device helpers for the gfx950 kernels: 8-wide typed vector access,
+// bf16 conversion, the Philox4x32-10 dropout generator, wavefront reductions.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "raf_mi355.h"
+
+namespace raf {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+constexpr int WAVE = 64;
+
+// ---------------------------------------------------------------- status --
+void set_hip_error(hipError_t e);
+inline raf_status check_launch() {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) {
+    set_hip_error(e);
+    return RAF_EHIP;
+  }
+  return RAF_OK;
+}
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// ------------------------------------------------------- typed 8-vectors --
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t hi16) { return __uint_as_float(hi16 << 16); }
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  // round-to-nearest-even; lowers to v_cvt_pk_bf16_f32 on gfx950
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  bf16x2_t v = {(__bf16)lo, (__bf16)hi};
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+template <typename T>
+struct Vec8;
+
+template <>
+struct Vec8<float> {
+  static __device__ __forceinline__ void load(const float* p, float (&o)[8]) {
+    const float4 a = *reinterpret_cast<const float4*>(p);
+    const float4 b = *reinterpret_cast<const float4*>(p + 4);
+    o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w;
+    o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+  }
+  static __device__ __forceinline__ void store(float* p, const float (&v)[8]) {
+    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+  }
+  // value as it will read back from storage
+  static __device__ __forceinline__ float round(float v) { return v; }
+};
+
+template <>
+struct Vec8<bf16_t> {
+  static __device__ __forceinline__ void load(const bf16_t* p, float (&o)[8]) {
+    const uint4 r = *reinterpret_cast<const uint4*>(p);
+    o[0] = bf16_bits_to_f32(r.x & 0xffffu); o[1] = __uint_as_float(r.x & 0xffff0000u);
+    o[2] = bf16_bits_to_f32(r.y & 0xffffu); o[3] = __uint_as_float(r.y & 0xffff0000u);
+    o[4] = bf16_bits_to_f32(r.z & 0xffffu); o[5] = __uint_as_float(r.z & 0xffff0000u);
+    o[6] = bf16_bits_to_f32(r.w & 0xffffu); o[7] = __uint_as_float(r.w & 0xffff0000u);
+  }
+  static __device__ __forceinline__ void store(bf16_t* p, const float (&v)[8]) {
+    uint4 r;
+    r.x = pack_bf16x2(v[0], v[1]);
+    r.y = pack_bf16x2(v[2], v[3]);
+    r.z = pack_bf16x2(v[4], v[5]);
+    r.w = pack_bf16x2(v[6], v[7]);
+    *reinterpret_cast<uint4*>(p) = r;
+  }
+  static __device__ __forceinline__ float round(float v) { return (float)(__bf16)v; }
+};
+
+__device__ __forceinline__ void load8f(const float* p, float (&o)[8]) { Vec8<float>::load(p, o); }
+
+// ----------------------------------------------------------------- Philox --
+// Philox4x32-10 (Salmon et al., SC'11): ten rounds of two 32x32->64 multiplies
+// with a Weyl-sequence key schedule.
+struct Philox4 {
+  uint32_t x, y, z, w;
+};
+
+__device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                                 uint32_t k1) {
+  constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
+    const uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+    const uint32_t n0 = hi1 ^ c1 ^ k0;
+    const uint32_t n2 = hi0 ^ c3 ^ k1;
+    c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+    k0 += W0;
+    k1 += W1;
+  }
+  return Philox4{c0, c1, c2, c3};
+}
+
+// Everything a kernel needs to regenerate one dropout site's mask.
+struct DropSite {
+  uint32_t k0, k1;      // seed lo, hi
+  uint32_t c1, c2, c3;  // step hi, site | layer<<8, step lo
+  uint32_t thr;         // keep iff word >= thr
+  float scale;          // 1/(1-p)
+  int enabled;          // 0: p == 0 or no dropout at this call
+};
+
+inline DropSite make_drop_site(const raf_layer_desc& d, int site, uint64_t step) {
+  DropSite s;
+  s.k0 = (uint32_t)(d.seed & 0xffffffffu);
+  s.k1 = (uint32_t)(d.seed >> 32);
+  s.c1 = (uint32_t)(step >> 32);
+  s.c2 = ((uint32_t)site & 0xffu) | ((d.layer_id & 0xffffffu) << 8);
+  s.c3 = (uint32_t)(step & 0xffffffffu);
+  const double t = d.dropout_p * 4294967296.0;
+  s.thr = (uint32_t)t;  // floor for t >= 0
+  s.scale = (float)(1.0 / (1.0 - d.dropout_p));
+  s.enabled = (site != 0 && d.dropout_p > 0.0) ? 1 : 0;
+  return s;
+}
+
+// keep-multipliers (0 or scale) for 8 consecutive elements starting at flat
+// index idx8 (a multiple of 8): two Philox blocks.
+__device__ __forceinline__ void drop_mult8(const DropSite& s, uint64_t idx8, float (&mult)[8]) {
+  const uint32_t blk = (uint32_t)(idx8 >> 2);
+  const Philox4 a = philox4x32_10(blk, s.c1, s.c2, s.c3, s.k0, s.k1);
+  const Philox4 b = philox4x32_10(blk + 1, s.c1, s.c2, s.c3, s.k0, s.k1);
+  mult[0] = a.x >= s.thr ? s.scale : 0.f; mult[1] = a.y >= s.thr ? s.scale : 0.f;
+  mult[2] = a.z >= s.thr ? s.scale : 0.f; mult[3] = a.w >= s.thr ? s.scale : 0.f;
+  mult[4] = b.x >= s.thr ? s.scale : 0.f; mult[5] = b.y >= s.thr ? s.scale : 0.f;
+  mult[6] = b.z >= s.thr ? s.scale : 0.f; mult[7] = b.w >= s.thr ? s.scale : 0.f;
+}
+
+// ------------------------------------------------------------- reductions --
+template <int WIDTH>
+__device__ __forceinline__ float group_sum(float v) {
+#pragma unroll
+  for (int o = WIDTH / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+  return v;
+}
+template <int WIDTH>
+__device__ __forceinline__ float group_max(float v) {
+#pragma unroll
+  for (int o = WIDTH / 2; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
+  return v;
+}
+
+// ------------------------------------------------------------------- GeLU --
+__device__ __forceinline__ float gelu_f(float u, int tanh_form) {
+  if (tanh_form) {
+    const float k = 0.7978845608028654f;
+    return 0.5f * u * (1.0f + tanhf(k * (u + 0.044715f * u * u * u)));
+  }
+  return 0.5f * u * (1.0f + erff(u * 0.7071067811865476f));
+}
+__device__ __forceinline__ float gelu_grad_f(float u, int tanh_form) {
+  if (tanh_form) {
+    const float k = 0.7978845608028654f;
+    const float t = tanhf(k * (u + 0.044715f * u * u * u));
+    return 0.5f * (1.0f + t) + 0.5f * u * (1.0f - t * t) * k * (1.0f + 0.134145f * u * u);
+  }
+  const float Phi = 0.5f * (1.0f + erff(u * 0.7071067811865476f));
+  const float phi = 0.3989422804014327f * __expf(-0.5f * u * u);
+  return Phi + u * phi;
+}
+
+// --------------------------------------------------------- internal ops ---
+enum Epilogue { EPI_NONE = 0, EPI_BIAS = 1, EPI_BIAS_GELU = 2, EPI_MUL_GELU_GRAD = 3, EPI_ADD_RES = 4 };
+
+// One (optionally batched) GEMM problem.  Batch index z = zb*nz_inner + zi
+// moves each pointer by zb*stride_*[0] + zi*stride_*[1] elements.
+struct GemmArgs {
+  int M, N, K;
+  const void* a; long lda; int a_kmajor;
+  const void* b; long ldb; int b_kmajor;
+  void* c; long ldc; int out_f32;
+  float alpha;
+  int epilogue;
+  const float* bias;
+  void* aux; long ldaux;   // EPI_BIAS_GELU: written; EPI_MUL_GELU_GRAD / EPI_ADD_RES: read
+  int gelu_tanh;
+  int batch;               // number of problems (>= 1)
+  int nz_inner;            // inner batch extent (>= 1)
+  long sa[2], sb[2], sc[2];
+};
+inline GemmArgs gemm_args_default() {
+  GemmArgs g{};
+  g.alpha = 1.0f;
+  g.batch = 1;
+  g.nz_inner = 1;
+  return g;
+}
+
+raf_status launch_gemm(int precision, const GemmArgs& g, hipStream_t st);
+
+raf_status launch_softmax_fwd(const raf_layer_desc& d, const void* s, const int32_t* lens, void* prob, void* prob_d,
+                              uint64_t step, hipStream_t st);
+raf_status launch_softmax_bwd(const raf_layer_desc& d, const void* prob, const void* prob_d, const void* dprob_d,
+                              void* ds, float scale_out, hipStream_t st);
+raf_status launch_ln_fwd(const raf_layer_desc& d, int site, int64_t rows, const void* a, const void* res,
+                         const float* gamma, const float* beta, void* out, void* z_out, float* mu, float* rstd,
+                         uint64_t step, hipStream_t st);
+size_t ln_bwd_partial_floats(int hidden, int64_t rows);
+raf_status launch_ln_bwd(const raf_layer_desc& d, int site, int64_t rows, const void* dout, const void* dout2,
+                         const void* z, const float* mu, const float* rstd, const float* gamma, const void* dres,
+                         void* dz, void* da, float* dgamma, float* dbeta, float* dbias, float* partial,
+                         uint64_t step, hipStream_t st);
+// out[j] = sum_i x[i*ld + j], x in compute dtype, rows x cols; partial scratch
+size_t colsum_partial_floats(int cols, int64_t rows);
+raf_status launch_colsum(int precision, const void* x, int64_t rows, int cols, long ld, float* out, float* partial,
+                         hipStream_t st);
+
+}  // namespace raf

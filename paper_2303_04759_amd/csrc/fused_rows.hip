@@ -1,0 +1,588 @@
+// Memory-bound fused row kernels of the training step (rule-based fusion of
+// elementwise + reduction operators, paper Section 3.2.2): masked softmax with
+// dropout and its adjoint, dropout + residual + LayerNorm and its adjoint,
+// column sums for bias gradients.  All arithmetic and statistics in fp32
+// (numerically sensitive operators stay in full precision, Section 3.1.2);
+// storage in the compute dtype with the casts fused into loads and stores.
+//
+// A row of L elements is owned by LPR lanes (a power of two <= 64) of one
+// wavefront, each holding NV vectors of 8 elements in registers:
+// vector index = lane_in_row + LPR * t, t < NV, valid while < L/8.
+#include "common.hpp"
+
+namespace raf {
+
+// ---------------------------------------------------------- row geometry --
+struct RowGeom {
+  int lpr, nv;
+};
+static RowGeom row_geom(int len) {
+  const int nvec = len / 8;
+  int lpr = 4;
+  while (lpr < 64 && lpr < nvec) lpr <<= 1;
+  int nv = 1;
+  while (lpr * nv < nvec) nv <<= 1;
+  return RowGeom{lpr, nv};
+}
+
+#define RAF_DISPATCH_GEOM(GEOM, CALL)                   \
+  do {                                                  \
+    const RowGeom _g = (GEOM);                          \
+    if (_g.lpr == 4) { CALL(4, 1); }                    \
+    else if (_g.lpr == 8) { CALL(8, 1); }               \
+    else if (_g.lpr == 16) { CALL(16, 1); }             \
+    else if (_g.lpr == 32) { CALL(32, 1); }             \
+    else if (_g.nv == 1) { CALL(64, 1); }               \
+    else if (_g.nv == 2) { CALL(64, 2); }               \
+    else if (_g.nv == 4) { CALL(64, 4); }               \
+    else { CALL(64, 8); }                               \
+  } while (0)
+
+// ---------------------------------------------------------- softmax fwd ---
+template <typename T, int LPR, int NV>
+__global__ __launch_bounds__(256) void softmax_fwd_kernel(const T* __restrict__ s, const int32_t* __restrict__ lens,
+                                                          T* __restrict__ prob, T* __restrict__ prob_d, long nrows,
+                                                          int S, int heads, int causal, DropSite drop) {
+  const int lane = threadIdx.x & (LPR - 1);
+  const long row = ((long)blockIdx.x * 256 + threadIdx.x) / LPR;
+  if (row >= nrows) return;   // whole LPR-group leaves together; shuffles below stay inside a group
+  const int nvec = S / 8;
+  const int i = (int)(row % S);
+  const int b = (int)(row / ((long)S * heads));
+  int limit = lens ? lens[b] : S;
+  limit = limit < 0 ? 0 : (limit > S ? S : limit);
+  if (causal) limit = limit < i + 1 ? limit : i + 1;
+
+  float v[NV][8];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int t = 0; t < NV; ++t) {
+    const int vec = lane + LPR * t;
+    if (vec < nvec) {
+      Vec8<T>::load(s + row * S + vec * 8, v[t]);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        if (vec * 8 + e >= limit) v[t][e] = -INFINITY;
+        mx = fmaxf(mx, v[t][e]);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[t][e] = -INFINITY;
+    }
+  }
+  mx = group_max<LPR>(mx);
+  const bool empty = (mx == -INFINITY);
+  float sum = 0.f;
+#pragma unroll
+  for (int t = 0; t < NV; ++t)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      v[t][e] = empty ? 0.f : expf(v[t][e] - mx);   // exp(-inf) == 0 exactly
+      sum += v[t][e];
+    }
+  sum = group_sum<LPR>(sum);
+  const float inv = empty ? 0.f : 1.0f / sum;
+#pragma unroll
+  for (int t = 0; t < NV; ++t) {
+    const int vec = lane + LPR * t;
+    if (vec < nvec) {
+      float p[8], pd[8], mult[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) p[e] = v[t][e] * inv;
+      if (drop.enabled) {
+        drop_mult8(drop, (uint64_t)row * S + vec * 8, mult);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pd[e] = p[e] * mult[e];
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pd[e] = p[e];
+      }
+      Vec8<T>::store(prob + row * S + vec * 8, p);
+      Vec8<T>::store(prob_d + row * S + vec * 8, pd);
+    }
+  }
+}
+
+// ---------------------------------------------------------- softmax bwd ---
+template <typename T, int LPR, int NV>
+__global__ __launch_bounds__(256) void softmax_bwd_kernel(const T* __restrict__ prob, const T* __restrict__ prob_d,
+                                                          const T* __restrict__ dprob_d, T* __restrict__ ds,
+                                                          long nrows, int S, float drop_scale, float scale_out) {
+  const int lane = threadIdx.x & (LPR - 1);
+  const long row = ((long)blockIdx.x * 256 + threadIdx.x) / LPR;
+  if (row >= nrows) return;
+  const int nvec = S / 8;
+  float p[NV][8], dp[NV][8];
+  float dot = 0.f;
+#pragma unroll
+  for (int t = 0; t < NV; ++t) {
+    const int vec = lane + LPR * t;
+    if (vec < nvec) {
+      float pd[8], g[8];
+      Vec8<T>::load(prob + row * S + vec * 8, p[t]);
+      Vec8<T>::load(prob_d + row * S + vec * 8, pd);
+      Vec8<T>::load(dprob_d + row * S + vec * 8, g);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        // an element was dropped iff its probability is non-zero but the
+        // post-dropout value is zero; for p == 0 the product below is 0 anyway
+        const bool keep = (pd[e] != 0.f) || (p[t][e] == 0.f);
+        dp[t][e] = keep ? g[e] * drop_scale : 0.f;
+        dot += dp[t][e] * p[t][e];
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) p[t][e] = dp[t][e] = 0.f;
+    }
+  }
+  dot = group_sum<LPR>(dot);
+#pragma unroll
+  for (int t = 0; t < NV; ++t) {
+    const int vec = lane + LPR * t;
+    if (vec < nvec) {
+      float o[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = scale_out * p[t][e] * (dp[t][e] - dot);
+      Vec8<T>::store(ds + row * S + vec * 8, o);
+    }
+  }
+}
+
+// -------------------------------------------- dropout + residual + LN fwd --
+template <typename T, int LPR, int NV>
+__global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ a, const T* __restrict__ res,
+                                                     const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                     T* __restrict__ out, T* __restrict__ z_out, float* __restrict__ mu,
+                                                     float* __restrict__ rstd, long nrows, int H, float eps,
+                                                     DropSite drop) {
+  const int lane = threadIdx.x & (LPR - 1);
+  const long row = ((long)blockIdx.x * 256 + threadIdx.x) / LPR;
+  if (row >= nrows) return;
+  const int nvec = H / 8;
+  float z[NV][8];
+  float sum = 0.f;
+#pragma unroll
+  for (int t = 0; t < NV; ++t) {
+    const int vec = lane + LPR * t;
+    if (vec < nvec) {
+      const long off = row * H + vec * 8;
+      Vec8<T>::load(res + off, z[t]);
+      if (a) {
+        float av[8];
+        Vec8<T>::load(a + off, av);
+        if (drop.enabled) {
+          float mult[8];
+          drop_mult8(drop, (uint64_t)off, mult);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) z[t][e] += av[e] * mult[e];
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) z[t][e] += av[e];
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        z[t][e] = Vec8<T>::round(z[t][e]);   // statistics of the value the backward pass reads back
+        sum += z[t][e];
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) z[t][e] = 0.f;
+    }
+  }
+  if (!gamma) {   // no normalisation: out = z
+#pragma unroll
+    for (int t = 0; t < NV; ++t) {
+      const int vec = lane + LPR * t;
+      if (vec < nvec) Vec8<T>::store(out + row * H + vec * 8, z[t]);
+    }
+    return;
+  }
+  const float mean = group_sum<LPR>(sum) / (float)H;
+  float sq = 0.f;
+#pragma unroll
+  for (int t = 0; t < NV; ++t) {
+    const int vec = lane + LPR * t;
+    if (vec < nvec) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float d = z[t][e] - mean;
+        sq += d * d;
+      }
+    }
+  }
+  const float var = group_sum<LPR>(sq) / (float)H;
+  const float rs = 1.0f / sqrtf(var + eps);
+#pragma unroll
+  for (int t = 0; t < NV; ++t) {
+    const int vec = lane + LPR * t;
+    if (vec < nvec) {
+      float gm[8], bt[8], o[8];
+      load8f(gamma + vec * 8, gm);
+      load8f(beta + vec * 8, bt);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = (z[t][e] - mean) * rs * gm[e] + bt[e];
+      Vec8<T>::store(out + row * H + vec * 8, o);
+      if (z_out) Vec8<T>::store(z_out + row * H + vec * 8, z[t]);
+    }
+  }
+  if (lane == 0) {
+    mu[row] = mean;
+    rstd[row] = rs;
+  }
+}
+
+// -------------------------------------------- dropout + residual + LN bwd --
+// Each LPR-lane group walks rows (group-strided) and keeps per-column partial
+// sums for dgamma, dbeta and dbias in registers; a block reduces them through
+// LDS and writes one partial row; a second kernel sums the partial rows in a
+// fixed order, so the result does not depend on scheduling.
+constexpr int LN_BWD_MAX_BLOCKS = 256;
+
+template <typename T, int LPR, int NV, bool HAS_LN>
+__global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dout, const T* __restrict__ dout2,
+                                                     const T* __restrict__ z, const float* __restrict__ mu,
+                                                     const float* __restrict__ rstd, const float* __restrict__ gamma,
+                                                     const T* __restrict__ dres, T* __restrict__ dz,
+                                                     T* __restrict__ da, float* __restrict__ partial, long nrows,
+                                                     int H, DropSite drop) {
+  extern __shared__ float red[];   // [3][H]
+  const int lane = threadIdx.x & (LPR - 1);
+  const int groups_per_block = 256 / LPR;
+  const long group = (long)blockIdx.x * groups_per_block + threadIdx.x / LPR;
+  const long ngroups = (long)gridDim.x * groups_per_block;
+  const int nvec = H / 8;
+
+  float cg[NV][8], cb[NV][8], cd[NV][8];
+  float gm[NV][8];
+#pragma unroll
+  for (int t = 0; t < NV; ++t) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) cg[t][e] = cb[t][e] = cd[t][e] = 0.f, gm[t][e] = 0.f;
+    const int vec = lane + LPR * t;
+    if (HAS_LN && vec < nvec) load8f(gamma + vec * 8, gm[t]);
+  }
+
+  for (long row = group; row < nrows; row += ngroups) {
+    float g[NV][8], xh[NV][8];
+    float s1 = 0.f, s2 = 0.f;
+    float mean = 0.f, rs = 0.f;
+    if (HAS_LN) {
+      mean = mu[row];
+      rs = rstd[row];
+    }
+#pragma unroll
+    for (int t = 0; t < NV; ++t) {
+      const int vec = lane + LPR * t;
+      if (vec < nvec) {
+        const long off = row * H + vec * 8;
+        Vec8<T>::load(dout + off, g[t]);
+        if (dout2) {
+          float g2[8];
+          Vec8<T>::load(dout2 + off, g2);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) g[t][e] += g2[e];
+        }
+        if (HAS_LN) {
+          float zv[8];
+          Vec8<T>::load(z + off, zv);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            xh[t][e] = (zv[e] - mean) * rs;
+            cg[t][e] += g[t][e] * xh[t][e];
+            cb[t][e] += g[t][e];
+            g[t][e] *= gm[t][e];           // dxhat
+            s1 += g[t][e];
+            s2 += g[t][e] * xh[t][e];
+          }
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) g[t][e] = xh[t][e] = 0.f;
+      }
+    }
+    if (HAS_LN) {
+      s1 = group_sum<LPR>(s1) / (float)H;
+      s2 = group_sum<LPR>(s2) / (float)H;
+    }
+#pragma unroll
+    for (int t = 0; t < NV; ++t) {
+      const int vec = lane + LPR * t;
+      if (vec < nvec) {
+        const long off = row * H + vec * 8;
+        float o[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = HAS_LN ? rs * (g[t][e] - s1 - xh[t][e] * s2) : g[t][e];
+        if (dres) {
+          float r[8];
+          Vec8<T>::load(dres + off, r);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[e] += r[e];
+        }
+        if (dz) Vec8<T>::store(dz + off, o);
+        if (da) {
+          if (drop.enabled) {
+            float mult[8];
+            drop_mult8(drop, (uint64_t)off, mult);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] *= mult[e];
+          }
+          Vec8<T>::store(da + off, o);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) cd[t][e] += o[e];
+        }
+      }
+    }
+  }
+
+  // lanes of different groups inside a wave that own the same columns
+#pragma unroll
+  for (int t = 0; t < NV; ++t)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+#pragma unroll
+      for (int o = LPR; o < WAVE; o <<= 1) {
+        cg[t][e] += __shfl_xor(cg[t][e], o, WAVE);
+        cb[t][e] += __shfl_xor(cb[t][e], o, WAVE);
+        cd[t][e] += __shfl_xor(cd[t][e], o, WAVE);
+      }
+    }
+  // the four waves add their sums into LDS one after the other (fixed order)
+  const int wave = threadIdx.x >> 6;
+  const int wlane = threadIdx.x & 63;
+  for (int w = 0; w < 4; ++w) {
+    if (wave == w && wlane < LPR) {
+#pragma unroll
+      for (int t = 0; t < NV; ++t) {
+        const int vec = lane + LPR * t;
+        if (vec < nvec) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const int c = vec * 8 + e;
+            if (w == 0) {
+              red[c] = cg[t][e];
+              red[H + c] = cb[t][e];
+              red[2 * H + c] = cd[t][e];
+            } else {
+              red[c] += cg[t][e];
+              red[H + c] += cb[t][e];
+              red[2 * H + c] += cd[t][e];
+            }
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+  for (int c = threadIdx.x; c < 3 * H; c += 256) partial[(long)blockIdx.x * 3 * H + c] = red[c];
+}
+
+// out_k[c] = sum_p partial[p][k][c], p ascending; k < nout
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int nparts, int ncols,
+                                                              int nout, float* o0, float* o1, float* o2) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= ncols * nout) return;
+  float acc = 0.f;
+  for (int p = 0; p < nparts; ++p) acc += partial[(long)p * nout * ncols + c];
+  const int k = c / ncols, cc = c % ncols;
+  float* o = k == 0 ? o0 : (k == 1 ? o1 : o2);
+  if (o) o[cc] = acc;
+}
+
+// ------------------------------------------------------------ column sum --
+constexpr int COLSUM_MAX_PARTS = 64;
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ x, long rows, int cols, long ld,
+                                                     float* __restrict__ partial) {
+  __shared__ float red[4][64 * 8];
+  const int cv = blockIdx.x * 64 + (threadIdx.x & 63);
+  const int rl = threadIdx.x >> 6;
+  float acc[8] = {};
+  if (cv * 8 < cols) {
+    for (long r = (long)blockIdx.y * 4 + rl; r < rows; r += (long)gridDim.y * 4) {
+      float v[8];
+      Vec8<T>::load(x + r * ld + cv * 8, v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] += v[e];
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) red[rl][(threadIdx.x & 63) * 8 + e] = acc[e];
+  __syncthreads();
+  for (int c = threadIdx.x; c < 64 * 8; c += 256) {
+    const int col = blockIdx.x * 512 + c;
+    if (col < cols) partial[(long)blockIdx.y * cols + col] = red[0][c] + red[1][c] + red[2][c] + red[3][c];
+  }
+}
+
+// ---------------------------------------------------------------- launch --
+static bool row_shape_ok(long len) { return len >= 32 && len % 8 == 0 && len <= 4096; }
+
+raf_status launch_softmax_fwd(const raf_layer_desc& d, const void* s, const int32_t* lens, void* prob, void* prob_d,
+                              uint64_t step, hipStream_t st) {
+  if (!s || !prob || !prob_d) return RAF_EINVAL;
+  if (!aligned16(s) || !aligned16(prob) || !aligned16(prob_d)) return RAF_EINVAL;
+  if (!row_shape_ok(d.seq)) return RAF_ENOTSUP;
+  const long nrows = (long)d.batch * d.heads * d.seq;
+  if ((uint64_t)nrows * d.seq / 4 > 0xffffffffull) return RAF_ENOTSUP;
+  const DropSite drop = make_drop_site(d, 1, step);
+#define CALL(LPR, NV)                                                                                          \
+  {                                                                                                            \
+    const long nblk = (nrows * LPR + 255) / 256;                                                               \
+    if (d.precision == RAF_F32)                                                                                \
+      hipLaunchKernelGGL((softmax_fwd_kernel<float, LPR, NV>), dim3(nblk), dim3(256), 0, st, (const float*)s, \
+                         lens, (float*)prob, (float*)prob_d, nrows, d.seq, d.heads, d.causal, drop);           \
+    else                                                                                                       \
+      hipLaunchKernelGGL((softmax_fwd_kernel<bf16_t, LPR, NV>), dim3(nblk), dim3(256), 0, st,                 \
+                         (const bf16_t*)s, lens, (bf16_t*)prob, (bf16_t*)prob_d, nrows, d.seq, d.heads,        \
+                         d.causal, drop);                                                                      \
+  }
+  RAF_DISPATCH_GEOM(row_geom(d.seq), CALL);
+#undef CALL
+  return check_launch();
+}
+
+raf_status launch_softmax_bwd(const raf_layer_desc& d, const void* prob, const void* prob_d, const void* dprob_d,
+                              void* ds, float scale_out, hipStream_t st) {
+  if (!prob || !prob_d || !dprob_d || !ds) return RAF_EINVAL;
+  if (!aligned16(prob) || !aligned16(prob_d) || !aligned16(dprob_d) || !aligned16(ds)) return RAF_EINVAL;
+  if (!row_shape_ok(d.seq)) return RAF_ENOTSUP;
+  const long nrows = (long)d.batch * d.heads * d.seq;
+  const float drop_scale = (float)(1.0 / (1.0 - d.dropout_p));
+#define CALL(LPR, NV)                                                                                             \
+  {                                                                                                               \
+    const long nblk = (nrows * LPR + 255) / 256;                                                                  \
+    if (d.precision == RAF_F32)                                                                                   \
+      hipLaunchKernelGGL((softmax_bwd_kernel<float, LPR, NV>), dim3(nblk), dim3(256), 0, st, (const float*)prob, \
+                         (const float*)prob_d, (const float*)dprob_d, (float*)ds, nrows, d.seq, drop_scale,       \
+                         scale_out);                                                                              \
+    else                                                                                                          \
+      hipLaunchKernelGGL((softmax_bwd_kernel<bf16_t, LPR, NV>), dim3(nblk), dim3(256), 0, st,                    \
+                         (const bf16_t*)prob, (const bf16_t*)prob_d, (const bf16_t*)dprob_d, (bf16_t*)ds, nrows,  \
+                         d.seq, drop_scale, scale_out);                                                           \
+  }
+  RAF_DISPATCH_GEOM(row_geom(d.seq), CALL);
+#undef CALL
+  return check_launch();
+}
+
+raf_status launch_ln_fwd(const raf_layer_desc& d, int site, int64_t rows, const void* a, const void* res,
+                         const float* gamma, const float* beta, void* out, void* z_out, float* mu, float* rstd,
+                         uint64_t step, hipStream_t st) {
+  if (!res || !out || rows <= 0) return RAF_EINVAL;
+  if (gamma && (!beta || !mu || !rstd)) return RAF_EINVAL;
+  if (a && site != 2 && site != 3) return RAF_EINVAL;
+  if (!aligned16(a) || !aligned16(res) || !aligned16(out) || !aligned16(z_out) || !aligned16(gamma) ||
+      !aligned16(beta))
+    return RAF_EINVAL;
+  if (!row_shape_ok(d.hidden)) return RAF_ENOTSUP;
+  if ((uint64_t)rows * d.hidden / 4 > 0xffffffffull) return RAF_ENOTSUP;
+  const DropSite drop = make_drop_site(d, a ? site : 0, step);
+  const int H = d.hidden;
+#define CALL(LPR, NV)                                                                                              \
+  {                                                                                                                \
+    const long nblk = ((long)rows * LPR + 255) / 256;                                                              \
+    if (d.precision == RAF_F32)                                                                                    \
+      hipLaunchKernelGGL((ln_fwd_kernel<float, LPR, NV>), dim3(nblk), dim3(256), 0, st, (const float*)a,          \
+                         (const float*)res, gamma, beta, (float*)out, (float*)z_out, mu, rstd, (long)rows, H,      \
+                         d.ln_eps, drop);                                                                          \
+    else                                                                                                           \
+      hipLaunchKernelGGL((ln_fwd_kernel<bf16_t, LPR, NV>), dim3(nblk), dim3(256), 0, st, (const bf16_t*)a,        \
+                         (const bf16_t*)res, gamma, beta, (bf16_t*)out, (bf16_t*)z_out, mu, rstd, (long)rows, H,   \
+                         d.ln_eps, drop);                                                                          \
+  }
+  RAF_DISPATCH_GEOM(row_geom(H), CALL);
+#undef CALL
+  return check_launch();
+}
+
+static int ln_bwd_blocks(int hidden, int64_t rows) {
+  const RowGeom g = row_geom(hidden);
+  const long groups_per_block = 256 / g.lpr;
+  long nb = (rows + groups_per_block * 4 - 1) / (groups_per_block * 4);   // >= 4 rows per group
+  if (nb < 1) nb = 1;
+  if (nb > LN_BWD_MAX_BLOCKS) nb = LN_BWD_MAX_BLOCKS;
+  return (int)nb;
+}
+
+size_t ln_bwd_partial_floats(int hidden, int64_t rows) {
+  if (hidden <= 0 || rows <= 0) return 0;
+  return (size_t)ln_bwd_blocks(hidden, rows) * 3 * (size_t)hidden;
+}
+
+raf_status launch_ln_bwd(const raf_layer_desc& d, int site, int64_t rows, const void* dout, const void* dout2,
+                         const void* z, const float* mu, const float* rstd, const float* gamma, const void* dres,
+                         void* dz, void* da, float* dgamma, float* dbeta, float* dbias, float* partial,
+                         uint64_t step, hipStream_t st) {
+  if (!dout || !partial || rows <= 0) return RAF_EINVAL;
+  if (gamma && (!z || !mu || !rstd || !dgamma || !dbeta)) return RAF_EINVAL;
+  if (!dz && !da) return RAF_EINVAL;
+  if (da && !dbias) return RAF_EINVAL;
+  if (site != 0 && site != 2 && site != 3) return RAF_EINVAL;
+  if (!aligned16(dout) || !aligned16(dout2) || !aligned16(z) || !aligned16(gamma) || !aligned16(dres) ||
+      !aligned16(dz) || !aligned16(da))
+    return RAF_EINVAL;
+  if (!row_shape_ok(d.hidden)) return RAF_ENOTSUP;
+  if ((uint64_t)rows * d.hidden / 4 > 0xffffffffull) return RAF_ENOTSUP;
+  const DropSite drop = make_drop_site(d, site, step);
+  const int H = d.hidden;
+  const int nb = ln_bwd_blocks(H, rows);
+  const size_t shm = (size_t)3 * H * sizeof(float);
+#define CALL(LPR, NV)                                                                                               \
+  {                                                                                                                 \
+    if (d.precision == RAF_F32) {                                                                                   \
+      if (gamma)                                                                                                    \
+        hipLaunchKernelGGL((ln_bwd_kernel<float, LPR, NV, true>), dim3(nb), dim3(256), shm, st, (const float*)dout, \
+                           (const float*)dout2, (const float*)z, mu, rstd, gamma, (const float*)dres, (float*)dz,   \
+                           (float*)da, partial, (long)rows, H, drop);                                               \
+      else                                                                                                          \
+        hipLaunchKernelGGL((ln_bwd_kernel<float, LPR, NV, false>), dim3(nb), dim3(256), shm, st,                    \
+                           (const float*)dout, (const float*)dout2, (const float*)z, mu, rstd, gamma,               \
+                           (const float*)dres, (float*)dz, (float*)da, partial, (long)rows, H, drop);               \
+    } else {                                                                                                        \
+      if (gamma)                                                                                                    \
+        hipLaunchKernelGGL((ln_bwd_kernel<bf16_t, LPR, NV, true>), dim3(nb), dim3(256), shm, st,                    \
+                           (const bf16_t*)dout, (const bf16_t*)dout2, (const bf16_t*)z, mu, rstd, gamma,            \
+                           (const bf16_t*)dres, (bf16_t*)dz, (bf16_t*)da, partial, (long)rows, H, drop);            \
+      else                                                                                                          \
+        hipLaunchKernelGGL((ln_bwd_kernel<bf16_t, LPR, NV, false>), dim3(nb), dim3(256), shm, st,                   \
+                           (const bf16_t*)dout, (const bf16_t*)dout2, (const bf16_t*)z, mu, rstd, gamma,            \
+                           (const bf16_t*)dres, (bf16_t*)dz, (bf16_t*)da, partial, (long)rows, H, drop);            \
+    }                                                                                                               \
+  }
+  RAF_DISPATCH_GEOM(row_geom(H), CALL);
+#undef CALL
+  raf_status rc = check_launch();
+  if (rc != RAF_OK) return rc;
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((3 * H + 255) / 256), dim3(256), 0, st, partial, nb, H, 3,
+                     gamma ? dgamma : nullptr, gamma ? dbeta : nullptr, da ? dbias : nullptr);
+  return check_launch();
+}
+
+static int colsum_parts(int64_t rows) {
+  long p = (rows + 63) / 64;
+  if (p < 1) p = 1;
+  if (p > COLSUM_MAX_PARTS) p = COLSUM_MAX_PARTS;
+  return (int)p;
+}
+size_t colsum_partial_floats(int cols, int64_t rows) { return (size_t)colsum_parts(rows) * (size_t)cols; }
+
+raf_status launch_colsum(int precision, const void* x, int64_t rows, int cols, long ld, float* out, float* partial,
+                         hipStream_t st) {
+  if (!x || !out || !partial || rows <= 0 || cols <= 0) return RAF_EINVAL;
+  if ((cols % 8) || (ld % 8) || !aligned16(x)) return RAF_EINVAL;
+  const int parts = colsum_parts(rows);
+  dim3 grid((cols + 511) / 512, parts);
+  if (precision == RAF_F32)
+    hipLaunchKernelGGL((colsum_kernel<float>), grid, dim3(256), 0, st, (const float*)x, (long)rows, cols, ld, partial);
+  else
+    hipLaunchKernelGGL((colsum_kernel<bf16_t>), grid, dim3(256), 0, st, (const bf16_t*)x, (long)rows, cols, ld,
+                       partial);
+  raf_status rc = check_launch();
+  if (rc != RAF_OK) return rc;
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((cols + 255) / 256), dim3(256), 0, st, partial, parts, cols, 1, out,
+                     nullptr, nullptr);
+  return check_launch();
+}
+
+}  // namespace raf

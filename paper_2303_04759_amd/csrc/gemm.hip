@@ -1,0 +1,294 @@
+// Dense contractions of the training step: bf16 MFMA GEMM (gfx950
+// v_mfma_f32_32x32x16_bf16, fp32 accumulate) and an fp32 FMA GEMM for the
+// full-precision mode, both with the fused epilogues the step needs
+// (bias, bias+GeLU with saved pre-activation, GeLU-gradient multiply, residual
+// add, scale, fp32 output).  Pattern-based "GEMM + elementwise epilogue"
+// fusion in the sense of the paper's Section 3.2.2.
+#include "common.hpp"
+
+namespace raf {
+
+struct GemmDev {
+  int M, N, K;
+  const void* a; long lda;
+  const void* b; long ldb;
+  void* c; long ldc;
+  float alpha;
+  int epilogue;
+  const float* bias;
+  void* aux; long ldaux;
+  int gelu_tanh;
+  int nz_inner;
+  long sa0, sa1, sb0, sb1, sc0, sc1;
+};
+
+template <typename TC, typename TAUX>
+__device__ __forceinline__ void epilogue_store(const GemmDev& g, TC* __restrict__ c, TAUX* __restrict__ aux, int i,
+                                               int j, float acc) {
+  float v = acc * g.alpha;
+  switch (g.epilogue) {
+    case EPI_BIAS:
+      v += g.bias[j];
+      break;
+    case EPI_BIAS_GELU: {
+      v += g.bias[j];
+      aux[(long)i * g.ldaux + j] = (TAUX)v;
+      // GeLU is evaluated on the value the backward pass will read back
+      v = gelu_f((float)(TAUX)v, g.gelu_tanh);
+      break;
+    }
+    case EPI_MUL_GELU_GRAD:
+      v *= gelu_grad_f((float)aux[(long)i * g.ldaux + j], g.gelu_tanh);
+      break;
+    case EPI_ADD_RES:
+      v += (float)aux[(long)i * g.ldaux + j];
+      break;
+    default:
+      break;
+  }
+  c[(long)i * g.ldc + j] = (TC)v;
+}
+
+// ------------------------------------------------------------- bf16 MFMA --
+constexpr int BK = 64;          // k extent of one LDS stage
+constexpr int KPAD = 8;         // bf16 elements of row padding (16 B)
+
+// Operand tile in LDS.  K-major operands are kept [row][BK+KPAD]; operands
+// whose rows are contiguous in memory (MN-major) are kept [k][ROWS+KPAD].
+template <int ROWS, bool KMAJOR>
+struct TileLds {
+  static constexpr int PITCH = KMAJOR ? (BK + KPAD) : (ROWS + KPAD);
+  static constexpr int ELEMS = KMAJOR ? ROWS * PITCH : BK * PITCH;
+  static constexpr int VEC_PER_THREAD = ROWS * BK / 8 / 256;
+};
+
+template <int ROWS, bool KMAJOR>
+__device__ __forceinline__ void tile_load_global(const bf16_t* __restrict__ base, long ld, int row0, int nrows, int k0,
+                                                 int K, uint4 (&reg)[TileLds<ROWS, KMAJOR>::VEC_PER_THREAD]) {
+  constexpr int NV = TileLds<ROWS, KMAJOR>::VEC_PER_THREAD;
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int t = 0; t < NV; ++t) {
+    const int v = tid + t * 256;
+    if (KMAJOR) {
+      int r = row0 + v / (BK / 8);
+      r = r < nrows ? r : nrows - 1;
+      const int k = k0 + (v % (BK / 8)) * 8;
+      reg[t] = k < K ? *reinterpret_cast<const uint4*>(base + (long)r * ld + k) : make_uint4(0, 0, 0, 0);
+    } else {
+      const int kr = v / (ROWS / 8);
+      int r = row0 + (v % (ROWS / 8)) * 8;
+      r = r < nrows ? r : nrows - 8;
+      reg[t] = k0 + kr < K ? *reinterpret_cast<const uint4*>(base + (long)(k0 + kr) * ld + r) : make_uint4(0, 0, 0, 0);
+    }
+  }
+}
+
+template <int ROWS, bool KMAJOR>
+__device__ __forceinline__ void tile_store_lds(bf16_t* lds, const uint4 (&reg)[TileLds<ROWS, KMAJOR>::VEC_PER_THREAD]) {
+  constexpr int NV = TileLds<ROWS, KMAJOR>::VEC_PER_THREAD;
+  constexpr int PITCH = TileLds<ROWS, KMAJOR>::PITCH;
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int t = 0; t < NV; ++t) {
+    const int v = tid + t * 256;
+    if (KMAJOR) {
+      *reinterpret_cast<uint4*>(lds + (v / (BK / 8)) * PITCH + (v % (BK / 8)) * 8) = reg[t];
+    } else {
+      *reinterpret_cast<uint4*>(lds + (v / (ROWS / 8)) * PITCH + (v % (ROWS / 8)) * 8) = reg[t];
+    }
+  }
+}
+
+// MFMA operand fragment for 32 rows starting at `row` and the 16 k values of
+// sub-step kk: lane l supplies row (l & 31), k = kk*16 + (l >> 5)*8 + 0..7.
+template <int ROWS, bool KMAJOR>
+__device__ __forceinline__ bf16x8_t tile_fragment(const bf16_t* lds, int row, int kk) {
+  constexpr int PITCH = TileLds<ROWS, KMAJOR>::PITCH;
+  const int lane = threadIdx.x & 63;
+  const int r = row + (lane & 31);
+  const int k = kk * 16 + (lane >> 5) * 8;
+  if (KMAJOR) {
+    return *reinterpret_cast<const bf16x8_t*>(lds + r * PITCH + k);
+  } else {
+    bf16x8_t f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) f[e] = lds[(k + e) * PITCH + r];
+    return f;
+  }
+}
+
+template <int BM, int BN, bool A_KMAJOR, bool B_KMAJOR, typename TC>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmDev g) {
+  constexpr int WM = BM / 2, WN = BN / 2;   // 2 x 2 waves
+  constexpr int TM = WM / 32, TN = WN / 32;
+  typedef TileLds<BM, A_KMAJOR> LA;
+  typedef TileLds<BN, B_KMAJOR> LB;
+  __shared__ __attribute__((aligned(16))) bf16_t lds_a[LA::ELEMS];
+  __shared__ __attribute__((aligned(16))) bf16_t lds_b[LB::ELEMS];
+
+  const int z = blockIdx.z;
+  const int zb = z / g.nz_inner, zi = z % g.nz_inner;
+  const bf16_t* __restrict__ A = (const bf16_t*)g.a + zb * g.sa0 + zi * g.sa1;
+  const bf16_t* __restrict__ B = (const bf16_t*)g.b + zb * g.sb0 + zi * g.sb1;
+  TC* __restrict__ C = (TC*)g.c + zb * g.sc0 + zi * g.sc1;
+  bf16_t* __restrict__ AUX = g.aux ? (bf16_t*)g.aux + zb * g.sc0 + zi * g.sc1 : nullptr;
+
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wm = (wave >> 1) * WM, wn = (wave & 1) * WN;
+
+  f32x16_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  uint4 ra[LA::VEC_PER_THREAD], rb[LB::VEC_PER_THREAD];
+  tile_load_global<BM, A_KMAJOR>(A, g.lda, m0, g.M, 0, g.K, ra);
+  tile_load_global<BN, B_KMAJOR>(B, g.ldb, n0, g.N, 0, g.K, rb);
+
+  for (int k0 = 0; k0 < g.K; k0 += BK) {
+    __syncthreads();   // previous stage fully consumed
+    tile_store_lds<BM, A_KMAJOR>(lds_a, ra);
+    tile_store_lds<BN, B_KMAJOR>(lds_b, rb);
+    __syncthreads();
+    if (k0 + BK < g.K) {
+      tile_load_global<BM, A_KMAJOR>(A, g.lda, m0, g.M, k0 + BK, g.K, ra);
+      tile_load_global<BN, B_KMAJOR>(B, g.ldb, n0, g.N, k0 + BK, g.K, rb);
+    }
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      bf16x8_t fa[TM], fb[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) fa[i] = tile_fragment<BM, A_KMAJOR>(lds_a, wm + i * 32, kk);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) fb[j] = tile_fragment<BN, B_KMAJOR>(lds_b, wn + j * 32, kk);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+  }
+
+  // accumulator layout of the 32x32 MFMA: register r of lane l holds
+  // row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int col = n0 + wn + j * 32 + (lane & 31);
+      if (col < g.N) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = m0 + wm + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          if (row < g.M) epilogue_store<TC, bf16_t>(g, C, AUX, row, col, acc[i][j][r]);
+        }
+      }
+    }
+}
+
+// -------------------------------------------------------------- fp32 FMA --
+// Plain LDS-tiled FMA kernel for the full-precision mode (small validation
+// shapes): 64x64 tile, 16x16 threads, 4x4 outputs each, any strides.
+__global__ __launch_bounds__(256) void gemm_f32_kernel(GemmDev g, long sa_i, long sa_k, long sb_k, long sb_j) {
+  constexpr int T = 64, KT = 16;
+  __shared__ float As[KT][T + 1];
+  __shared__ float Bs[KT][T + 1];
+  const int z = blockIdx.z;
+  const int zb = z / g.nz_inner, zi = z % g.nz_inner;
+  const float* __restrict__ A = (const float*)g.a + zb * g.sa0 + zi * g.sa1;
+  const float* __restrict__ B = (const float*)g.b + zb * g.sb0 + zi * g.sb1;
+  float* __restrict__ C = (float*)g.c + zb * g.sc0 + zi * g.sc1;
+  float* __restrict__ AUX = g.aux ? (float*)g.aux + zb * g.sc0 + zi * g.sc1 : nullptr;
+  const int m0 = blockIdx.y * T, n0 = blockIdx.x * T;
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  float acc[4][4] = {};
+  for (int k0 = 0; k0 < g.K; k0 += KT) {
+    for (int e = threadIdx.x; e < T * KT; e += 256) {
+      const int r = e / KT, k = e % KT;     // k fastest: good for k-major operands
+      const int i = m0 + r, j = n0 + r, kk = k0 + k;
+      As[k][r] = (i < g.M && kk < g.K) ? A[i * sa_i + kk * sa_k] : 0.f;
+      Bs[k][r] = (j < g.N && kk < g.K) ? B[kk * sb_k + j * sb_j] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < KT; ++k) {
+      float a[4], b[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        a[u] = As[k][ty * 4 + u];
+        b[u] = Bs[k][tx * 4 + u];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int w = 0; w < 4; ++w) acc[u][w] = fmaf(a[u], b[w], acc[u][w]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const int i = m0 + ty * 4 + u, j = n0 + tx * 4 + w;
+      if (i < g.M && j < g.N) epilogue_store<float, float>(g, C, AUX, i, j, acc[u][w]);
+    }
+}
+
+// ---------------------------------------------------------------- launch --
+template <int BM, int BN, bool AK, bool BKM>
+static void launch_bf16_tile(const GemmDev& d, int out_f32, int batch, hipStream_t st) {
+  dim3 grid((d.N + BN - 1) / BN, (d.M + BM - 1) / BM, batch);
+  if (out_f32)
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, AK, BKM, float>), grid, dim3(256), 0, st, d);
+  else
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, AK, BKM, bf16_t>), grid, dim3(256), 0, st, d);
+}
+
+template <bool AK, bool BKM>
+static void launch_bf16_layout(const GemmDev& d, int out_f32, int batch, hipStream_t st) {
+  if (d.M <= 64 && d.N <= 64)
+    launch_bf16_tile<64, 64, AK, BKM>(d, out_f32, batch, st);
+  else if (d.N <= 64)
+    launch_bf16_tile<128, 64, AK, BKM>(d, out_f32, batch, st);
+  else
+    launch_bf16_tile<128, 128, AK, BKM>(d, out_f32, batch, st);
+}
+
+raf_status launch_gemm(int precision, const GemmArgs& g, hipStream_t st) {
+  if (g.M <= 0 || g.N <= 0 || g.K <= 0 || g.batch <= 0 || g.nz_inner <= 0) return RAF_EINVAL;
+  if ((g.M % 32) || (g.N % 32) || (g.K % 32)) return RAF_ENOTSUP;
+  if (!g.a || !g.b || !g.c) return RAF_EINVAL;
+  if (!aligned16(g.a) || !aligned16(g.b) || !aligned16(g.c)) return RAF_EINVAL;
+  if ((g.epilogue == EPI_BIAS || g.epilogue == EPI_BIAS_GELU) && !g.bias) return RAF_EINVAL;
+  if (g.epilogue >= EPI_BIAS_GELU && !g.aux) return RAF_EINVAL;
+  if (g.epilogue < 0 || g.epilogue > EPI_ADD_RES) return RAF_EINVAL;
+  if ((g.lda % 8) || (g.ldb % 8) || (g.ldc % 8) || (g.aux && (g.ldaux % 8))) return RAF_EINVAL;
+  if (g.batch > 65535) return RAF_ENOTSUP;
+  GemmDev d;
+  d.M = g.M; d.N = g.N; d.K = g.K;
+  d.a = g.a; d.lda = g.lda; d.b = g.b; d.ldb = g.ldb; d.c = g.c; d.ldc = g.ldc;
+  d.alpha = g.alpha; d.epilogue = g.epilogue; d.bias = g.bias; d.aux = g.aux; d.ldaux = g.ldaux;
+  d.gelu_tanh = g.gelu_tanh; d.nz_inner = g.nz_inner;
+  d.sa0 = g.sa[0]; d.sa1 = g.sa[1]; d.sb0 = g.sb[0]; d.sb1 = g.sb[1]; d.sc0 = g.sc[0]; d.sc1 = g.sc[1];
+  if (precision == RAF_F32) {
+    dim3 grid((g.N + 63) / 64, (g.M + 63) / 64, g.batch);
+    const long sa_i = g.a_kmajor ? g.lda : 1, sa_k = g.a_kmajor ? 1 : g.lda;
+    const long sb_k = g.b_kmajor ? 1 : g.ldb, sb_j = g.b_kmajor ? g.ldb : 1;
+    hipLaunchKernelGGL(gemm_f32_kernel, grid, dim3(256), 0, st, d, sa_i, sa_k, sb_k, sb_j);
+  } else if (precision == RAF_BF16_AMP) {
+    if (g.a_kmajor && g.b_kmajor) launch_bf16_layout<true, true>(d, g.out_f32, g.batch, st);
+    else if (g.a_kmajor && !g.b_kmajor) launch_bf16_layout<true, false>(d, g.out_f32, g.batch, st);
+    else if (!g.a_kmajor && !g.b_kmajor) launch_bf16_layout<false, false>(d, g.out_f32, g.batch, st);
+    else launch_bf16_layout<false, true>(d, g.out_f32, g.batch, st);
+  } else {
+    return RAF_EINVAL;
+  }
+  return check_launch();
+}
+
+}  // namespace raf

@@ -1,0 +1,402 @@
+// The training step of one transformer layer as a fixed kernel schedule:
+// forward graph and the reverse chain of adjoints (paper Sections 2.1, 3.1.1),
+// with the fused operators of Section 3.2.2.  Host code only: it validates
+// the descriptor, lays out the saved/scratch buffers and enqueues kernels on
+// the caller's stream; it never allocates or synchronises.
+#include <mutex>
+#include <string>
+
+#include "common.hpp"
+
+namespace raf {
+
+static std::mutex g_err_mutex;
+static std::string g_err = "";
+void set_hip_error(hipError_t e) {
+  std::lock_guard<std::mutex> lk(g_err_mutex);
+  g_err = hipGetErrorString(e);
+}
+
+static raf_status validate_desc(const raf_layer_desc* d) {
+  if (!d) return RAF_EINVAL;
+  if (d->batch <= 0 || d->seq <= 0 || d->hidden <= 0 || d->heads <= 0 || d->ffn <= 0) return RAF_EINVAL;
+  if (d->precision != RAF_F32 && d->precision != RAF_BF16_AMP) return RAF_EINVAL;
+  if ((d->pre_ln | 1) != 1 || (d->causal | 1) != 1 || (d->gelu_tanh | 1) != 1) return RAF_EINVAL;
+  if (!(d->dropout_p >= 0.0 && d->dropout_p < 1.0)) return RAF_EINVAL;
+  if (!(d->ln_eps >= 0.f)) return RAF_EINVAL;
+  if (d->reserved != 0) return RAF_EINVAL;
+  if (d->hidden % d->heads) return RAF_ENOTSUP;
+  if (d->hidden / d->heads != 64) return RAF_ENOTSUP;
+  if ((d->seq % 32) || (d->hidden % 32) || (d->ffn % 32)) return RAF_ENOTSUP;
+  if (d->seq > 4096 || d->hidden > 4096 || d->ffn > 65536) return RAF_ENOTSUP;
+  const long T = (long)d->batch * d->seq;
+  if (T > (1l << 24) || (long)d->batch * d->heads > 65535) return RAF_ENOTSUP;
+  // 32-bit Philox block counters per site
+  if ((unsigned long)d->batch * d->heads * d->seq * d->seq / 4 > 0xfffffffful) return RAF_ENOTSUP;
+  return RAF_OK;
+}
+
+// Byte offsets into the two caller-provided buffers.
+struct Plan {
+  size_t e;   // element size of the compute dtype
+  long T, H, F, S, NH, B, PS;   // PS = B*heads*S*S
+  // saved
+  size_t qkv, prob, prob_d, c, z1, ffn_in, u, g, z2, n1, mu1, rstd1, mu2, rstd2, saved_bytes;
+  // scratch, forward
+  size_t s, a;
+  // scratch, backward
+  size_t dz2, da, du, dffn, dz1, dc, dprob_d, ds, dqkv, dattn, partial;
+  size_t scratch_bytes;
+};
+
+static size_t bump(size_t& off, size_t bytes) {
+  const size_t at = off;
+  off += (bytes + 255) & ~(size_t)255;
+  return at;
+}
+
+static Plan make_plan(const raf_layer_desc& d) {
+  Plan p{};
+  p.e = d.precision == RAF_F32 ? 4 : 2;
+  p.B = d.batch; p.S = d.seq; p.H = d.hidden; p.F = d.ffn; p.NH = d.heads;
+  p.T = p.B * p.S;
+  p.PS = p.B * p.NH * p.S * p.S;
+  const size_t TH = (size_t)p.T * p.H * p.e, TF = (size_t)p.T * p.F * p.e, PSb = (size_t)p.PS * p.e;
+  size_t o = 0;
+  p.qkv = bump(o, 3 * TH);
+  p.prob = bump(o, PSb);
+  p.prob_d = bump(o, PSb);
+  p.c = bump(o, TH);
+  p.z1 = bump(o, TH);
+  p.ffn_in = bump(o, TH);
+  p.u = bump(o, TF);
+  p.g = bump(o, TF);
+  p.z2 = bump(o, TH);
+  p.n1 = bump(o, TH);
+  p.mu1 = bump(o, p.T * 4);
+  p.rstd1 = bump(o, p.T * 4);
+  p.mu2 = bump(o, p.T * 4);
+  p.rstd2 = bump(o, p.T * 4);
+  p.saved_bytes = o;
+  size_t f = 0;
+  p.s = bump(f, PSb);
+  p.a = bump(f, TH);
+  size_t b = 0;
+  p.dz2 = bump(b, TH);
+  p.da = bump(b, TH);
+  p.du = bump(b, TF);
+  p.dffn = bump(b, TH);
+  p.dz1 = bump(b, TH);
+  p.dc = bump(b, TH);
+  p.dprob_d = bump(b, PSb);
+  p.ds = bump(b, PSb);
+  p.dqkv = bump(b, 3 * TH);
+  p.dattn = bump(b, TH);
+  size_t pf = ln_bwd_partial_floats((int)p.H, p.T);
+  const size_t c1 = colsum_partial_floats((int)(3 * p.H), p.T), c2 = colsum_partial_floats((int)p.F, p.T);
+  if (c1 > pf) pf = c1;
+  if (c2 > pf) pf = c2;
+  p.partial = bump(b, pf * 4);
+  p.scratch_bytes = f > b ? f : b;
+  return p;
+}
+
+static inline char* at(void* base, size_t off) { return (char*)base + off; }
+static inline const char* at(const void* base, size_t off) { return (const char*)base + off; }
+
+static bool tensors_ok(const raf_layer_tensors* t) {
+  if (!t) return false;
+  const void* const* p = (const void* const*)t;
+  for (int i = 0; i < 12; ++i)
+    if (!p[i] || !aligned16(p[i])) return false;
+  return true;
+}
+
+#define RAF_TRY(expr)                \
+  do {                               \
+    raf_status _rc = (expr);         \
+    if (_rc != RAF_OK) return _rc;   \
+  } while (0)
+
+// plain (un-batched) GEMM helper: C[M,N] = A.B, see GemmArgs
+static raf_status gemm(int prec, hipStream_t st, int M, int N, int K, const void* a, long lda, int ak, const void* b,
+                       long ldb, int bk, void* c, long ldc, int out_f32 = 0, int epi = EPI_NONE,
+                       const float* bias = nullptr, void* aux = nullptr, long ldaux = 0, int gelu_tanh = 0) {
+  GemmArgs g = gemm_args_default();
+  g.M = M; g.N = N; g.K = K;
+  g.a = a; g.lda = lda; g.a_kmajor = ak;
+  g.b = b; g.ldb = ldb; g.b_kmajor = bk;
+  g.c = c; g.ldc = ldc; g.out_f32 = out_f32;
+  g.epilogue = epi; g.bias = bias; g.aux = aux; g.ldaux = ldaux; g.gelu_tanh = gelu_tanh;
+  return launch_gemm(prec, g, st);
+}
+
+// per-(batch, head) GEMM over views of [T, ld] tensors (64 columns per head)
+// and/or [B, heads, S, S] tensors
+struct HeadView {
+  const void* p; long ld; int kmajor; bool is_prob;   // is_prob: [B,heads,S,S] else [T, ld] with head offset 64*h
+};
+static raf_status gemm_heads(const Plan& p, int prec, hipStream_t st, int M, int N, int K, HeadView a, HeadView b,
+                             void* c, long ldc, bool c_is_prob, float alpha) {
+  GemmArgs g = gemm_args_default();
+  g.M = M; g.N = N; g.K = K;
+  g.a = a.p; g.lda = a.ld; g.a_kmajor = a.kmajor;
+  g.b = b.p; g.ldb = b.ld; g.b_kmajor = b.kmajor;
+  g.c = c; g.ldc = ldc; g.alpha = alpha;
+  g.batch = (int)(p.B * p.NH);
+  g.nz_inner = (int)p.NH;
+  g.sa[0] = a.is_prob ? p.NH * p.S * p.S : p.S * a.ld; g.sa[1] = a.is_prob ? p.S * p.S : 64;
+  g.sb[0] = b.is_prob ? p.NH * p.S * p.S : p.S * b.ld; g.sb[1] = b.is_prob ? p.S * p.S : 64;
+  g.sc[0] = c_is_prob ? p.NH * p.S * p.S : p.S * ldc;  g.sc[1] = c_is_prob ? p.S * p.S : 64;
+  return launch_gemm(prec, g, st);
+}
+
+}  // namespace raf
+
+using namespace raf;
+
+extern "C" raf_status raf_layer_workspace(const raf_layer_desc* desc, size_t* saved_bytes, size_t* scratch_bytes) {
+  RAF_TRY(validate_desc(desc));
+  if (!saved_bytes || !scratch_bytes) return RAF_EINVAL;
+  const Plan p = make_plan(*desc);
+  *saved_bytes = p.saved_bytes;
+  *scratch_bytes = p.scratch_bytes;
+  return RAF_OK;
+}
+
+extern "C" raf_status raf_layer_fwd(const raf_layer_desc* desc, const raf_layer_tensors* w, const void* x,
+                                    const int32_t* seq_lens, void* y, void* saved, void* scratch, uint64_t step,
+                                    void* hip_stream) {
+  RAF_TRY(validate_desc(desc));
+  if (!tensors_ok(w) || !x || !y || !saved || !scratch) return RAF_EINVAL;
+  if (!aligned16(x) || !aligned16(y) || !aligned16(saved) || !aligned16(scratch)) return RAF_EINVAL;
+  if (seq_lens && ((uintptr_t)seq_lens & 3u)) return RAF_EINVAL;
+  const raf_layer_desc& d = *desc;
+  const Plan p = make_plan(d);
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int prec = d.precision;
+  const int T = (int)p.T, H = (int)p.H, F = (int)p.F, S = (int)p.S;
+  const size_t e = p.e;
+  const float alpha = 0.125f;   // 1/sqrt(64)
+
+  void* qkv = at(saved, p.qkv);
+  void* prob = at(saved, p.prob);
+  void* prob_d = at(saved, p.prob_d);
+  void* c = at(saved, p.c);
+  void* z1 = at(saved, p.z1);
+  void* ffn_in = at(saved, p.ffn_in);
+  void* u = at(saved, p.u);
+  void* g = at(saved, p.g);
+  void* z2 = at(saved, p.z2);
+  void* n1 = at(saved, p.n1);
+  float* mu1 = (float*)at(saved, p.mu1);
+  float* rstd1 = (float*)at(saved, p.rstd1);
+  float* mu2 = (float*)at(saved, p.mu2);
+  float* rstd2 = (float*)at(saved, p.rstd2);
+  void* s = at(scratch, p.s);
+  void* a = at(scratch, p.a);
+
+  const void* attn_in = x;
+  if (d.pre_ln) {
+    RAF_TRY(launch_ln_fwd(d, 0, T, nullptr, x, (const float*)w->ln1_g, (const float*)w->ln1_b, n1, nullptr, mu1,
+                          rstd1, step, st));
+    attn_in = n1;
+  }
+  // F1: qkv = attn_in . Wqkv^T + bqkv
+  RAF_TRY(gemm(prec, st, T, 3 * H, H, attn_in, H, 1, w->w_qkv, H, 1, qkv, 3 * H, 0, EPI_BIAS, (const float*)w->b_qkv));
+  // F2: s = Q K^T / 8 per (batch, head)
+  RAF_TRY(gemm_heads(p, prec, st, S, S, 64, HeadView{qkv, 3 * H, 1, false},
+                     HeadView{at(qkv, (size_t)H * e), 3 * H, 1, false}, s, S, true, alpha));
+  // F3: masked softmax + dropout site 1
+  RAF_TRY(launch_softmax_fwd(d, s, seq_lens, prob, prob_d, step, st));
+  // F4: c = prob_d . V, heads merged on store
+  RAF_TRY(gemm_heads(p, prec, st, S, 64, S, HeadView{prob_d, S, 1, true},
+                     HeadView{at(qkv, (size_t)2 * H * e), 3 * H, 0, false}, c, H, false, 1.0f));
+  // F5: a1 = c . Wo^T + bo
+  RAF_TRY(gemm(prec, st, T, H, H, c, H, 1, w->w_o, H, 1, a, H, 0, EPI_BIAS, (const float*)w->b_o));
+  // F6: z1 = x + drop2(a1); ffn_in = LN(z1)   (LN1 in post-LN, LN2 in pre-LN)
+  if (d.pre_ln)
+    RAF_TRY(launch_ln_fwd(d, 2, T, a, x, (const float*)w->ln2_g, (const float*)w->ln2_b, ffn_in, z1, mu2, rstd2, step,
+                          st));
+  else
+    RAF_TRY(launch_ln_fwd(d, 2, T, a, x, (const float*)w->ln1_g, (const float*)w->ln1_b, ffn_in, z1, mu1, rstd1, step,
+                          st));
+  // F7: u = ffn_in . W1^T + b1 (saved); g = gelu(u)
+  RAF_TRY(gemm(prec, st, T, F, H, ffn_in, H, 1, w->w_1, H, 1, g, F, 0, EPI_BIAS_GELU, (const float*)w->b_1, u, F,
+               d.gelu_tanh));
+  // F8: a2 = g . W2^T + b2
+  RAF_TRY(gemm(prec, st, T, H, F, g, F, 1, w->w_2, F, 1, a, H, 0, EPI_BIAS, (const float*)w->b_2));
+  // F9: post-LN: z2 = ffn_in + drop3(a2), y = LN2(z2); pre-LN: y = z1 + drop3(a2)
+  if (d.pre_ln)
+    RAF_TRY(launch_ln_fwd(d, 3, T, a, z1, nullptr, nullptr, y, nullptr, nullptr, nullptr, step, st));
+  else
+    RAF_TRY(launch_ln_fwd(d, 3, T, a, ffn_in, (const float*)w->ln2_g, (const float*)w->ln2_b, y, z2, mu2, rstd2, step,
+                          st));
+  return RAF_OK;
+}
+
+extern "C" raf_status raf_layer_bwd(const raf_layer_desc* desc, const raf_layer_tensors* w, const void* x,
+                                    const void* dy, const int32_t* seq_lens, const void* saved, void* dx,
+                                    raf_layer_tensors* grads, void* scratch, uint64_t step, void* hip_stream) {
+  RAF_TRY(validate_desc(desc));
+  if (!tensors_ok(w) || !tensors_ok(grads) || !x || !dy || !dx || !saved || !scratch) return RAF_EINVAL;
+  if (!aligned16(x) || !aligned16(dy) || !aligned16(dx) || !aligned16(saved) || !aligned16(scratch)) return RAF_EINVAL;
+  (void)seq_lens;   // masked probabilities are exactly zero in `saved`; no mask is needed again
+  const raf_layer_desc& d = *desc;
+  const Plan p = make_plan(d);
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int prec = d.precision;
+  const int T = (int)p.T, H = (int)p.H, F = (int)p.F, S = (int)p.S;
+  const size_t e = p.e;
+  const float alpha = 0.125f;
+
+  const void* qkv = at(saved, p.qkv);
+  const void* prob = at(saved, p.prob);
+  const void* prob_d = at(saved, p.prob_d);
+  const void* c = at(saved, p.c);
+  const void* z1 = at(saved, p.z1);
+  const void* ffn_in = at(saved, p.ffn_in);
+  void* u = (void*)at(saved, p.u);
+  const void* g = at(saved, p.g);
+  const void* z2 = at(saved, p.z2);
+  const void* n1 = at(saved, p.n1);
+  const float* mu1 = (const float*)at(saved, p.mu1);
+  const float* rstd1 = (const float*)at(saved, p.rstd1);
+  const float* mu2 = (const float*)at(saved, p.mu2);
+  const float* rstd2 = (const float*)at(saved, p.rstd2);
+
+  void* dz2 = at(scratch, p.dz2);
+  void* da = at(scratch, p.da);
+  void* du = at(scratch, p.du);
+  void* dffn = at(scratch, p.dffn);
+  void* dz1 = at(scratch, p.dz1);
+  void* dc = at(scratch, p.dc);
+  void* dprob_d = at(scratch, p.dprob_d);
+  void* ds = at(scratch, p.ds);
+  void* dqkv = at(scratch, p.dqkv);
+  void* dattn = at(scratch, p.dattn);
+  float* partial = (float*)at(scratch, p.partial);
+
+  // B9: adjoint of the output block
+  if (d.pre_ln)   // y = z1 + drop3(a2): da2 = dy * keep3/(1-p)
+    RAF_TRY(launch_ln_bwd(d, 3, T, dy, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, da, nullptr,
+                          nullptr, (float*)grads->b_2, partial, step, st));
+  else            // y = LN2(z2), z2 = ffn_in + drop3(a2)
+    RAF_TRY(launch_ln_bwd(d, 3, T, dy, nullptr, z2, mu2, rstd2, (const float*)w->ln2_g, nullptr, dz2, da,
+                          (float*)grads->ln2_g, (float*)grads->ln2_b, (float*)grads->b_2, partial, step, st));
+  // B8: a2 = g W2^T + b2  ->  dW2 = da2^T g ; du = (da2 W2) * gelu'(u)
+  RAF_TRY(gemm(prec, st, H, F, T, da, H, 0, g, F, 0, grads->w_2, F, 1));
+  RAF_TRY(gemm(prec, st, T, F, H, da, H, 1, w->w_2, F, 0, du, F, 0, EPI_MUL_GELU_GRAD, nullptr, u, F, d.gelu_tanh));
+  // B7: u = ffn_in W1^T + b1  ->  dW1 = du^T ffn_in ; db1 ; dffn = du W1
+  RAF_TRY(gemm(prec, st, F, H, T, du, F, 0, ffn_in, H, 0, grads->w_1, H, 1));
+  RAF_TRY(launch_colsum(prec, du, T, F, F, (float*)grads->b_1, partial, st));
+  RAF_TRY(gemm(prec, st, T, H, F, du, F, 1, w->w_1, H, 0, dffn, H));
+  // B6: the LayerNorm between the two halves, the residual, dropout site 2
+  if (d.pre_ln)   // ffn_in = LN2(z1); dz1 = dy + LN2'(dffn); da1 = dz1 * keep2/(1-p)
+    RAF_TRY(launch_ln_bwd(d, 2, T, dffn, nullptr, z1, mu2, rstd2, (const float*)w->ln2_g, dy, dz1, da,
+                          (float*)grads->ln2_g, (float*)grads->ln2_b, (float*)grads->b_o, partial, step, st));
+  else            // ffn_in = LN1(z1) feeds the ffn and the residual: g_in = dz2 + dffn
+    RAF_TRY(launch_ln_bwd(d, 2, T, dz2, dffn, z1, mu1, rstd1, (const float*)w->ln1_g, nullptr, dz1, da,
+                          (float*)grads->ln1_g, (float*)grads->ln1_b, (float*)grads->b_o, partial, step, st));
+  // B5: a1 = c Wo^T + bo  ->  dWo = da1^T c ; dc = da1 Wo
+  RAF_TRY(gemm(prec, st, H, H, T, da, H, 0, c, H, 0, grads->w_o, H, 1));
+  RAF_TRY(gemm(prec, st, T, H, H, da, H, 1, w->w_o, H, 0, dc, H));
+  // B4: c = prob_d V  ->  dprob_d = dc V^T ; dV = prob_d^T dc
+  RAF_TRY(gemm_heads(p, prec, st, S, S, 64, HeadView{dc, H, 1, false},
+                     HeadView{at(qkv, (size_t)2 * H * e), 3 * H, 1, false}, dprob_d, S, true, 1.0f));
+  RAF_TRY(gemm_heads(p, prec, st, S, 64, S, HeadView{prob_d, S, 0, true}, HeadView{dc, H, 0, false},
+                     at(dqkv, (size_t)2 * H * e), 3 * H, false, 1.0f));
+  // B3: softmax + dropout adjoint, with the 1/8 of the score scaling folded in
+  RAF_TRY(launch_softmax_bwd(d, prob, prob_d, dprob_d, ds, alpha, st));
+  // B2: s = Q K^T / 8  ->  dQ = ds K ; dK = ds^T Q
+  RAF_TRY(gemm_heads(p, prec, st, S, 64, S, HeadView{ds, S, 1, true},
+                     HeadView{at(qkv, (size_t)H * e), 3 * H, 0, false}, dqkv, 3 * H, false, 1.0f));
+  RAF_TRY(gemm_heads(p, prec, st, S, 64, S, HeadView{ds, S, 0, true}, HeadView{qkv, 3 * H, 0, false},
+                     at(dqkv, (size_t)H * e), 3 * H, false, 1.0f));
+  // B1: qkv = attn_in Wqkv^T + bqkv
+  RAF_TRY(launch_colsum(prec, dqkv, T, 3 * H, 3 * H, (float*)grads->b_qkv, partial, st));
+  if (d.pre_ln) {
+    RAF_TRY(gemm(prec, st, 3 * H, H, T, dqkv, 3 * H, 0, n1, H, 0, grads->w_qkv, H, 1));
+    RAF_TRY(gemm(prec, st, T, H, 3 * H, dqkv, 3 * H, 1, w->w_qkv, H, 0, dattn, H));
+    // attn_in = LN1(x); dx = dz1 + LN1'(dattn)
+    RAF_TRY(launch_ln_bwd(d, 0, T, dattn, nullptr, x, mu1, rstd1, (const float*)w->ln1_g, dz1, dx, nullptr,
+                          (float*)grads->ln1_g, (float*)grads->ln1_b, nullptr, partial, step, st));
+  } else {
+    RAF_TRY(gemm(prec, st, 3 * H, H, T, dqkv, 3 * H, 0, x, H, 0, grads->w_qkv, H, 1));
+    // dx = dz1 + dqkv Wqkv (residual add in the epilogue)
+    RAF_TRY(gemm(prec, st, T, H, 3 * H, dqkv, 3 * H, 1, w->w_qkv, H, 0, dx, H, 0, EPI_ADD_RES, nullptr, dz1, H));
+  }
+  return RAF_OK;
+}
+
+// ------------------------------------------------------ single operators --
+extern "C" raf_status raf_op_gemm(int32_t precision, int32_t M, int32_t N, int32_t K, const void* a, int32_t lda,
+                                  int32_t a_kmajor, const void* b, int32_t ldb, int32_t b_kmajor, void* c,
+                                  int32_t ldc, int32_t out_f32, float alpha, int32_t epilogue, const float* bias,
+                                  void* aux, int32_t gelu_tanh, void* hip_stream) {
+  if (precision != RAF_F32 && precision != RAF_BF16_AMP) return RAF_EINVAL;
+  GemmArgs g = gemm_args_default();
+  g.M = M; g.N = N; g.K = K;
+  g.a = a; g.lda = lda; g.a_kmajor = a_kmajor ? 1 : 0;
+  g.b = b; g.ldb = ldb; g.b_kmajor = b_kmajor ? 1 : 0;
+  g.c = c; g.ldc = ldc; g.out_f32 = out_f32 ? 1 : 0;
+  g.alpha = alpha; g.epilogue = epilogue; g.bias = bias; g.aux = aux; g.ldaux = ldc; g.gelu_tanh = gelu_tanh ? 1 : 0;
+  if (aux && !aligned16(aux)) return RAF_EINVAL;
+  return launch_gemm(precision, g, (hipStream_t)hip_stream);
+}
+
+extern "C" raf_status raf_op_softmax_fwd(const raf_layer_desc* desc, const void* s, const int32_t* seq_lens,
+                                         void* prob, void* prob_d, uint64_t step, void* hip_stream) {
+  RAF_TRY(validate_desc(desc));
+  return launch_softmax_fwd(*desc, s, seq_lens, prob, prob_d, step, (hipStream_t)hip_stream);
+}
+
+extern "C" raf_status raf_op_softmax_bwd(const raf_layer_desc* desc, const void* prob, const void* prob_d,
+                                         const void* dprob_d, void* ds, float scale_out, void* hip_stream) {
+  RAF_TRY(validate_desc(desc));
+  return launch_softmax_bwd(*desc, prob, prob_d, dprob_d, ds, scale_out, (hipStream_t)hip_stream);
+}
+
+extern "C" raf_status raf_op_dropout_residual_ln_fwd(const raf_layer_desc* desc, int32_t site, int64_t rows,
+                                                     const void* a, const void* res, const float* gamma,
+                                                     const float* beta, void* out, void* z_out, float* mu,
+                                                     float* rstd, uint64_t step, void* hip_stream) {
+  RAF_TRY(validate_desc(desc));
+  return launch_ln_fwd(*desc, site, rows, a, res, gamma, beta, out, z_out, mu, rstd, step, (hipStream_t)hip_stream);
+}
+
+extern "C" size_t raf_op_ln_bwd_partial_floats(int32_t hidden, int64_t rows) {
+  if (hidden < 32 || hidden > 4096 || (hidden % 8)) return 0;
+  return ln_bwd_partial_floats(hidden, rows);
+}
+
+extern "C" raf_status raf_op_dropout_residual_ln_bwd(const raf_layer_desc* desc, int32_t site, int64_t rows,
+                                                     const void* dout, const void* dout2, const void* z,
+                                                     const float* mu, const float* rstd, const float* gamma,
+                                                     const void* dres, void* dz, void* da, float* dgamma,
+                                                     float* dbeta, float* dbias, float* partial, uint64_t step,
+                                                     void* hip_stream) {
+  RAF_TRY(validate_desc(desc));
+  return launch_ln_bwd(*desc, site, rows, dout, dout2, z, mu, rstd, gamma, dres, dz, da, dgamma, dbeta, dbias, partial,
+                       step, (hipStream_t)hip_stream);
+}
+
+extern "C" const char* raf_status_string(raf_status s) {
+  switch (s) {
+    case RAF_OK: return "ok";
+    case RAF_EINVAL: return "invalid argument";
+    case RAF_ENOTSUP: return "unsupported shape or mode";
+    case RAF_EWORKSPACE: return "workspace too small";
+    case RAF_EHIP: return "HIP error";
+  }
+  return "unknown status";
+}
+
+extern "C" const char* raf_last_hip_error(void) {
+  static thread_local std::string copy;
+  std::lock_guard<std::mutex> lk(g_err_mutex);
+  copy = g_err;
+  return copy.c_str();
+}
+
+extern "C" const char* raf_version(void) { return "raf_mi355 0.1 gfx950"; }

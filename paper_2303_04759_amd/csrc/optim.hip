@@ -1,0 +1,214 @@
+// Fused multi-tensor Adam with loss-scale removal and the bf16 weight copy
+// (optimizer inside the training step with in-place parameter update, paper
+// Section 3; the AMP cast fused into its producer, Section 3.1.2), the loss
+// seed of the benchmark workload, and the dropout-mask test hook.
+#include "common.hpp"
+
+namespace raf {
+
+constexpr int ADAM_MAX_TENSORS = 48;       // per launch (kernel-argument budget)
+constexpr int ADAM_CHUNK = 256 * 4 * 4;    // elements per block
+
+struct AdamTable {
+  float* master[ADAM_MAX_TENSORS];
+  const float* grad[ADAM_MAX_TENSORS];
+  float* m[ADAM_MAX_TENSORS];
+  float* v[ADAM_MAX_TENSORS];
+  bf16_t* lowp[ADAM_MAX_TENSORS];
+  long n[ADAM_MAX_TENSORS];
+  int block_start[ADAM_MAX_TENSORS + 1];   // first block of each tensor
+  int count;
+};
+
+struct AdamHyper {
+  float lr_over_bc1, inv_bc2, beta1, beta2, one_minus_beta1, one_minus_beta2, eps, weight_decay, inv_scale;
+};
+
+__device__ __forceinline__ void adam_update(float& w, float g, float& m, float& v, const AdamHyper& h) {
+  g = g * h.inv_scale + h.weight_decay * w;
+  m = h.beta1 * m + h.one_minus_beta1 * g;
+  v = h.beta2 * v + h.one_minus_beta2 * g * g;
+  w = w - h.lr_over_bc1 * m / (sqrtf(v * h.inv_bc2) + h.eps);
+}
+
+__global__ __launch_bounds__(256) void adam_kernel(AdamTable tab, AdamHyper h) {
+  int ti = 0;
+  while (ti + 1 < tab.count && (int)blockIdx.x >= tab.block_start[ti + 1]) ++ti;
+  const long n = tab.n[ti];
+  float* __restrict__ W = tab.master[ti];
+  const float* __restrict__ G = tab.grad[ti];
+  float* __restrict__ Mo = tab.m[ti];
+  float* __restrict__ Vo = tab.v[ti];
+  bf16_t* __restrict__ L = tab.lowp[ti];
+  const long base = (long)(blockIdx.x - tab.block_start[ti]) * ADAM_CHUNK;
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const long i = base + ((long)it * 256 + threadIdx.x) * 4;
+    if (i + 3 < n) {
+      float4 w = *reinterpret_cast<const float4*>(W + i);
+      const float4 g = *reinterpret_cast<const float4*>(G + i);
+      float4 m = *reinterpret_cast<const float4*>(Mo + i);
+      float4 v = *reinterpret_cast<const float4*>(Vo + i);
+      adam_update(w.x, g.x, m.x, v.x, h);
+      adam_update(w.y, g.y, m.y, v.y, h);
+      adam_update(w.z, g.z, m.z, v.z, h);
+      adam_update(w.w, g.w, m.w, v.w, h);
+      *reinterpret_cast<float4*>(W + i) = w;
+      *reinterpret_cast<float4*>(Mo + i) = m;
+      *reinterpret_cast<float4*>(Vo + i) = v;
+      if (L) {
+        uint2 p;
+        p.x = pack_bf16x2(w.x, w.y);
+        p.y = pack_bf16x2(w.z, w.w);
+        *reinterpret_cast<uint2*>(L + i) = p;
+      }
+    } else {
+      for (long j = i; j < n && j < i + 4; ++j) {
+        float w = W[j], m = Mo[j], v = Vo[j];
+        adam_update(w, G[j], m, v, h);
+        W[j] = w;
+        Mo[j] = m;
+        Vo[j] = v;
+        if (L) L[j] = (bf16_t)w;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------- loss seed --
+template <typename T>
+__global__ __launch_bounds__(256) void loss_seed_kernel(const T* __restrict__ y, const T* __restrict__ G, long n,
+                                                        float loss_scale, T* __restrict__ dy,
+                                                        float* __restrict__ partial) {
+  __shared__ float red[4];
+  float acc = 0.f;
+  for (long i = ((long)blockIdx.x * 256 + threadIdx.x) * 8; i < n; i += (long)gridDim.x * 256 * 8) {
+    float a[8], g[8];
+    Vec8<T>::load(y + i, a);
+    Vec8<T>::load(G + i, g);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      acc += a[e] * g[e];
+      g[e] *= loss_scale;
+    }
+    Vec8<T>::store(dy + i, g);
+  }
+  acc = group_sum<64>(acc);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) partial[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+__global__ __launch_bounds__(256) void loss_final_kernel(const float* __restrict__ partial, int nparts,
+                                                         float* __restrict__ loss_out) {
+  __shared__ float red[256];
+  float acc = 0.f;
+  for (int i = threadIdx.x; i < nparts; i += 256) acc += partial[i];
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *loss_out = red[0];
+}
+
+// ------------------------------------------------------- mask test hook ---
+__global__ __launch_bounds__(256) void dropout_mask_kernel(uint8_t* __restrict__ out, long n, DropSite drop) {
+  const long i8 = ((long)blockIdx.x * 256 + threadIdx.x) * 8;
+  if (i8 >= n) return;
+  float mult[8];
+  if (drop.enabled) {
+    drop_mult8(drop, (uint64_t)i8, mult);
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) mult[e] = 1.f;
+  }
+  for (int e = 0; e < 8 && i8 + e < n; ++e) out[i8 + e] = mult[e] != 0.f ? 1 : 0;
+}
+
+}  // namespace raf
+
+using namespace raf;
+
+extern "C" raf_status raf_adam_step(const raf_adam_tensor* list, int32_t count, float lr, float beta1, float beta2,
+                                    float eps, float weight_decay, int64_t t, float inv_loss_scale,
+                                    void* hip_stream) {
+  if (count < 0 || (count > 0 && !list)) return RAF_EINVAL;
+  if (t < 1 || !(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f)) return RAF_EINVAL;
+  for (int i = 0; i < count; ++i) {
+    const raf_adam_tensor& a = list[i];
+    if (a.n < 0) return RAF_EINVAL;
+    if (a.n == 0) continue;
+    if (!a.master || !a.grad || !a.m || !a.v) return RAF_EINVAL;
+    if (!aligned16(a.master) || !aligned16(a.grad) || !aligned16(a.m) || !aligned16(a.v) || !aligned16(a.lowp))
+      return RAF_EINVAL;
+  }
+  AdamHyper h;
+  const double bc1 = 1.0 - pow((double)beta1, (double)t);
+  const double bc2 = 1.0 - pow((double)beta2, (double)t);
+  h.lr_over_bc1 = (float)((double)lr / bc1);
+  h.inv_bc2 = (float)(1.0 / bc2);
+  h.beta1 = beta1;
+  h.beta2 = beta2;
+  h.one_minus_beta1 = (float)(1.0 - (double)beta1);
+  h.one_minus_beta2 = (float)(1.0 - (double)beta2);
+  h.eps = eps;
+  h.weight_decay = weight_decay;
+  h.inv_scale = inv_loss_scale;
+  hipStream_t st = (hipStream_t)hip_stream;
+  int i = 0;
+  while (i < count) {
+    AdamTable tab;
+    tab.count = 0;
+    long blocks = 0;
+    while (i < count && tab.count < ADAM_MAX_TENSORS) {
+      const raf_adam_tensor& a = list[i++];
+      if (a.n == 0) continue;
+      const long nb = (a.n + ADAM_CHUNK - 1) / ADAM_CHUNK;
+      if (blocks + nb > 0x7fffffff) return RAF_ENOTSUP;
+      const int k = tab.count++;
+      tab.master[k] = a.master; tab.grad[k] = a.grad; tab.m[k] = a.m; tab.v[k] = a.v;
+      tab.lowp[k] = (bf16_t*)a.lowp; tab.n[k] = a.n;
+      tab.block_start[k] = (int)blocks;
+      blocks += nb;
+    }
+    if (tab.count == 0) continue;
+    tab.block_start[tab.count] = (int)blocks;
+    hipLaunchKernelGGL(adam_kernel, dim3((unsigned)blocks), dim3(256), 0, st, tab, h);
+    raf_status rc = check_launch();
+    if (rc != RAF_OK) return rc;
+  }
+  return RAF_OK;
+}
+
+extern "C" raf_status raf_loss_seed(int32_t precision, const void* y, const void* G, int64_t n, float loss_scale,
+                                    float* loss_out, void* dy, float* partial, void* hip_stream) {
+  if (!y || !G || !loss_out || !dy || !partial || n <= 0 || (n % 8)) return RAF_EINVAL;
+  if (!aligned16(y) || !aligned16(G) || !aligned16(dy)) return RAF_EINVAL;
+  if (precision != RAF_F32 && precision != RAF_BF16_AMP) return RAF_EINVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  long nb = (n / 8 + 255) / 256;
+  if (nb > RAF_LOSS_PARTIALS) nb = RAF_LOSS_PARTIALS;
+  if (precision == RAF_F32)
+    hipLaunchKernelGGL((loss_seed_kernel<float>), dim3(nb), dim3(256), 0, st, (const float*)y, (const float*)G,
+                       (long)n, loss_scale, (float*)dy, partial);
+  else
+    hipLaunchKernelGGL((loss_seed_kernel<bf16_t>), dim3(nb), dim3(256), 0, st, (const bf16_t*)y, (const bf16_t*)G,
+                       (long)n, loss_scale, (bf16_t*)dy, partial);
+  raf_status rc = check_launch();
+  if (rc != RAF_OK) return rc;
+  hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(256), 0, st, partial, (int)nb, loss_out);
+  return check_launch();
+}
+
+extern "C" raf_status raf_debug_dropout_mask(const raf_layer_desc* desc, int32_t site, uint64_t step,
+                                             uint8_t* mask_out, int64_t n, void* hip_stream) {
+  if (!desc || !mask_out || n <= 0 || site < 1 || site > 255) return RAF_EINVAL;
+  if (!(desc->dropout_p >= 0.0 && desc->dropout_p < 1.0)) return RAF_EINVAL;
+  if ((uint64_t)n / 4 > 0xffffffffull) return RAF_ENOTSUP;
+  const DropSite drop = make_drop_site(*desc, site, step);
+  const long nb = ((n + 7) / 8 + 255) / 256;
+  hipLaunchKernelGGL(dropout_mask_kernel, dim3(nb), dim3(256), 0, (hipStream_t)hip_stream, mask_out, (long)n, drop);
+  return check_launch();
+}

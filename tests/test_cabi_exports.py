@@ -1,0 +1,90 @@
+"""CPU-only checks of the boundary: the library loads, exports every symbol the
+header declares, and rejects bad arguments on the host before any launch."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2303_04759_amd as raf
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(raf.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    return raf.load_library()
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "raf_mi355.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(raf_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    syms = header_symbols()
+    assert len(syms) >= 14
+    for s in syms:
+        assert hasattr(lib, s), s
+    assert sorted(raf.EXPORTS) == syms
+
+
+def test_struct_layout_matches_header():
+    assert C.sizeof(raf.LayerDesc) == 64
+    assert raf.LayerDesc.dropout_p.offset == 40 and raf.LayerDesc.seed.offset == 48
+    assert C.sizeof(raf.LayerTensors) == 96
+    assert C.sizeof(raf.AdamTensor) == 48
+
+
+def good_cfg(**kw):
+    cfg = dict(batch=2, seq=32, hidden=128, heads=2, ffn=512, pre_ln=0, causal=0, gelu_tanh=0, precision=0,
+               ln_eps=1e-5, dropout_p=0.1, seed=1, layer_id=0)
+    cfg.update(kw)
+    return cfg
+
+
+def test_workspace_and_descriptor_validation(lib):
+    sv, sc = raf.raf_layer_workspace(raf.make_desc(good_cfg()))
+    assert sv > 0 and sc > 0 and sv % 256 == 0 and sc % 256 == 0
+    sv2, _ = raf.raf_layer_workspace(raf.make_desc(good_cfg(precision=1)))
+    assert sv2 < sv
+    for bad, code in ((dict(heads=4), raf.RAF_ENOTSUP), (dict(seq=33), raf.RAF_ENOTSUP),
+                      (dict(dropout_p=1.0), raf.RAF_EINVAL), (dict(batch=0), raf.RAF_EINVAL),
+                      (dict(precision=7), raf.RAF_EINVAL), (dict(hidden=8192, heads=128), raf.RAF_ENOTSUP),
+                      (dict(pre_ln=2), raf.RAF_EINVAL)):
+        with pytest.raises(raf.RafError) as e:
+            raf.raf_layer_workspace(raf.make_desc(good_cfg(**bad)))
+        assert e.value.status == code, bad
+
+
+def test_null_and_misaligned_pointers_are_rejected_on_host(lib):
+    d = raf.make_desc(good_cfg())
+    w = raf.LayerTensors()          # all NULL
+    rc = lib.raf_layer_fwd(C.byref(d), C.byref(w), 256, None, 256, 256, 256, 0, None)
+    assert rc == raf.RAF_EINVAL
+    for n in raf.PARAM_NAMES:
+        setattr(w, n, 4096)
+    rc = lib.raf_layer_fwd(C.byref(d), C.byref(w), 4096 + 8, None, 4096, 4096, 4096, 0, None)   # x misaligned
+    assert rc == raf.RAF_EINVAL
+    rc = lib.raf_layer_bwd(C.byref(d), C.byref(w), 4096, None, None, 4096, 4096, C.byref(w), 4096, 0, None)
+    assert rc == raf.RAF_EINVAL
+    assert lib.raf_adam_step(None, 0, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, 1.0, None) == raf.RAF_OK     # empty list
+    assert lib.raf_adam_step(None, 1, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, 1.0, None) == raf.RAF_EINVAL
+    t = (raf.AdamTensor * 1)(raf.AdamTensor(4096, 4096, 4096, 4096 + 4, None, 10))
+    assert lib.raf_adam_step(t, 1, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, 1.0, None) == raf.RAF_EINVAL
+    assert lib.raf_adam_step(t, 1, 1e-3, 0.9, 0.999, 1e-8, 0.0, 0, 1.0, None) == raf.RAF_EINVAL    # t is 1-based
+    assert lib.raf_op_gemm(1, 64, 64, 48, 4096, 64, 1, 4096, 64, 1, 4096, 64, 0, 1.0, 0, None, None, 0,
+                           None) == raf.RAF_ENOTSUP
+    assert raf.status_string(raf.RAF_ENOTSUP) == "unsupported shape or mode"
+    assert raf.version().startswith("raf_mi355")
+
+
+def test_product_path_has_no_oracle_or_cpu_fallback():
+    pkg = os.path.join(ROOT, "paper_2303_04759_amd")
+    for fn in ("__init__.py", "harness.py"):
+        src = open(os.path.join(pkg, fn)).read()
+        assert "oracle" not in src.replace("CPU oracle", "")

@@ -1,0 +1,172 @@
+"""Whole-step parity on the GPU through the C ABI: forward, loss seed,
+backward and Adam of one layer against the fp64 oracle on identical seeded
+inputs.  Tolerances (relative Frobenius): fp32 mode 1e-5 forward, 1e-4
+gradients and updates; bf16 AMP 2e-2 forward, 3e-2 gradients and updates."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2303_04759_amd as raf
+from paper_2303_04759_amd.harness import DeviceLayer
+from oracle.step import train_step
+from workloads.synthetic import ADAM, CONFIGS, PARAM_NAMES, make_layer_inputs
+
+from gpu_util import announce, host, rel_fro
+
+pytestmark = pytest.mark.gpu
+
+FWD_TOL = {0: 1e-5, 1: 2e-2}
+BWD_TOL = {0: 1e-4, 1: 3e-2}
+
+
+def run_and_compare(cfg, seed, steps, random_affine=False, lens_override=None, check_lower=False):
+    inp = make_layer_inputs(cfg, seed=seed, random_affine=random_affine)
+    if lens_override is not None:
+        inp["seq_lens"] = np.asarray(lens_override, dtype=np.int32)
+    lay = DeviceLayer(cfg, inp, ADAM)
+    prec = cfg["precision"]
+    p = {k: v.astype(np.float64) for k, v in inp["params"].items()}
+    m = {k: np.zeros_like(v) for k, v in p.items()}
+    v = {k: np.zeros_like(v) for k, v in p.items()}
+    hyper = dict(ADAM, loss_scale=cfg["loss_scale"])
+    report = {}
+    for t in range(1, steps + 1):
+        w_before = {k: host(lay.master[k]) for k in PARAM_NAMES}
+        lay.train_step(t)
+        torch.cuda.synchronize()
+        ref = train_step(cfg, p, m, v, inp["x"], inp["G"], inp["seq_lens"], t, hyper)
+        e_y = rel_fro(host(lay.y), ref["y"])
+        e_dx = rel_fro(host(lay.dx), ref["dx"])
+        assert np.isfinite(host(lay.y)).all()
+        assert e_y <= FWD_TOL[prec], ("y", t, e_y)
+        assert e_dx <= BWD_TOL[prec], ("dx", t, e_dx)
+        loss_ref = ref["loss"]
+        # loss = sum(y*G): independent relative errors eps on y move it by about eps * ||y*G||_2
+        yg = np.linalg.norm(ref["y"] * np.asarray(inp["G"], dtype=np.float64).reshape(ref["y"].shape))
+        assert abs(float(lay.loss.item()) - loss_ref) <= FWD_TOL[prec] * max(1.0, yg), ("loss", t)
+        worst = 0.0
+        worst_dw = 0.0
+        for k in PARAM_NAMES:
+            g_ref = ref["grads"][k].reshape(p[k].shape)
+            e_g = rel_fro(host(lay.grads[k]), g_ref)
+            assert e_g <= BWD_TOL[prec], ("grad", k, t, e_g)
+            worst = max(worst, e_g)
+            e_w = rel_fro(host(lay.master[k]), ref["params"][k])
+            assert e_w <= BWD_TOL[prec], ("w", k, t, e_w)
+            # the update itself: at small t Adam is sign-like (dw ~ -lr*sign(g)), so an element whose
+            # tiny gradient changes sign under bf16 rounding moves by 2*lr; reported, bounded in fp32 only
+            e_dw = rel_fro(host(lay.master[k]) - w_before[k], ref["params"][k] - w_before[k])
+            worst_dw = max(worst_dw, e_dw)
+            if prec == 0:
+                assert e_dw <= 2e-2, ("dw", k, t, e_dw)
+            e_m = rel_fro(host(lay.m[k]), ref["m"][k])
+            e_v = rel_fro(host(lay.v[k]), ref["v"][k])
+            if np.linalg.norm(ref["m"][k]) > 1e-12:
+                assert e_m <= BWD_TOL[prec] and e_v <= 2 * BWD_TOL[prec], ("mv", k, t, e_m, e_v)
+            if lay.lowp[k] is not None:
+                assert torch.equal(lay.lowp[k], lay.master[k].to(torch.bfloat16)), k
+        report[t] = dict(y=e_y, dx=e_dx, worst_grad=worst, worst_dw=worst_dw)
+        p, m, v = ref["params"], ref["m"], ref["v"]
+        # keep the two trajectories on the same weights: the update is sign-like at small t, so
+        # compare each step from the oracle's state rounded the way the device stores it
+        for k in PARAM_NAMES:
+            lay.master[k].copy_(torch.from_numpy(p[k].astype(np.float32)))
+            lay.m[k].copy_(torch.from_numpy(m[k].astype(np.float32)))
+            lay.v[k].copy_(torch.from_numpy(v[k].astype(np.float32)))
+            if lay.lowp[k] is not None:
+                lay.lowp[k].copy_(lay.master[k].to(torch.bfloat16))
+            p[k] = host(lay.master[k])
+            m[k] = host(lay.m[k])
+            v[k] = host(lay.v[k])
+    if check_lower:
+        # a bf16 run that is closer than ~1e-4 would mean bf16 is not being exercised
+        assert report[1]["y"] > 1e-4
+    print("parity", {t: {k: "%.2e" % v for k, v in r.items()} for t, r in report.items()}, flush=True)
+    return report
+
+
+def test_tiny_fp32_three_steps():
+    announce("layer tiny fp32")
+    run_and_compare(CONFIGS["tiny"], seed=0, steps=3)
+
+
+def test_tiny_fp32_random_affine_padding_dropout():
+    announce("layer tiny fp32 affine+padding+dropout")
+    cfg = dict(CONFIGS["tiny"], dropout_p=0.1, loss_scale=8.0)
+    run_and_compare(cfg, seed=1, steps=2, random_affine=True, lens_override=[32, 13])
+
+
+@pytest.mark.parametrize("variant", [dict(pre_ln=1, causal=1), dict(gelu_tanh=1), dict(pre_ln=1, gelu_tanh=1, dropout_p=0.2),
+                                     dict(causal=1, dropout_p=0.1)])
+def test_small_fp32_variants(variant):
+    announce("layer small fp32", variant)
+    cfg = dict(CONFIGS["tiny"], batch=3, seq=96, hidden=192, heads=3, ffn=320, ln_eps=1e-5, **variant)
+    run_and_compare(cfg, seed=2, steps=2, random_affine=True, lens_override=[96, 40, 1])
+
+
+def test_tiny_shape_in_bf16_amp():
+    announce("layer tiny bf16")
+    cfg = dict(CONFIGS["tiny"], precision=1, loss_scale=1024.0, dropout_p=0.1)
+    run_and_compare(cfg, seed=0, steps=2, check_lower=True)
+
+
+@pytest.mark.parametrize("variant", [dict(), dict(pre_ln=1, causal=1, ln_eps=1e-5)])
+def test_ragged_bf16_amp(variant):
+    announce("layer ragged bf16", variant)
+    cfg = dict(CONFIGS["bert_base"], batch=3, seq=160, hidden=320, heads=5, ffn=1056, **variant)
+    run_and_compare(cfg, seed=3, steps=2, random_affine=True, lens_override=[160, 77, 5])
+
+
+def test_bert_base_full_size_bf16_amp():
+    announce("layer bert_base full")
+    run_and_compare(CONFIGS["bert_base"], seed=0, steps=3, check_lower=True)
+
+
+def test_bert_large_full_size_bf16_amp():
+    announce("layer bert_large full")
+    run_and_compare(CONFIGS["bert_large"], seed=0, steps=1)
+
+
+def test_gpt2_medium_full_size_bf16_amp():
+    announce("layer gpt2_medium full")
+    run_and_compare(CONFIGS["gpt2_medium"], seed=0, steps=1)
+
+
+def test_determinism_and_step_dependence():
+    announce("layer determinism")
+    cfg = CONFIGS["bert_base"]
+    inp = make_layer_inputs(cfg, seed=1)
+    a, b = DeviceLayer(cfg, inp, ADAM), DeviceLayer(cfg, inp, ADAM)
+    a.train_step(1)
+    b.train_step(1)
+    torch.cuda.synchronize()
+    assert torch.equal(a.y, b.y) and torch.equal(a.dx, b.dx)
+    for k in PARAM_NAMES:
+        assert torch.equal(a.grads[k], b.grads[k]) and torch.equal(a.master[k], b.master[k])
+    y1 = a.y.clone()
+    a.fwd(2)
+    torch.cuda.synchronize()
+    assert not torch.equal(a.y, y1)      # another step draws other dropout masks
+
+
+def test_checkpoint_resume_is_bit_exact():
+    announce("layer resume")
+    cfg = dict(CONFIGS["tiny"], precision=1, loss_scale=1024.0, dropout_p=0.1)
+    inp = make_layer_inputs(cfg, seed=4)
+    a = DeviceLayer(cfg, inp, ADAM)
+    for t in (1, 2, 3, 4):
+        a.train_step(t)
+    b = DeviceLayer(cfg, inp, ADAM)
+    for t in (1, 2):
+        b.train_step(t)
+    torch.cuda.synchronize()
+    c = DeviceLayer(cfg, inp, ADAM)      # "reload": state copied out of b
+    for k in PARAM_NAMES:
+        c.master[k].copy_(b.master[k]); c.m[k].copy_(b.m[k]); c.v[k].copy_(b.v[k])
+        if c.lowp[k] is not None:
+            c.lowp[k].copy_(b.lowp[k])
+    for t in (3, 4):
+        c.train_step(t)
+    torch.cuda.synchronize()
+    for k in PARAM_NAMES:
+        assert torch.equal(a.master[k], c.master[k]) and torch.equal(a.v[k], c.v[k])
