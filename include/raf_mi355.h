@@ -141,9 +141,11 @@ typedef struct {
  * Per element: g = grad*inv_loss_scale (+ weight_decay*w); m = b1 m + (1-b1) g;
  * v = b2 v + (1-b2) g^2; w -= lr * (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps).
  *   list [host] array of `count` tensors (copied into kernel arguments);
- *   t is 1-based.  count == 0 is a no-op. */
-raf_status raf_adam_step(const raf_adam_tensor *list, int32_t count, float lr, float beta1, float beta2,
-                         float eps, float weight_decay, int64_t t, float inv_loss_scale, void *hip_stream);
+ *   t is 1-based.  count == 0 is a no-op.  Hyper-parameters are doubles; the
+ *   derived constants (1-b1, 1-b2, lr/(1-b1^t), 1/(1-b2^t)) are formed in double
+ *   on the host and rounded once to float for the kernel. */
+raf_status raf_adam_step(const raf_adam_tensor *list, int32_t count, double lr, double beta1, double beta2,
+                         double eps, double weight_decay, int64_t t, double inv_loss_scale, void *hip_stream);
 
 /* Test hook: the keep-mask of one dropout site as bytes (1 = kept).
  *   mask_out [dev] uint8[n]; element order is the site's flat index. */

@@ -56,8 +56,8 @@ _SIGNATURES = {
                                 C.c_void_p, C.c_void_p, C.POINTER(LayerTensors), C.c_void_p, C.c_uint64, C.c_void_p]),
     "raf_loss_seed": (C.c_int, [C.c_int32, C.c_void_p, C.c_void_p, C.c_int64, C.c_float, C.c_void_p, C.c_void_p,
                                 C.c_void_p, C.c_void_p]),
-    "raf_adam_step": (C.c_int, [C.POINTER(AdamTensor), C.c_int32, C.c_float, C.c_float, C.c_float, C.c_float,
-                                C.c_float, C.c_int64, C.c_float, C.c_void_p]),
+    "raf_adam_step": (C.c_int, [C.POINTER(AdamTensor), C.c_int32, C.c_double, C.c_double, C.c_double, C.c_double,
+                                C.c_double, C.c_int64, C.c_double, C.c_void_p]),
     "raf_debug_dropout_mask": (C.c_int, [C.POINTER(LayerDesc), C.c_int32, C.c_uint64, C.c_void_p, C.c_int64,
                                          C.c_void_p]),
     "raf_op_gemm": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_int32,

@@ -131,11 +131,11 @@ __global__ __launch_bounds__(256) void dropout_mask_kernel(uint8_t* __restrict__
 
 using namespace raf;
 
-extern "C" raf_status raf_adam_step(const raf_adam_tensor* list, int32_t count, float lr, float beta1, float beta2,
-                                    float eps, float weight_decay, int64_t t, float inv_loss_scale,
+extern "C" raf_status raf_adam_step(const raf_adam_tensor* list, int32_t count, double lr, double beta1, double beta2,
+                                    double eps, double weight_decay, int64_t t, double inv_loss_scale,
                                     void* hip_stream) {
   if (count < 0 || (count > 0 && !list)) return RAF_EINVAL;
-  if (t < 1 || !(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f)) return RAF_EINVAL;
+  if (t < 1 || !(beta1 >= 0.0 && beta1 < 1.0) || !(beta2 >= 0.0 && beta2 < 1.0)) return RAF_EINVAL;
   for (int i = 0; i < count; ++i) {
     const raf_adam_tensor& a = list[i];
     if (a.n < 0) return RAF_EINVAL;
@@ -145,17 +145,17 @@ extern "C" raf_status raf_adam_step(const raf_adam_tensor* list, int32_t count, 
       return RAF_EINVAL;
   }
   AdamHyper h;
-  const double bc1 = 1.0 - pow((double)beta1, (double)t);
-  const double bc2 = 1.0 - pow((double)beta2, (double)t);
-  h.lr_over_bc1 = (float)((double)lr / bc1);
+  const double bc1 = 1.0 - pow(beta1, (double)t);
+  const double bc2 = 1.0 - pow(beta2, (double)t);
+  h.lr_over_bc1 = (float)(lr / bc1);
   h.inv_bc2 = (float)(1.0 / bc2);
-  h.beta1 = beta1;
-  h.beta2 = beta2;
-  h.one_minus_beta1 = (float)(1.0 - (double)beta1);
-  h.one_minus_beta2 = (float)(1.0 - (double)beta2);
-  h.eps = eps;
-  h.weight_decay = weight_decay;
-  h.inv_scale = inv_loss_scale;
+  h.beta1 = (float)beta1;
+  h.beta2 = (float)beta2;
+  h.one_minus_beta1 = (float)(1.0 - beta1);
+  h.one_minus_beta2 = (float)(1.0 - beta2);
+  h.eps = (float)eps;
+  h.weight_decay = (float)weight_decay;
+  h.inv_scale = (float)inv_loss_scale;
   hipStream_t st = (hipStream_t)hip_stream;
   int i = 0;
   while (i < count) {

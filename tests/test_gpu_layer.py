@@ -51,11 +51,22 @@ def run_and_compare(cfg, seed, steps, random_affine=False, lens_override=None, c
             e_g = rel_fro(host(lay.grads[k]), g_ref)
             assert e_g <= BWD_TOL[prec], ("grad", k, t, e_g)
             worst = max(worst, e_g)
-            e_w = rel_fro(host(lay.master[k]), ref["params"][k])
+            # Updated weights.  Adam's step lr*m_hat/(sqrt(v_hat)+eps) is sign-like in g at small t,
+            # so where the true gradient is (near) zero - e.g. the key bias, whose gradient vanishes
+            # identically - the step's sign is decided by rounding noise on either side.  Such
+            # elements (|g| below the gradient tolerance times the tensor's rms) are only required
+            # to respect Adam's step bound; all others must match to the stated tolerance.
+            w_dev, w_ref = host(lay.master[k]), ref["params"][k]
+            g_un = g_ref / cfg["loss_scale"]
+            cond = np.abs(g_un) > BWD_TOL[prec] * np.sqrt(np.mean(g_un ** 2))
+            e_w = rel_fro(w_dev[cond], w_ref[cond])
             assert e_w <= BWD_TOL[prec], ("w", k, t, e_w)
+            assert cond.mean() > (0.6 if k != "b_qkv" else 0.3), ("conditioned fraction", k, cond.mean())
+            # |step| <= lr * (1-b1^t)^-1 * ... <= ~3.2*lr for t <= 3 with these betas
+            assert np.abs(w_dev - w_before[k]).max() <= 4.0 * ADAM["lr"], ("step bound", k, t)
             # the update itself: at small t Adam is sign-like (dw ~ -lr*sign(g)), so an element whose
             # tiny gradient changes sign under bf16 rounding moves by 2*lr; reported, bounded in fp32 only
-            e_dw = rel_fro(host(lay.master[k]) - w_before[k], ref["params"][k] - w_before[k])
+            e_dw = rel_fro((w_dev - w_before[k])[cond], (w_ref - w_before[k])[cond])
             worst_dw = max(worst_dw, e_dw)
             if prec == 0:
                 assert e_dw <= 2e-2, ("dw", k, t, e_dw)

@@ -236,9 +236,12 @@ def test_adam_multi_tensor_matches_oracle():
             if n == 0:
                 continue
             w_new, M64[i], V64[i] = adam_step(W64[i], G[i], M64[i], V64[i], t, 1e-3, 0.9, 0.999, 1e-8, 0.01, 1.0 / 1024)
-            assert rel_fro(host(Wd[i]) - W64[i], w_new - W64[i]) <= 1e-4, (t, i)
+            # the master weight is stored in float: the update is exact to 1e-4 of itself plus one
+            # float rounding of the weight
+            err = np.linalg.norm(host(Wd[i]) - w_new)
+            assert err <= 1e-4 * np.linalg.norm(w_new - W64[i]) + 1.2e-7 * np.linalg.norm(w_new), (t, i)
             assert rel_fro(host(Md[i]), M64[i]) <= 1e-5 and rel_fro(host(Vd[i]), V64[i]) <= 1e-5
-            W64[i] = w_new
+            W64[i] = host(Wd[i])         # continue from the stored (float-rounded) weights
             if Ld[i] is not None:    # the low-precision copy is the rounded master, bit for bit
                 assert torch.equal(Ld[i], Wd[i].to(torch.bfloat16))
 
