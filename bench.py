@@ -1,0 +1,168 @@
+#!/usr/bin/env python3
+"""Benchmark of the layer training step on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch: forward, loss
+seed, backward, fused Adam of a BERT-base-shaped layer in bf16 AMP (inputs
+resident in HBM).  Prints ONE JSON line with the metric, a roofline object for
+the dominant kernel and the CPU oracle timed on the host cores.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload bert_base] [--no-cpu]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def gemm_launches(cfg):
+    """The dense contractions of one step as (name, M, N, K, a_kmajor, b_kmajor, out_f32, epilogue, batch)."""
+    B, S, H, F, nh = cfg["batch"], cfg["seq"], cfg["hidden"], cfg["ffn"], cfg["heads"]
+    T = B * S
+    z = B * nh
+    return [
+        ("qkv_fwd", T, 3 * H, H, 1, 1, 0, 1, 1), ("scores_fwd", S, S, 64, 1, 1, 0, 0, z),
+        ("context_fwd", S, 64, S, 1, 0, 0, 0, z), ("out_fwd", T, H, H, 1, 1, 0, 1, 1),
+        ("ffn1_fwd", T, F, H, 1, 1, 0, 2, 1), ("ffn2_fwd", T, H, F, 1, 1, 0, 1, 1),
+        ("ffn2_wgrad", H, F, T, 0, 0, 1, 0, 1), ("ffn2_dgrad", T, F, H, 1, 0, 0, 3, 1),
+        ("ffn1_wgrad", F, H, T, 0, 0, 1, 0, 1), ("ffn1_dgrad", T, H, F, 1, 0, 0, 0, 1),
+        ("out_wgrad", H, H, T, 0, 0, 1, 0, 1), ("out_dgrad", T, H, H, 1, 0, 0, 0, 1),
+        ("dprob", S, S, 64, 1, 1, 0, 0, z), ("dv", S, 64, S, 0, 0, 0, 0, z),
+        ("dq", S, 64, S, 1, 0, 0, 0, z), ("dk", S, 64, S, 0, 0, 0, 0, z),
+        ("qkv_wgrad", 3 * H, H, T, 0, 0, 1, 0, 1), ("qkv_dgrad", T, H, 3 * H, 1, 0, 0, 4, 1),
+    ]
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="bert_base")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline leg")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build is single-GPU by design (no collectives, no sharding); run with --gpus 1")
+
+    import numpy as np
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU; there is no CPU path for the library")
+    import paper_2303_04759_amd as raf
+    from paper_2303_04759_amd.harness import DeviceLayer
+    from workloads.synthetic import ADAM, CONFIGS, make_layer_inputs
+
+    cfg = CONFIGS[args.workload]
+    inp = make_layer_inputs(cfg, seed=0)
+    lay = DeviceLayer(cfg, inp, ADAM)
+    stream = torch.cuda.Stream()          # default priority
+    K, W = args.steps, args.warmup
+
+    with torch.cuda.stream(stream):
+        graph = None
+        t_step = 1
+        for _ in range(max(W, 1)):
+            lay.train_step(t_step, stream)
+            t_step += 1
+        stream.synchronize()
+        if not args.no_graph:
+            # one HIP graph of the whole step; replays re-run the same kernels on the same buffers
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                lay.train_step(t_step, stream)
+            for _ in range(3):
+                graph.replay()
+            stream.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record(stream)
+        for _ in range(K):
+            if graph is not None:
+                graph.replay()
+            else:
+                lay.train_step(t_step, stream)
+                t_step += 1
+        e1.record(stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        ms_per_step = e0.elapsed_time(e1) / K
+
+        # ---- roofline of the dominant kernel: the K-major x K-major bf16 MFMA GEMM instantiation
+        # (the four forward weight GEMMs), timed with events on the launch stream
+        dt = lay.cdtype
+        T, H, F = lay.T, cfg["hidden"], cfg["ffn"]
+        big = max(3 * H, F)
+        a_buf = torch.randn(T, big, device="cuda").to(dt)
+        w_buf = (0.02 * torch.randn(big, big, device="cuda")).to(dt)
+        c_buf = torch.empty(T, big, dtype=dt, device="cuda")
+        u_buf = torch.empty(T, big, dtype=dt, device="cuda")
+        bias = torch.zeros(big, device="cuda")
+        dom = [g for g in gemm_launches(cfg) if g[4] == 1 and g[5] == 1 and g[8] == 1]
+        reps = max(10, min(K, 50))
+
+        def run_dom():
+            for (_, M, N, Kd, ak, bk, of32, epi, _) in dom:
+                raf.raf_op_gemm(cfg["precision"], M, N, Kd, a_buf, Kd, 1, w_buf, Kd, 1, c_buf, N, epilogue=epi,
+                                bias=bias, aux=u_buf if epi == 2 else None, stream=stream)
+        for _ in range(3):
+            run_dom()
+        stream.synchronize()
+        e0.record(stream)
+        for _ in range(reps):
+            run_dom()
+        e1.record(stream)
+        stream.synchronize()
+        dom_ms = e0.elapsed_time(e1) / (reps * len(dom))
+        dom_flops = sum(2.0 * M * N * Kd for (_, M, N, Kd, *_r) in dom) / len(dom)
+        achieved = dom_flops / (dom_ms * 1e-3) / 1e12
+
+    samples_per_s = cfg["batch"] / (ms_per_step * 1e-3)
+    valid_tokens = int(np.sum(inp["seq_lens"])) if inp["seq_lens"] is not None else lay.T
+    total_flops = sum(2.0 * M * N * Kd * b for (_, M, N, Kd, _a, _b, _f, _e, b) in gemm_launches(cfg))
+    out = {
+        "metric": "train samples/sec, BERT-base layer fwd+bwd+Adam (bf16 AMP, 1 GPU)",
+        "value": samples_per_s, "unit": "samples/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg["precision"] == 1 else "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "batch": cfg["batch"], "seq_len": cfg["seq"], "hidden": cfg["hidden"],
+                   "heads": cfg["heads"], "ffn": cfg["ffn"], "dropout_p": cfg["dropout_p"],
+                   "launch": "eager" if graph is None else "hip_graph", "parallelism": "single GPU"},
+        "tokens_per_s_padded": lay.T / (ms_per_step * 1e-3),
+        "tokens_per_s_valid": valid_tokens / (ms_per_step * 1e-3),
+        "step_gemm_tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
+        "wall_ms_per_step": wall * 1e3 / K,
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel<128,128,K-major A,K-major B> (forward weight GEMMs)",
+                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "avg_launch_us": dom_ms * 1e3,
+                     "flops_per_launch": dom_flops, "traffic": None},
+    }
+    if not args.no_cpu:
+        from oracle.step import train_step
+        p = {k: v.astype(np.float64) for k, v in inp["params"].items()}
+        z = {k: np.zeros_like(v) for k, v in p.items()}
+        hyper = dict(ADAM, loss_scale=cfg["loss_scale"])
+        t0 = time.perf_counter()
+        train_step(cfg, p, z, z, inp["x"], inp["G"], inp["seq_lens"], 1, hyper)
+        dt_cpu = time.perf_counter() - t0
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+        except Exception:
+            threads = os.cpu_count()
+        out["cpu_baseline"] = {"value": cfg["batch"] / dt_cpu, "unit": "samples/s", "cores": threads,
+                               "kind": "oracle", "sample": "one full step (batch %d) of the same workload, numpy fp64, "
+                               "%.1f s" % (cfg["batch"], dt_cpu)}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

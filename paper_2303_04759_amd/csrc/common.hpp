@@ -151,12 +151,31 @@ __device__ __forceinline__ float group_max(float v) {
 }
 
 // ------------------------------------------------------------------- GeLU --
+// erf by the rational approximation 7.1.28 of Abramowitz & Stegun:
+// erf(x) = 1 - (1 + a1 x + ... + a6 x^6)^-16 for x >= 0, |error| <= 3e-7;
+// branch-free and about a third of the instructions of the library erff.
+__device__ __forceinline__ float erf_as(float x) {
+  const float ax = fabsf(x);
+  float p = 0.0000430638f;
+  p = fmaf(p, ax, 0.0002765672f);
+  p = fmaf(p, ax, 0.0001520143f);
+  p = fmaf(p, ax, 0.0092705272f);
+  p = fmaf(p, ax, 0.0422820123f);
+  p = fmaf(p, ax, 0.0705230784f);
+  p = fmaf(p, ax, 1.0f);
+  p = p * p;
+  p = p * p;
+  p = p * p;
+  p = p * p;
+  const float r = 1.0f - __frcp_rn(p);
+  return copysignf(r, x);
+}
 __device__ __forceinline__ float gelu_f(float u, int tanh_form) {
   if (tanh_form) {
     const float k = 0.7978845608028654f;
     return 0.5f * u * (1.0f + tanhf(k * (u + 0.044715f * u * u * u)));
   }
-  return 0.5f * u * (1.0f + erff(u * 0.7071067811865476f));
+  return 0.5f * u * (1.0f + erf_as(u * 0.7071067811865476f));
 }
 __device__ __forceinline__ float gelu_grad_f(float u, int tanh_form) {
   if (tanh_form) {
@@ -164,7 +183,7 @@ __device__ __forceinline__ float gelu_grad_f(float u, int tanh_form) {
     const float t = tanhf(k * (u + 0.044715f * u * u * u));
     return 0.5f * (1.0f + t) + 0.5f * u * (1.0f - t * t) * k * (1.0f + 0.134145f * u * u);
   }
-  const float Phi = 0.5f * (1.0f + erff(u * 0.7071067811865476f));
+  const float Phi = 0.5f * (1.0f + erf_as(u * 0.7071067811865476f));
   const float phi = 0.3989422804014327f * __expf(-0.5f * u * u);
   return Phi + u * phi;
 }

@@ -377,16 +377,34 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dout,
   for (int c = threadIdx.x; c < 3 * H; c += 256) partial[(long)blockIdx.x * 3 * H + c] = red[c];
 }
 
-// out_k[c] = sum_p partial[p][k][c], p ascending; k < nout
+// out_k[c] = sum_p partial[p][k][c], k < nout.  64 columns per block; the
+// four 64-lane slices of a block take parts p = slice, slice+4, ... and are
+// combined in a fixed order, so the sum is reproducible.
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int nparts, int ncols,
                                                               int nout, float* o0, float* o1, float* o2) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= ncols * nout) return;
-  float acc = 0.f;
-  for (int p = 0; p < nparts; ++p) acc += partial[(long)p * nout * ncols + c];
-  const int k = c / ncols, cc = c % ncols;
-  float* o = k == 0 ? o0 : (k == 1 ? o1 : o2);
-  if (o) o[cc] = acc;
+  __shared__ float red[4][64];
+  const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+  const int slice = threadIdx.x >> 6;
+  const long width = (long)nout * ncols;
+  float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+  if (c < width) {
+    int p = slice;
+    for (; p + 12 < nparts; p += 16) {
+      a0 += partial[(long)p * width + c];
+      a1 += partial[(long)(p + 4) * width + c];
+      a2 += partial[(long)(p + 8) * width + c];
+      a3 += partial[(long)(p + 12) * width + c];
+    }
+    for (; p < nparts; p += 4) a0 += partial[(long)p * width + c];
+  }
+  red[slice][threadIdx.x & 63] = (a0 + a1) + (a2 + a3);
+  __syncthreads();
+  if (slice == 0 && c < width) {
+    const float acc = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+    const int k = c / ncols, cc = c % ncols;
+    float* o = k == 0 ? o0 : (k == 1 ? o1 : o2);
+    if (o) o[cc] = acc;
+  }
 }
 
 // ------------------------------------------------------------ column sum --
@@ -554,7 +572,7 @@ raf_status launch_ln_bwd(const raf_layer_desc& d, int site, int64_t rows, const 
 #undef CALL
   raf_status rc = check_launch();
   if (rc != RAF_OK) return rc;
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3((3 * H + 255) / 256), dim3(256), 0, st, partial, nb, H, 3,
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((3 * H + 63) / 64), dim3(256), 0, st, partial, nb, H, 3,
                      gamma ? dgamma : nullptr, gamma ? dbeta : nullptr, da ? dbias : nullptr);
   return check_launch();
 }
@@ -580,7 +598,7 @@ raf_status launch_colsum(int precision, const void* x, int64_t rows, int cols, l
                        partial);
   raf_status rc = check_launch();
   if (rc != RAF_OK) return rc;
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3((cols + 255) / 256), dim3(256), 0, st, partial, parts, cols, 1, out,
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((cols + 63) / 64), dim3(256), 0, st, partial, parts, cols, 1, out,
                      nullptr, nullptr);
   return check_launch();
 }

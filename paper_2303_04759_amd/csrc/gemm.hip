@@ -4,60 +4,23 @@
 // (bias, bias+GeLU with saved pre-activation, GeLU-gradient multiply, residual
 // add, scale, fp32 output).  Pattern-based "GEMM + elementwise epilogue"
 // fusion in the sense of the paper's Section 3.2.2.
-#include "common.hpp"
+#include "gemm_device.hpp"
 
 namespace raf {
 
-struct GemmDev {
-  int M, N, K;
-  const void* a; long lda;
-  const void* b; long ldb;
-  void* c; long ldc;
-  float alpha;
-  int epilogue;
-  const float* bias;
-  void* aux; long ldaux;
-  int gelu_tanh;
-  int nz_inner;
-  long sa0, sa1, sb0, sb1, sc0, sc1;
-};
-
-template <typename TC, typename TAUX>
-__device__ __forceinline__ void epilogue_store(const GemmDev& g, TC* __restrict__ c, TAUX* __restrict__ aux, int i,
-                                               int j, float acc) {
-  float v = acc * g.alpha;
-  switch (g.epilogue) {
-    case EPI_BIAS:
-      v += g.bias[j];
-      break;
-    case EPI_BIAS_GELU: {
-      v += g.bias[j];
-      aux[(long)i * g.ldaux + j] = (TAUX)v;
-      // GeLU is evaluated on the value the backward pass will read back
-      v = gelu_f((float)(TAUX)v, g.gelu_tanh);
-      break;
-    }
-    case EPI_MUL_GELU_GRAD:
-      v *= gelu_grad_f((float)aux[(long)i * g.ldaux + j], g.gelu_tanh);
-      break;
-    case EPI_ADD_RES:
-      v += (float)aux[(long)i * g.ldaux + j];
-      break;
-    default:
-      break;
-  }
-  c[(long)i * g.ldc + j] = (TC)v;
-}
-
 // ------------------------------------------------------------- bf16 MFMA --
 constexpr int BK = 64;          // k extent of one LDS stage
-constexpr int KPAD = 8;         // bf16 elements of row padding (16 B)
 
-// Operand tile in LDS.  K-major operands are kept [row][BK+KPAD]; operands
-// whose rows are contiguous in memory (MN-major) are kept [k][ROWS+KPAD].
+// Operand tile in LDS.
+//  K-major operands (contraction index contiguous in memory) are kept
+//  [row][BK+8]: the 16-byte pad makes the 128-bit fragment reads conflict-free.
+//  MN-major operands (row index contiguous in memory, i.e. the operand arrives
+//  transposed) are kept [k][ROWS+32] and read with the transposing LDS load
+//  ds_read_b64_tr_b16; a pitch of 16 dwords modulo 32 spreads the four k-rows a
+//  16-lane group touches over distinct banks.
 template <int ROWS, bool KMAJOR>
 struct TileLds {
-  static constexpr int PITCH = KMAJOR ? (BK + KPAD) : (ROWS + KPAD);
+  static constexpr int PITCH = KMAJOR ? (BK + 8) : (ROWS + 32);
   static constexpr int ELEMS = KMAJOR ? ROWS * PITCH : BK * PITCH;
   static constexpr int VEC_PER_THREAD = ROWS * BK / 8 / 256;
 };
@@ -102,24 +65,35 @@ __device__ __forceinline__ void tile_store_lds(bf16_t* lds, const uint4 (&reg)[T
 
 // MFMA operand fragment for 32 rows starting at `row` and the 16 k values of
 // sub-step kk: lane l supplies row (l & 31), k = kk*16 + (l >> 5)*8 + 0..7.
+//
+// Transposing read (measured lane layout of ds_read_b64_tr_b16): inside each
+// group of 16 lanes, lane s points at 4 consecutive 16-bit elements and lane t
+// receives element (t & 3) of lanes (t >> 2), 4 + (t >> 2), 8 + (t >> 2),
+// 12 + (t >> 2).  With lane s pointing at k-row (s >> 2), columns 4*(s & 3)..+3
+// of a [k][row] tile, lane t ends up with 4 consecutive k of column t.
 template <int ROWS, bool KMAJOR>
 __device__ __forceinline__ bf16x8_t tile_fragment(const bf16_t* lds, int row, int kk) {
   constexpr int PITCH = TileLds<ROWS, KMAJOR>::PITCH;
   const int lane = threadIdx.x & 63;
-  const int r = row + (lane & 31);
-  const int k = kk * 16 + (lane >> 5) * 8;
   if (KMAJOR) {
+    const int r = row + (lane & 31);
+    const int k = kk * 16 + (lane >> 5) * 8;
     return *reinterpret_cast<const bf16x8_t*>(lds + r * PITCH + k);
   } else {
-    bf16x8_t f;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) f[e] = lds[(k + e) * PITCH + r];
-    return f;
+    const int grp = lane >> 4, s = lane & 15;
+    const int k = kk * 16 + (grp >> 1) * 8 + (s >> 2);
+    const int col = row + (grp & 1) * 16 + (s & 3) * 4;
+    typedef s16x4_t __attribute__((address_space(3))) * lds_v4_ptr;
+    const bf16_t* p = lds + k * PITCH + col;
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4_ptr)(p));
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4_ptr)(p + 4 * PITCH));
+    const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8_t, both);
   }
 }
 
 template <int BM, int BN, bool A_KMAJOR, bool B_KMAJOR, typename TC>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmDev g) {
+__global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(GemmDev g) {
   constexpr int WM = BM / 2, WN = BN / 2;   // 2 x 2 waves
   constexpr int TM = WM / 32, TN = WN / 32;
   typedef TileLds<BM, A_KMAJOR> LA;
@@ -166,29 +140,34 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmDev g) {
       for (int i = 0; i < TM; ++i) fa[i] = tile_fragment<BM, A_KMAJOR>(lds_a, wm + i * 32, kk);
 #pragma unroll
       for (int j = 0; j < TN; ++j) fb[j] = tile_fragment<BN, B_KMAJOR>(lds_b, wn + j * 32, kk);
+      // operands swapped: the MFMA produces the transposed 32x32 block, so that
+      // a lane ends up with 4 consecutive output columns per register group
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
     }
   }
 
-  // accumulator layout of the 32x32 MFMA: register r of lane l holds
-  // row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+  // accumulator layout of the (transposed) 32x32 block: register r of lane l
+  // holds output row (l & 31), column 8*(r/4) + 4*(l/32) + r%4.
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+  for (int i = 0; i < TM; ++i) {
+    const int row = m0 + wm + i * 32 + (lane & 31);
+    if (row < g.M) {
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int col = n0 + wn + j * 32 + (lane & 31);
-      if (col < g.N) {
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = m0 + wm + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-          if (row < g.M) epilogue_store<TC, bf16_t>(g, C, AUX, row, col, acc[i][j][r]);
+        for (int q = 0; q < 4; ++q) {
+          const int col = n0 + wn + j * 32 + 8 * q + 4 * (lane >> 5);
+          if (col < g.N) {
+            float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+            epilogue_store4<TC>(g, C, AUX, row, col, v);
+          }
         }
-      }
     }
+  }
 }
 
 // -------------------------------------------------------------- fp32 FMA --
@@ -281,6 +260,7 @@ raf_status launch_gemm(int precision, const GemmArgs& g, hipStream_t st) {
     const long sb_k = g.b_kmajor ? 1 : g.ldb, sb_j = g.b_kmajor ? g.ldb : 1;
     hipLaunchKernelGGL(gemm_f32_kernel, grid, dim3(256), 0, st, d, sa_i, sa_k, sb_k, sb_j);
   } else if (precision == RAF_BF16_AMP) {
+    if (launch_gemm_pipe(d, g.a_kmajor, g.b_kmajor, g.out_f32, g.batch, st)) return check_launch();
     if (g.a_kmajor && g.b_kmajor) launch_bf16_layout<true, true>(d, g.out_f32, g.batch, st);
     else if (g.a_kmajor && !g.b_kmajor) launch_bf16_layout<true, false>(d, g.out_f32, g.batch, st);
     else if (!g.a_kmajor && !g.b_kmajor) launch_bf16_layout<false, false>(d, g.out_f32, g.batch, st);

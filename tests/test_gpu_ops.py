@@ -43,7 +43,8 @@ def test_dropout_mask_bit_exact(site, n, p, step):
 
 
 # ------------------------------------------------------------------- gemm --
-GEMM_SHAPES = [(32, 32, 32), (64, 96, 64), (160, 224, 96), (256, 128, 192), (128, 64, 128), (416, 320, 64)]
+GEMM_SHAPES = [(32, 32, 32), (64, 96, 64), (160, 224, 96), (256, 128, 192), (128, 64, 128), (416, 320, 64),
+               (256, 384, 768), (160, 96, 320), (384, 64, 512)]
 
 
 @pytest.mark.parametrize("precision", [0, 1])
