@@ -216,6 +216,8 @@ inline GemmArgs gemm_args_default() {
 }
 
 raf_status launch_gemm(int precision, const GemmArgs& g, hipStream_t st);
+// up to 4 independent weight-gradient GEMMs (A, B MN-major, float out) in one launch
+raf_status launch_gemm_group_wgrad(int precision, const GemmArgs* gs, int count, hipStream_t st);
 
 raf_status launch_softmax_fwd(const raf_layer_desc& d, const void* s, const int32_t* lens, void* prob, void* prob_d,
                               uint64_t step, hipStream_t st);

@@ -18,21 +18,22 @@ constexpr int BK = 64;          // k extent of one LDS stage
 //  transposed) are kept [k][ROWS+32] and read with the transposing LDS load
 //  ds_read_b64_tr_b16; a pitch of 16 dwords modulo 32 spreads the four k-rows a
 //  16-lane group touches over distinct banks.
-template <int ROWS, bool KMAJOR>
+template <int ROWS, bool KMAJOR, int NTHREADS>
 struct TileLds {
   static constexpr int PITCH = KMAJOR ? (BK + 8) : (ROWS + 32);
   static constexpr int ELEMS = KMAJOR ? ROWS * PITCH : BK * PITCH;
-  static constexpr int VEC_PER_THREAD = ROWS * BK / 8 / 256;
+  static constexpr int VEC_PER_THREAD = ROWS * BK / 8 / NTHREADS;
+  static_assert(VEC_PER_THREAD >= 1, "tile too small for the workgroup");
 };
 
-template <int ROWS, bool KMAJOR>
+template <int ROWS, bool KMAJOR, int NTHREADS>
 __device__ __forceinline__ void tile_load_global(const bf16_t* __restrict__ base, long ld, int row0, int nrows, int k0,
-                                                 int K, uint4 (&reg)[TileLds<ROWS, KMAJOR>::VEC_PER_THREAD]) {
-  constexpr int NV = TileLds<ROWS, KMAJOR>::VEC_PER_THREAD;
+                                                 int K, uint4 (&reg)[TileLds<ROWS, KMAJOR, NTHREADS>::VEC_PER_THREAD]) {
+  constexpr int NV = TileLds<ROWS, KMAJOR, NTHREADS>::VEC_PER_THREAD;
   const int tid = threadIdx.x;
 #pragma unroll
   for (int t = 0; t < NV; ++t) {
-    const int v = tid + t * 256;
+    const int v = tid + t * NTHREADS;
     if (KMAJOR) {
       int r = row0 + v / (BK / 8);
       r = r < nrows ? r : nrows - 1;
@@ -47,14 +48,15 @@ __device__ __forceinline__ void tile_load_global(const bf16_t* __restrict__ base
   }
 }
 
-template <int ROWS, bool KMAJOR>
-__device__ __forceinline__ void tile_store_lds(bf16_t* lds, const uint4 (&reg)[TileLds<ROWS, KMAJOR>::VEC_PER_THREAD]) {
-  constexpr int NV = TileLds<ROWS, KMAJOR>::VEC_PER_THREAD;
-  constexpr int PITCH = TileLds<ROWS, KMAJOR>::PITCH;
+template <int ROWS, bool KMAJOR, int NTHREADS>
+__device__ __forceinline__ void tile_store_lds(bf16_t* lds,
+                                               const uint4 (&reg)[TileLds<ROWS, KMAJOR, NTHREADS>::VEC_PER_THREAD]) {
+  constexpr int NV = TileLds<ROWS, KMAJOR, NTHREADS>::VEC_PER_THREAD;
+  constexpr int PITCH = TileLds<ROWS, KMAJOR, NTHREADS>::PITCH;
   const int tid = threadIdx.x;
 #pragma unroll
   for (int t = 0; t < NV; ++t) {
-    const int v = tid + t * 256;
+    const int v = tid + t * NTHREADS;
     if (KMAJOR) {
       *reinterpret_cast<uint4*>(lds + (v / (BK / 8)) * PITCH + (v % (BK / 8)) * 8) = reg[t];
     } else {
@@ -71,9 +73,8 @@ __device__ __forceinline__ void tile_store_lds(bf16_t* lds, const uint4 (&reg)[T
 // receives element (t & 3) of lanes (t >> 2), 4 + (t >> 2), 8 + (t >> 2),
 // 12 + (t >> 2).  With lane s pointing at k-row (s >> 2), columns 4*(s & 3)..+3
 // of a [k][row] tile, lane t ends up with 4 consecutive k of column t.
-template <int ROWS, bool KMAJOR>
+template <int PITCH, bool KMAJOR>
 __device__ __forceinline__ bf16x8_t tile_fragment(const bf16_t* lds, int row, int kk) {
-  constexpr int PITCH = TileLds<ROWS, KMAJOR>::PITCH;
   const int lane = threadIdx.x & 63;
   if (KMAJOR) {
     const int r = row + (lane & 31);
@@ -92,25 +93,26 @@ __device__ __forceinline__ bf16x8_t tile_fragment(const bf16_t* lds, int row, in
   }
 }
 
-template <int BM, int BN, bool A_KMAJOR, bool B_KMAJOR, typename TC>
-__global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(GemmDev g) {
-  constexpr int WM = BM / 2, WN = BN / 2;   // 2 x 2 waves
+// One BM x BN output tile of problem g (batch index z) by a workgroup of
+// WGM x WGN wavefronts: operand tiles are staged global -> registers -> LDS
+// with the next k-step's global loads in flight during the MFMAs.
+template <int BM, int BN, int WGM, int WGN, bool A_KMAJOR, bool B_KMAJOR, typename TC>
+__device__ __forceinline__ void staged_tile(const GemmDev& g, int m0, int n0, int z, bf16_t* lds_a, bf16_t* lds_b) {
+  constexpr int NTHREADS = 64 * WGM * WGN;
+  constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
-  typedef TileLds<BM, A_KMAJOR> LA;
-  typedef TileLds<BN, B_KMAJOR> LB;
-  __shared__ __attribute__((aligned(16))) bf16_t lds_a[LA::ELEMS];
-  __shared__ __attribute__((aligned(16))) bf16_t lds_b[LB::ELEMS];
+  static_assert(TM >= 1 && TN >= 1, "wave tile below one MFMA block");
+  typedef TileLds<BM, A_KMAJOR, NTHREADS> LA;
+  typedef TileLds<BN, B_KMAJOR, NTHREADS> LB;
 
-  const int z = blockIdx.z;
   const int zb = z / g.nz_inner, zi = z % g.nz_inner;
   const bf16_t* __restrict__ A = (const bf16_t*)g.a + zb * g.sa0 + zi * g.sa1;
   const bf16_t* __restrict__ B = (const bf16_t*)g.b + zb * g.sb0 + zi * g.sb1;
   TC* __restrict__ C = (TC*)g.c + zb * g.sc0 + zi * g.sc1;
   bf16_t* __restrict__ AUX = g.aux ? (bf16_t*)g.aux + zb * g.sc0 + zi * g.sc1 : nullptr;
 
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int wm = (wave >> 1) * WM, wn = (wave & 1) * WN;
+  const int wm = (wave / WGN) * WM, wn = (wave % WGN) * WN;
 
   f32x16_t acc[TM][TN];
 #pragma unroll
@@ -121,32 +123,40 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(GemmDev g) {
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   uint4 ra[LA::VEC_PER_THREAD], rb[LB::VEC_PER_THREAD];
-  tile_load_global<BM, A_KMAJOR>(A, g.lda, m0, g.M, 0, g.K, ra);
-  tile_load_global<BN, B_KMAJOR>(B, g.ldb, n0, g.N, 0, g.K, rb);
+  tile_load_global<BM, A_KMAJOR, NTHREADS>(A, g.lda, m0, g.M, 0, g.K, ra);
+  tile_load_global<BN, B_KMAJOR, NTHREADS>(B, g.ldb, n0, g.N, 0, g.K, rb);
 
   for (int k0 = 0; k0 < g.K; k0 += BK) {
     __syncthreads();   // previous stage fully consumed
-    tile_store_lds<BM, A_KMAJOR>(lds_a, ra);
-    tile_store_lds<BN, B_KMAJOR>(lds_b, rb);
+    tile_store_lds<BM, A_KMAJOR, NTHREADS>(lds_a, ra);
+    tile_store_lds<BN, B_KMAJOR, NTHREADS>(lds_b, rb);
     __syncthreads();
     if (k0 + BK < g.K) {
-      tile_load_global<BM, A_KMAJOR>(A, g.lda, m0, g.M, k0 + BK, g.K, ra);
-      tile_load_global<BN, B_KMAJOR>(B, g.ldb, n0, g.N, k0 + BK, g.K, rb);
+      tile_load_global<BM, A_KMAJOR, NTHREADS>(A, g.lda, m0, g.M, k0 + BK, g.K, ra);
+      tile_load_global<BN, B_KMAJOR, NTHREADS>(B, g.ldb, n0, g.N, k0 + BK, g.K, rb);
     }
+    // fragment loads run one sub-step ahead of the MFMAs that consume them
+    bf16x8_t fa[2][TM], fb[2][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[0][i] = tile_fragment<LA::PITCH, A_KMAJOR>(lds_a, wm + i * 32, 0);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[0][j] = tile_fragment<LB::PITCH, B_KMAJOR>(lds_b, wn + j * 32, 0);
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8_t fa[TM], fb[TN];
+      const int cur = kk & 1, nx = cur ^ 1;
+      if (kk + 1 < BK / 16) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i) fa[i] = tile_fragment<BM, A_KMAJOR>(lds_a, wm + i * 32, kk);
+        for (int i = 0; i < TM; ++i) fa[nx][i] = tile_fragment<LA::PITCH, A_KMAJOR>(lds_a, wm + i * 32, kk + 1);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) fb[j] = tile_fragment<BN, B_KMAJOR>(lds_b, wn + j * 32, kk);
+        for (int j = 0; j < TN; ++j) fb[nx][j] = tile_fragment<LB::PITCH, B_KMAJOR>(lds_b, wn + j * 32, kk + 1);
+      }
       // operands swapped: the MFMA produces the transposed 32x32 block, so that
       // a lane ends up with 4 consecutive output columns per register group
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[cur][j], fa[cur][i], acc[i][j], 0, 0, 0);
     }
   }
 
@@ -168,6 +178,55 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(GemmDev g) {
         }
     }
   }
+}
+
+// Consecutive workgroup ids are dealt round-robin to the 8 XCDs (each with its
+// own L2).  Give XCD x the contiguous range [x*per, (x+1)*per) of the row-major
+// tile list, so that tiles sharing A rows / B columns meet in one L2.
+__device__ __forceinline__ int xcd_tile(int block, int ntile) {
+  const int per = (ntile + 7) >> 3;
+  return (block & 7) * per + (block >> 3);
+}
+
+template <int BM, int BN, int WGM, int WGN, bool A_KMAJOR, bool B_KMAJOR, typename TC>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev g, int tiles_m, int tiles_n, int remap) {
+  constexpr int NTHREADS = 64 * WGM * WGN;
+  __shared__ __attribute__((aligned(16))) bf16_t lds_a[TileLds<BM, A_KMAJOR, NTHREADS>::ELEMS];
+  __shared__ __attribute__((aligned(16))) bf16_t lds_b[TileLds<BN, B_KMAJOR, NTHREADS>::ELEMS];
+  const int ntile = tiles_m * tiles_n;
+  const int t = remap ? xcd_tile(blockIdx.x, ntile) : (int)blockIdx.x;
+  if (t >= ntile) return;
+  staged_tile<BM, BN, WGM, WGN, A_KMAJOR, B_KMAJOR, TC>(g, (t / tiles_n) * BM, (t % tiles_n) * BN, blockIdx.y, lds_a,
+                                                          lds_b);
+}
+
+// Several independent problems of one layout in a single launch (the four
+// weight-gradient GEMMs of a layer: each alone has too few tiles to fill the
+// chip).  tile_start[p] is the first linear tile of problem p.
+constexpr int GEMM_GROUP_MAX = 4;
+struct GemmGroupDev {
+  GemmDev p[GEMM_GROUP_MAX];
+  int tile_start[GEMM_GROUP_MAX + 1];
+  int tiles_n[GEMM_GROUP_MAX];
+  int count;
+};
+
+template <int BM, int BN, int WGM, int WGN, bool A_KMAJOR, bool B_KMAJOR, typename TC>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_group_kernel(GemmGroupDev grp) {
+  constexpr int NTHREADS = 64 * WGM * WGN;
+  __shared__ __attribute__((aligned(16))) bf16_t lds_a[TileLds<BM, A_KMAJOR, NTHREADS>::ELEMS];
+  __shared__ __attribute__((aligned(16))) bf16_t lds_b[TileLds<BN, B_KMAJOR, NTHREADS>::ELEMS];
+  const int ntile = grp.tile_start[grp.count];
+  const int t = xcd_tile(blockIdx.x, ntile);
+  if (t >= ntile) return;
+  int p = 0;
+#pragma unroll
+  for (int q = 1; q < GEMM_GROUP_MAX; ++q)
+    if (q < grp.count && t >= grp.tile_start[q]) p = q;
+  const int lt = t - grp.tile_start[p];
+  const int tn = grp.tiles_n[p];
+  // the problem descriptor is selected with wave-uniform scalar loads
+  staged_tile<BM, BN, WGM, WGN, A_KMAJOR, B_KMAJOR, TC>(grp.p[p], (lt / tn) * BM, (lt % tn) * BN, 0, lds_a, lds_b);
 }
 
 // -------------------------------------------------------------- fp32 FMA --
@@ -219,26 +278,41 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmDev g, long sa_i, lon
 }
 
 // ---------------------------------------------------------------- launch --
-template <int BM, int BN, bool AK, bool BKM>
+template <int BM, int BN, int WGM, int WGN, bool AK, bool BKM>
 static void launch_bf16_tile(const GemmDev& d, int out_f32, int batch, hipStream_t st) {
-  dim3 grid((d.N + BN - 1) / BN, (d.M + BM - 1) / BM, batch);
+  const int tiles_m = (d.M + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
+  const int ntile = tiles_m * tiles_n;
+  const int remap = (batch == 1 && ntile >= 64) ? 1 : 0;   // XCD-aware order only pays for one large problem
+  dim3 grid(remap ? ((ntile + 7) / 8) * 8 : ntile, batch);
+  dim3 block(64 * WGM * WGN);
   if (out_f32)
-    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, AK, BKM, float>), grid, dim3(256), 0, st, d);
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WGM, WGN, AK, BKM, float>), grid, block, 0, st, d, tiles_m, tiles_n,
+                       remap);
   else
-    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, AK, BKM, bf16_t>), grid, dim3(256), 0, st, d);
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WGM, WGN, AK, BKM, bf16_t>), grid, block, 0, st, d, tiles_m, tiles_n,
+                       remap);
+}
+
+// Few tiles: one workgroup per CU at most, so use 8 wavefronts per workgroup
+// (2 per SIMD) to overlap LDS/global latency with MFMA inside the workgroup.
+static bool few_tiles(const GemmDev& d, int batch) {
+  const long tiles = (long)((d.M + 127) / 128) * ((d.N + 127) / 128) * batch;
+  return tiles < 384;
 }
 
 template <bool AK, bool BKM>
 static void launch_bf16_layout(const GemmDev& d, int out_f32, int batch, hipStream_t st) {
   if (d.M <= 64 && d.N <= 64)
-    launch_bf16_tile<64, 64, AK, BKM>(d, out_f32, batch, st);
+    launch_bf16_tile<64, 64, 2, 2, AK, BKM>(d, out_f32, batch, st);
   else if (d.N <= 64)
-    launch_bf16_tile<128, 64, AK, BKM>(d, out_f32, batch, st);
+    launch_bf16_tile<128, 64, 2, 2, AK, BKM>(d, out_f32, batch, st);
+  else if (few_tiles(d, batch))
+    launch_bf16_tile<128, 128, 2, 4, AK, BKM>(d, out_f32, batch, st);
   else
-    launch_bf16_tile<128, 128, AK, BKM>(d, out_f32, batch, st);
+    launch_bf16_tile<128, 128, 2, 2, AK, BKM>(d, out_f32, batch, st);
 }
 
-raf_status launch_gemm(int precision, const GemmArgs& g, hipStream_t st) {
+static raf_status check_gemm_args(const GemmArgs& g) {
   if (g.M <= 0 || g.N <= 0 || g.K <= 0 || g.batch <= 0 || g.nz_inner <= 0) return RAF_EINVAL;
   if ((g.M % 32) || (g.N % 32) || (g.K % 32)) return RAF_ENOTSUP;
   if (!g.a || !g.b || !g.c) return RAF_EINVAL;
@@ -248,12 +322,60 @@ raf_status launch_gemm(int precision, const GemmArgs& g, hipStream_t st) {
   if (g.epilogue < 0 || g.epilogue > EPI_ADD_RES) return RAF_EINVAL;
   if ((g.lda % 8) || (g.ldb % 8) || (g.ldc % 8) || (g.aux && (g.ldaux % 8))) return RAF_EINVAL;
   if (g.batch > 65535) return RAF_ENOTSUP;
+  return RAF_OK;
+}
+
+static GemmDev to_dev(const GemmArgs& g) {
   GemmDev d;
   d.M = g.M; d.N = g.N; d.K = g.K;
   d.a = g.a; d.lda = g.lda; d.b = g.b; d.ldb = g.ldb; d.c = g.c; d.ldc = g.ldc;
   d.alpha = g.alpha; d.epilogue = g.epilogue; d.bias = g.bias; d.aux = g.aux; d.ldaux = g.ldaux;
   d.gelu_tanh = g.gelu_tanh; d.nz_inner = g.nz_inner;
   d.sa0 = g.sa[0]; d.sa1 = g.sa[1]; d.sb0 = g.sb[0]; d.sb1 = g.sb[1]; d.sc0 = g.sc[0]; d.sc1 = g.sc[1];
+  return d;
+}
+
+// Weight-gradient form only: A and B both MN-major, float output, no batch.
+raf_status launch_gemm_group_wgrad(int precision, const GemmArgs* gs, int count, hipStream_t st) {
+  if (count <= 0 || count > GEMM_GROUP_MAX || !gs) return RAF_EINVAL;
+  bool groupable = precision == RAF_BF16_AMP;
+  for (int i = 0; i < count; ++i) {
+    raf_status rc = check_gemm_args(gs[i]);
+    if (rc != RAF_OK) return rc;
+    if (gs[i].a_kmajor || gs[i].b_kmajor || !gs[i].out_f32 || gs[i].batch != 1 || gs[i].epilogue != EPI_NONE ||
+        gs[i].M < 128 || gs[i].N < 128)
+      groupable = false;
+  }
+  if (!groupable) {
+    for (int i = 0; i < count; ++i) {
+      raf_status rc = launch_gemm(precision, gs[i], st);
+      if (rc != RAF_OK) return rc;
+    }
+    return RAF_OK;
+  }
+  GemmGroupDev grp;
+  grp.count = count;
+  int tiles = 0;
+  for (int i = 0; i < count; ++i) {
+    grp.p[i] = to_dev(gs[i]);
+    grp.tile_start[i] = tiles;
+    grp.tiles_n[i] = (gs[i].N + 127) / 128;
+    tiles += ((gs[i].M + 127) / 128) * grp.tiles_n[i];
+  }
+  for (int i = count; i <= GEMM_GROUP_MAX; ++i) grp.tile_start[i] = tiles;
+  for (int i = count; i < GEMM_GROUP_MAX; ++i) { grp.p[i] = grp.p[0]; grp.tiles_n[i] = 1; }
+  dim3 grid(((tiles + 7) / 8) * 8);
+  if (tiles < 384)
+    hipLaunchKernelGGL((gemm_bf16_group_kernel<128, 128, 2, 4, false, false, float>), grid, dim3(512), 0, st, grp);
+  else
+    hipLaunchKernelGGL((gemm_bf16_group_kernel<128, 128, 2, 2, false, false, float>), grid, dim3(256), 0, st, grp);
+  return check_launch();
+}
+
+raf_status launch_gemm(int precision, const GemmArgs& g, hipStream_t st) {
+  raf_status rc = check_gemm_args(g);
+  if (rc != RAF_OK) return rc;
+  const GemmDev d = to_dev(g);
   if (precision == RAF_F32) {
     dim3 grid((g.N + 63) / 64, (g.M + 63) / 64, g.batch);
     const long sa_i = g.a_kmajor ? g.lda : 1, sa_k = g.a_kmajor ? 1 : g.lda;

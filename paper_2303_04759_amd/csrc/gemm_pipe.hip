@@ -237,7 +237,7 @@ static bool launch_pipe_layout(const GemmDev& d, int batch, hipStream_t st) {
 
 bool launch_gemm_pipe(const GemmDev& d, int a_kmajor, int b_kmajor, int out_f32, int batch, hipStream_t st) {
   if (d.K % PBK) return false;
-  if (d.M < 128 || d.N < 128) return false;
+  if (d.M < 128 || d.N < 128 || batch != 1) return false;
   // measured on MI355X: the direct-to-LDS ring wins for K-major x K-major
   // operands; with a transposed operand the register-staged kernel is faster
   if (!(a_kmajor && b_kmajor)) return false;

@@ -45,7 +45,7 @@ struct Plan {
   // scratch, forward
   size_t s, a;
   // scratch, backward
-  size_t dz2, da, du, dffn, dz1, dc, dprob_d, ds, dqkv, dattn, partial;
+  size_t dz2, da, da1, du, dffn, dz1, dc, dprob_d, ds, dqkv, dattn, partial;
   size_t scratch_bytes;
 };
 
@@ -84,6 +84,7 @@ static Plan make_plan(const raf_layer_desc& d) {
   size_t b = 0;
   p.dz2 = bump(b, TH);
   p.da = bump(b, TH);
+  p.da1 = bump(b, TH);
   p.du = bump(b, TF);
   p.dffn = bump(b, TH);
   p.dz1 = bump(b, TH);
@@ -129,6 +130,16 @@ static raf_status gemm(int prec, hipStream_t st, int M, int N, int K, const void
   g.c = c; g.ldc = ldc; g.out_f32 = out_f32;
   g.epilogue = epi; g.bias = bias; g.aux = aux; g.ldaux = ldaux; g.gelu_tanh = gelu_tanh;
   return launch_gemm(prec, g, st);
+}
+
+// weight-gradient form: C[M,N] (float) = A^T B with A [K,M], B [K,N] row-major
+static GemmArgs wgrad_args(int M, int N, int K, const void* a, long lda, const void* b, long ldb, void* c, long ldc) {
+  GemmArgs g = gemm_args_default();
+  g.M = M; g.N = N; g.K = K;
+  g.a = a; g.lda = lda; g.a_kmajor = 0;
+  g.b = b; g.ldb = ldb; g.b_kmajor = 0;
+  g.c = c; g.ldc = ldc; g.out_f32 = 1;
+  return g;
 }
 
 // per-(batch, head) GEMM over views of [T, ld] tensors (64 columns per head)
@@ -266,7 +277,8 @@ extern "C" raf_status raf_layer_bwd(const raf_layer_desc* desc, const raf_layer_
   const float* rstd2 = (const float*)at(saved, p.rstd2);
 
   void* dz2 = at(scratch, p.dz2);
-  void* da = at(scratch, p.da);
+  void* da = at(scratch, p.da);     // da2, kept until the grouped weight-gradient launch
+  void* da1 = at(scratch, p.da1);
   void* du = at(scratch, p.du);
   void* dffn = at(scratch, p.dffn);
   void* dz1 = at(scratch, p.dz1);
@@ -284,23 +296,22 @@ extern "C" raf_status raf_layer_bwd(const raf_layer_desc* desc, const raf_layer_
   else            // y = LN2(z2), z2 = ffn_in + drop3(a2)
     RAF_TRY(launch_ln_bwd(d, 3, T, dy, nullptr, z2, mu2, rstd2, (const float*)w->ln2_g, nullptr, dz2, da,
                           (float*)grads->ln2_g, (float*)grads->ln2_b, (float*)grads->b_2, partial, step, st));
-  // B8: a2 = g W2^T + b2  ->  dW2 = da2^T g ; du = (da2 W2) * gelu'(u)
-  RAF_TRY(gemm(prec, st, H, F, T, da, H, 0, g, F, 0, grads->w_2, F, 1));
+  // The four weight gradients (dW = dY^T X) are deferred to one grouped launch
+  // at the end: each alone has too few output tiles to fill 256 CUs.
+  // B8: a2 = g W2^T + b2  ->  du = (da2 W2) * gelu'(u)      [dW2 = da2^T g deferred]
   RAF_TRY(gemm(prec, st, T, F, H, da, H, 1, w->w_2, F, 0, du, F, 0, EPI_MUL_GELU_GRAD, nullptr, u, F, d.gelu_tanh));
-  // B7: u = ffn_in W1^T + b1  ->  dW1 = du^T ffn_in ; db1 ; dffn = du W1
-  RAF_TRY(gemm(prec, st, F, H, T, du, F, 0, ffn_in, H, 0, grads->w_1, H, 1));
+  // B7: u = ffn_in W1^T + b1  ->  db1 ; dffn = du W1          [dW1 = du^T ffn_in deferred]
   RAF_TRY(launch_colsum(prec, du, T, F, F, (float*)grads->b_1, partial, st));
   RAF_TRY(gemm(prec, st, T, H, F, du, F, 1, w->w_1, H, 0, dffn, H));
   // B6: the LayerNorm between the two halves, the residual, dropout site 2
   if (d.pre_ln)   // ffn_in = LN2(z1); dz1 = dy + LN2'(dffn); da1 = dz1 * keep2/(1-p)
-    RAF_TRY(launch_ln_bwd(d, 2, T, dffn, nullptr, z1, mu2, rstd2, (const float*)w->ln2_g, dy, dz1, da,
+    RAF_TRY(launch_ln_bwd(d, 2, T, dffn, nullptr, z1, mu2, rstd2, (const float*)w->ln2_g, dy, dz1, da1,
                           (float*)grads->ln2_g, (float*)grads->ln2_b, (float*)grads->b_o, partial, step, st));
   else            // ffn_in = LN1(z1) feeds the ffn and the residual: g_in = dz2 + dffn
-    RAF_TRY(launch_ln_bwd(d, 2, T, dz2, dffn, z1, mu1, rstd1, (const float*)w->ln1_g, nullptr, dz1, da,
+    RAF_TRY(launch_ln_bwd(d, 2, T, dz2, dffn, z1, mu1, rstd1, (const float*)w->ln1_g, nullptr, dz1, da1,
                           (float*)grads->ln1_g, (float*)grads->ln1_b, (float*)grads->b_o, partial, step, st));
-  // B5: a1 = c Wo^T + bo  ->  dWo = da1^T c ; dc = da1 Wo
-  RAF_TRY(gemm(prec, st, H, H, T, da, H, 0, c, H, 0, grads->w_o, H, 1));
-  RAF_TRY(gemm(prec, st, T, H, H, da, H, 1, w->w_o, H, 0, dc, H));
+  // B5: a1 = c Wo^T + bo  ->  dc = da1 Wo                   [dWo = da1^T c deferred]
+  RAF_TRY(gemm(prec, st, T, H, H, da1, H, 1, w->w_o, H, 0, dc, H));
   // B4: c = prob_d V  ->  dprob_d = dc V^T ; dV = prob_d^T dc
   RAF_TRY(gemm_heads(p, prec, st, S, S, 64, HeadView{dc, H, 1, false},
                      HeadView{at(qkv, (size_t)2 * H * e), 3 * H, 1, false}, dprob_d, S, true, 1.0f));
@@ -316,17 +327,21 @@ extern "C" raf_status raf_layer_bwd(const raf_layer_desc* desc, const raf_layer_
   // B1: qkv = attn_in Wqkv^T + bqkv
   RAF_TRY(launch_colsum(prec, dqkv, T, 3 * H, 3 * H, (float*)grads->b_qkv, partial, st));
   if (d.pre_ln) {
-    RAF_TRY(gemm(prec, st, 3 * H, H, T, dqkv, 3 * H, 0, n1, H, 0, grads->w_qkv, H, 1));
     RAF_TRY(gemm(prec, st, T, H, 3 * H, dqkv, 3 * H, 1, w->w_qkv, H, 0, dattn, H));
     // attn_in = LN1(x); dx = dz1 + LN1'(dattn)
     RAF_TRY(launch_ln_bwd(d, 0, T, dattn, nullptr, x, mu1, rstd1, (const float*)w->ln1_g, dz1, dx, nullptr,
                           (float*)grads->ln1_g, (float*)grads->ln1_b, nullptr, partial, step, st));
   } else {
-    RAF_TRY(gemm(prec, st, 3 * H, H, T, dqkv, 3 * H, 0, x, H, 0, grads->w_qkv, H, 1));
     // dx = dz1 + dqkv Wqkv (residual add in the epilogue)
     RAF_TRY(gemm(prec, st, T, H, 3 * H, dqkv, 3 * H, 1, w->w_qkv, H, 0, dx, H, 0, EPI_ADD_RES, nullptr, dz1, H));
   }
-  return RAF_OK;
+  // dW2 = da2^T g ; dW1 = du^T ffn_in ; dWqkv = dqkv^T attn_in ; dWo = da1^T c   (float outputs)
+  GemmArgs wg[4];
+  wg[0] = wgrad_args(H, F, T, da, H, g, F, grads->w_2, F);
+  wg[1] = wgrad_args(F, H, T, du, F, ffn_in, H, grads->w_1, H);
+  wg[2] = wgrad_args(3 * H, H, T, dqkv, 3 * H, d.pre_ln ? n1 : x, H, grads->w_qkv, H);
+  wg[3] = wgrad_args(H, H, T, da1, H, c, H, grads->w_o, H);
+  return launch_gemm_group_wgrad(prec, wg, 4, st);
 }
 
 // ------------------------------------------------------ single operators --
