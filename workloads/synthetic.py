@@ -90,3 +90,68 @@ def make_layer_inputs(cfg, seed=0, random_affine=False):
         x = round_to_bf16(x)
         G = round_to_bf16(G)
     return dict(x=x, G=G, params=params, seq_lens=seq_lens)
+
+
+# ---------------------------------------------------------------- full model --
+MODEL_CONFIGS = {
+    # 12-layer BERT-base-shaped encoder + MLM head, tied 30522 x 768 embedding, bf16 AMP
+    "bert_base_12l_mlm": dict(CONFIGS["bert_base"], batch=64, layers=12, vocab=30522, max_pos=512,
+                              layer_id_base=0, embed_layer_id=0xE0, mlm_prob=0.15),
+    # small fp32 model for parity tests that the oracle finishes in seconds
+    "tiny_model": dict(CONFIGS["tiny"], layers=2, vocab=1000, max_pos=64, layer_id_base=0, embed_layer_id=0xE0,
+                       mlm_prob=0.15, dropout_p=0.1, loss_scale=4.0, len_lo=8, len_hi=32),
+}
+
+EMBED_PARAMS = ("word", "pos", "emb_ln_g", "emb_ln_b")
+HEAD_PARAMS = ("head_w", "head_b", "head_ln_g", "head_ln_b", "dec_b")
+
+
+def vocab_padded(cfg):
+    """Rows of the word table as stored: the vocabulary rounded up to a multiple of 32 (extra rows zero)."""
+    return (cfg["vocab"] + 31) // 32 * 32
+
+
+def make_model_inputs(cfg, seed=0):
+    """Returns dict(ids [B,S] int32, seq_lens, sel int32 (ascending flat positions), labels int32,
+    P {embedding/head name: f32}, layers [ {layer param: f32} ]).
+
+    Draw order: seq_lens, ids, selection mask, labels, embedding/head parameters, then each layer's
+    twelve tensors.  Selected positions: Bernoulli(mlm_prob) on valid tokens (at least one); labels
+    and ids uniform over the vocabulary; tables ~ N(0,0.02); LayerNorm gamma 1, beta 0; biases 0.
+    These stand in for tokenised text and a pretrained checkpoint.
+    """
+    rng = np.random.Generator(np.random.PCG64(seed))
+    B, S, H, V = cfg["batch"], cfg["seq"], cfg["hidden"], cfg["vocab"]
+    seq_lens = rng.integers(cfg["len_lo"], cfg["len_hi"], size=B, endpoint=True).astype(np.int32)
+    ids = rng.integers(0, V, size=(B, S)).astype(np.int32)
+    valid = np.arange(S)[None, :] < seq_lens[:, None]
+    pick = (rng.random((B, S)) < cfg["mlm_prob"]) & valid
+    if not pick.any():
+        pick[0, 0] = True
+    sel = np.flatnonzero(pick.reshape(-1)).astype(np.int32)
+    labels = rng.integers(0, V, size=sel.size).astype(np.int32)
+    Vp = vocab_padded(cfg)
+    P = {}
+    word = np.zeros((Vp, H), dtype=np.float32)
+    word[:V] = 0.02 * rng.standard_normal((V, H), dtype=np.float32)
+    P["word"] = word
+    P["pos"] = (0.02 * rng.standard_normal((cfg["max_pos"], H), dtype=np.float32)).astype(np.float32)
+    P["emb_ln_g"] = np.ones(H, dtype=np.float32)
+    P["emb_ln_b"] = np.zeros(H, dtype=np.float32)
+    P["head_w"] = (0.02 * rng.standard_normal((H, H), dtype=np.float32)).astype(np.float32)
+    P["head_b"] = np.zeros(H, dtype=np.float32)
+    P["head_ln_g"] = np.ones(H, dtype=np.float32)
+    P["head_ln_b"] = np.zeros(H, dtype=np.float32)
+    P["dec_b"] = np.zeros(V, dtype=np.float32)
+    layers = []
+    for _ in range(cfg["layers"]):
+        lp = {}
+        for name, shape in param_shapes(cfg).items():
+            if name.startswith("w_"):
+                lp[name] = (0.02 * rng.standard_normal(shape, dtype=np.float32)).astype(np.float32)
+            elif name.endswith("_g"):
+                lp[name] = np.ones(shape, dtype=np.float32)
+            else:
+                lp[name] = np.zeros(shape, dtype=np.float32)
+        layers.append(lp)
+    return dict(ids=ids, seq_lens=seq_lens, sel=sel, labels=labels, P=P, layers=layers)
