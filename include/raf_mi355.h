@@ -152,6 +152,74 @@ raf_status raf_adam_step(const raf_adam_tensor *list, int32_t count, double lr, 
 raf_status raf_debug_dropout_mask(const raf_layer_desc *desc, int32_t site, uint64_t step, uint8_t *mask_out,
                                   int64_t n, void *hip_stream);
 
+/* ---- whole-model pieces around the layer stack (largest workload): token +
+ * position embedding with LayerNorm and dropout, and the masked-language-model
+ * head with a decoder tied to the word table and a summed softmax
+ * cross-entropy.  Same composition rule as the layer (Section 2.1) and the same
+ * fusion / precision policy (Sections 3.1.2, 3.2.2).
+ *
+ * The word table is stored with vocab_pad = vocab rounded up to a multiple of 32
+ * rows; rows >= vocab must be zero (they take part in padded GEMM tiles with a
+ * zero coefficient).  Its gradient has the same vocab_pad rows. */
+typedef struct {
+  int32_t batch, seq, hidden, vocab, max_pos;
+  int32_t precision; /* raf_precision */
+  float ln_eps;
+  uint32_t layer_id; /* dropout counter id of the embedding (site 4) */
+  double dropout_p;
+  uint64_t seed;
+} raf_embed_desc;
+
+raf_status raf_embed_workspace(const raf_embed_desc *desc, size_t *saved_bytes, size_t *scratch_bytes);
+
+/* x0 = dropout_site4(LayerNorm(word[ids] + pos[position])).
+ *   ids [dev] int32 [B*S] in [0,vocab); word [dev] [vocab_pad,H] and pos [dev]
+ *   [max_pos,H] in compute dtype; gamma/beta [dev] float [H]; x0 [dev] [B*S,H]
+ *   compute dtype; saved [dev] >= saved_bytes (written). */
+raf_status raf_embed_fwd(const raf_embed_desc *desc, const int32_t *ids, const void *word, const void *pos,
+                         const float *gamma, const float *beta, void *x0, void *saved, uint64_t step,
+                         void *hip_stream);
+
+/* Adjoint.  dx0 [dev] [B*S,H] compute dtype.  dword [dev] float [vocab_pad,H]:
+ * the embedding's contribution is ADDED to what is there (call after
+ * raf_mlm_head_fwd_bwd, which overwrites it with the tied decoder's gradient);
+ * rows with the same id are summed in ascending position order, so the result
+ * is reproducible.  dpos [dev] float [max_pos,H], dgamma/dbeta [dev] float [H]:
+ * overwritten. */
+raf_status raf_embed_bwd(const raf_embed_desc *desc, const int32_t *ids, const void *dx0, const void *saved,
+                         const float *gamma, float *dword, float *dpos, float *dgamma, float *dbeta, void *scratch,
+                         uint64_t step, void *hip_stream);
+
+typedef struct {
+  int32_t rows;      /* B*S rows of the final hidden state                      */
+  int32_t hidden, vocab;
+  int32_t n_sel;     /* number of selected (masked) positions, >= 1             */
+  int32_t precision; /* raf_precision */
+  int32_t gelu_tanh;
+  float ln_eps;
+  int32_t reserved;  /* must be 0 */
+} raf_mlm_desc;
+
+/* head_w [H,H] and word [vocab_pad,H] in compute dtype as weights; everything
+ * else float.  As gradients: all float, word with vocab_pad rows. */
+typedef struct {
+  void *head_w, *head_b, *ln_g, *ln_b, *word, *dec_b;
+} raf_mlm_tensors;
+
+raf_status raf_mlm_workspace(const raf_mlm_desc *desc, size_t *scratch_bytes);
+
+/* Forward and backward of the head in one call:
+ *   r = x[sel]; t = LN(gelu(r head_w^T + head_b)); logits = t word^T + dec_b;
+ *   loss = sum_i (logsumexp(logits_i) - logits_i[labels_i]);
+ *   gradients of loss_scale * loss.
+ *   x [dev] [rows,H] compute dtype; sel [dev] int32 [n_sel] flat row indices,
+ *   strictly ascending; labels [dev] int32 [n_sel] in [0,vocab).
+ *   loss_out [dev] one float (unscaled loss); dx [dev] [rows,H] compute dtype,
+ *   fully overwritten (zero on unselected rows); grads overwritten. */
+raf_status raf_mlm_head_fwd_bwd(const raf_mlm_desc *desc, const raf_mlm_tensors *w, const void *x,
+                                const int32_t *sel, const int32_t *labels, float loss_scale, float *loss_out,
+                                void *dx, raf_mlm_tensors *grads, void *scratch, void *hip_stream);
+
 /* ---- single fused operators, exported for per-kernel parity tests and
  * per-kernel roofline measurement; the layer calls above use the same kernels. */
 

@@ -41,6 +41,24 @@ class LayerTensors(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in PARAM_NAMES]
 
 
+class EmbedDesc(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("seq", C.c_int32), ("hidden", C.c_int32), ("vocab", C.c_int32),
+                ("max_pos", C.c_int32), ("precision", C.c_int32), ("ln_eps", C.c_float), ("layer_id", C.c_uint32),
+                ("dropout_p", C.c_double), ("seed", C.c_uint64)]
+
+
+class MlmDesc(C.Structure):
+    _fields_ = [("rows", C.c_int32), ("hidden", C.c_int32), ("vocab", C.c_int32), ("n_sel", C.c_int32),
+                ("precision", C.c_int32), ("gelu_tanh", C.c_int32), ("ln_eps", C.c_float), ("reserved", C.c_int32)]
+
+
+MLM_NAMES = ("head_w", "head_b", "ln_g", "ln_b", "word", "dec_b")
+
+
+class MlmTensors(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in MLM_NAMES]
+
+
 class AdamTensor(C.Structure):
     _fields_ = [("master", C.c_void_p), ("grad", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p),
                 ("lowp", C.c_void_p), ("n", C.c_int64)]
@@ -60,6 +78,13 @@ _SIGNATURES = {
                                 C.c_double, C.c_int64, C.c_double, C.c_void_p]),
     "raf_debug_dropout_mask": (C.c_int, [C.POINTER(LayerDesc), C.c_int32, C.c_uint64, C.c_void_p, C.c_int64,
                                          C.c_void_p]),
+    "raf_embed_workspace": (C.c_int, [C.POINTER(EmbedDesc), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]),
+    "raf_embed_fwd": (C.c_int, [C.POINTER(EmbedDesc)] + [C.c_void_p] * 7 + [C.c_uint64, C.c_void_p]),
+    "raf_embed_bwd": (C.c_int, [C.POINTER(EmbedDesc)] + [C.c_void_p] * 9 + [C.c_uint64, C.c_void_p]),
+    "raf_mlm_workspace": (C.c_int, [C.POINTER(MlmDesc), C.POINTER(C.c_size_t)]),
+    "raf_mlm_head_fwd_bwd": (C.c_int, [C.POINTER(MlmDesc), C.POINTER(MlmTensors), C.c_void_p, C.c_void_p, C.c_void_p,
+                                       C.c_float, C.c_void_p, C.c_void_p, C.POINTER(MlmTensors), C.c_void_p,
+                                       C.c_void_p]),
     "raf_op_gemm": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_int32,
                               C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_float,
                               C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
@@ -227,3 +252,50 @@ def raf_op_dropout_residual_ln_bwd(desc, site, rows, dout, dout2, z, mu, rstd, g
         C.byref(desc), int(site), int(rows), _ptr(dout), _ptr(dout2), _ptr(z), _ptr(mu), _ptr(rstd), _ptr(gamma),
         _ptr(dres), _ptr(dz), _ptr(da), _ptr(dgamma), _ptr(dbeta), _ptr(dbias), _ptr(partial), int(step),
         _stream(stream)), "raf_op_dropout_residual_ln_bwd")
+
+
+def make_embed_desc(cfg):
+    return EmbedDesc(batch=cfg["batch"], seq=cfg["seq"], hidden=cfg["hidden"], vocab=cfg["vocab"],
+                     max_pos=cfg["max_pos"], precision=cfg["precision"], ln_eps=cfg["ln_eps"],
+                     layer_id=cfg["embed_layer_id"], dropout_p=cfg["dropout_p"], seed=cfg["seed"])
+
+
+def make_mlm_desc(cfg, n_sel):
+    return MlmDesc(rows=cfg["batch"] * cfg["seq"], hidden=cfg["hidden"], vocab=cfg["vocab"], n_sel=int(n_sel),
+                   precision=cfg["precision"], gelu_tanh=cfg.get("gelu_tanh", 0), ln_eps=cfg["ln_eps"], reserved=0)
+
+
+def make_mlm_tensors(d):
+    t = MlmTensors()
+    for n in MLM_NAMES:
+        setattr(t, n, _ptr(d[n]))
+    return t
+
+
+def raf_embed_workspace(desc):
+    sv, sc = C.c_size_t(0), C.c_size_t(0)
+    _check(load_library().raf_embed_workspace(C.byref(desc), C.byref(sv), C.byref(sc)), "raf_embed_workspace")
+    return sv.value, sc.value
+
+
+def raf_embed_fwd(desc, ids, word, pos, gamma, beta, x0, saved, step, stream=None):
+    _check(load_library().raf_embed_fwd(C.byref(desc), _ptr(ids), _ptr(word), _ptr(pos), _ptr(gamma), _ptr(beta),
+                                        _ptr(x0), _ptr(saved), int(step), _stream(stream)), "raf_embed_fwd")
+
+
+def raf_embed_bwd(desc, ids, dx0, saved, gamma, dword, dpos, dgamma, dbeta, scratch, step, stream=None):
+    _check(load_library().raf_embed_bwd(C.byref(desc), _ptr(ids), _ptr(dx0), _ptr(saved), _ptr(gamma), _ptr(dword),
+                                        _ptr(dpos), _ptr(dgamma), _ptr(dbeta), _ptr(scratch), int(step),
+                                        _stream(stream)), "raf_embed_bwd")
+
+
+def raf_mlm_workspace(desc):
+    sc = C.c_size_t(0)
+    _check(load_library().raf_mlm_workspace(C.byref(desc), C.byref(sc)), "raf_mlm_workspace")
+    return sc.value
+
+
+def raf_mlm_head_fwd_bwd(desc, w, x, sel, labels, loss_scale, loss_out, dx, grads, scratch, stream=None):
+    _check(load_library().raf_mlm_head_fwd_bwd(C.byref(desc), C.byref(w), _ptr(x), _ptr(sel), _ptr(labels),
+                                               float(loss_scale), _ptr(loss_out), _ptr(dx), C.byref(grads),
+                                               _ptr(scratch), _stream(stream)), "raf_mlm_head_fwd_bwd")

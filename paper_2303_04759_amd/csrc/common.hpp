@@ -188,6 +188,32 @@ __device__ __forceinline__ float gelu_grad_f(float u, int tanh_form) {
   return Phi + u * phi;
 }
 
+// ---------------------------------------------------------- row geometry --
+struct RowGeom {
+  int lpr, nv;
+};
+inline RowGeom row_geom(int len) {
+  const int nvec = len / 8;
+  int lpr = 4;
+  while (lpr < 64 && lpr < nvec) lpr <<= 1;
+  int nv = 1;
+  while (lpr * nv < nvec) nv <<= 1;
+  return RowGeom{lpr, nv};
+}
+
+#define RAF_DISPATCH_GEOM(GEOM, CALL)                   \
+  do {                                                  \
+    const RowGeom _g = (GEOM);                          \
+    if (_g.lpr == 4) { CALL(4, 1); }                    \
+    else if (_g.lpr == 8) { CALL(8, 1); }               \
+    else if (_g.lpr == 16) { CALL(16, 1); }             \
+    else if (_g.lpr == 32) { CALL(32, 1); }             \
+    else if (_g.nv == 1) { CALL(64, 1); }               \
+    else if (_g.nv == 2) { CALL(64, 2); }               \
+    else if (_g.nv == 4) { CALL(64, 4); }               \
+    else { CALL(64, 8); }                               \
+  } while (0)
+
 // --------------------------------------------------------- internal ops ---
 enum Epilogue { EPI_NONE = 0, EPI_BIAS = 1, EPI_BIAS_GELU = 2, EPI_MUL_GELU_GRAD = 3, EPI_ADD_RES = 4 };
 
@@ -230,10 +256,13 @@ size_t ln_bwd_partial_floats(int hidden, int64_t rows);
 raf_status launch_ln_bwd(const raf_layer_desc& d, int site, int64_t rows, const void* dout, const void* dout2,
                          const void* z, const float* mu, const float* rstd, const float* gamma, const void* dres,
                          void* dz, void* da, float* dgamma, float* dbeta, float* dbias, float* partial,
-                         uint64_t step, hipStream_t st);
+                         uint64_t step, hipStream_t st, int site_in = 0);
 // out[j] = sum_i x[i*ld + j], x in compute dtype, rows x cols; partial scratch
 size_t colsum_partial_floats(int cols, int64_t rows);
+// only the first out_cols (<= cols, 0 = all) sums are written
 raf_status launch_colsum(int precision, const void* x, int64_t rows, int cols, long ld, float* out, float* partial,
-                         hipStream_t st);
+                         hipStream_t st, int out_cols = 0);
+// loss_out[0] = sum of partial[0..nparts) in a fixed order
+raf_status launch_sum_partials(const float* partial, int nparts, float* out, hipStream_t st);
 
 }  // namespace raf

@@ -12,32 +12,6 @@
 
 namespace raf {
 
-// ---------------------------------------------------------- row geometry --
-struct RowGeom {
-  int lpr, nv;
-};
-static RowGeom row_geom(int len) {
-  const int nvec = len / 8;
-  int lpr = 4;
-  while (lpr < 64 && lpr < nvec) lpr <<= 1;
-  int nv = 1;
-  while (lpr * nv < nvec) nv <<= 1;
-  return RowGeom{lpr, nv};
-}
-
-#define RAF_DISPATCH_GEOM(GEOM, CALL)                   \
-  do {                                                  \
-    const RowGeom _g = (GEOM);                          \
-    if (_g.lpr == 4) { CALL(4, 1); }                    \
-    else if (_g.lpr == 8) { CALL(8, 1); }               \
-    else if (_g.lpr == 16) { CALL(16, 1); }             \
-    else if (_g.lpr == 32) { CALL(32, 1); }             \
-    else if (_g.nv == 1) { CALL(64, 1); }               \
-    else if (_g.nv == 2) { CALL(64, 2); }               \
-    else if (_g.nv == 4) { CALL(64, 4); }               \
-    else { CALL(64, 8); }                               \
-  } while (0)
-
 // ---------------------------------------------------------- softmax fwd ---
 template <typename T, int LPR, int NV>
 __global__ __launch_bounds__(256) void softmax_fwd_kernel(const T* __restrict__ s, const int32_t* __restrict__ lens,
@@ -245,7 +219,7 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dout,
                                                      const float* __restrict__ rstd, const float* __restrict__ gamma,
                                                      const T* __restrict__ dres, T* __restrict__ dz,
                                                      T* __restrict__ da, float* __restrict__ partial, long nrows,
-                                                     int H, DropSite drop) {
+                                                     int H, DropSite drop, DropSite drop_in) {
   extern __shared__ float red[];   // [3][H]
   const int lane = threadIdx.x & (LPR - 1);
   const int groups_per_block = 256 / LPR;
@@ -282,6 +256,12 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dout,
           Vec8<T>::load(dout2 + off, g2);
 #pragma unroll
           for (int e = 0; e < 8; ++e) g[t][e] += g2[e];
+        }
+        if (drop_in.enabled) {   // the incoming gradient passes a dropout that follows the LayerNorm
+          float mult[8];
+          drop_mult8(drop_in, (uint64_t)off, mult);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) g[t][e] *= mult[e];
         }
         if (HAS_LN) {
           float zv[8];
@@ -381,13 +361,14 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dout,
 // four 64-lane slices of a block take parts p = slice, slice+4, ... and are
 // combined in a fixed order, so the sum is reproducible.
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int nparts, int ncols,
-                                                              int nout, float* o0, float* o1, float* o2) {
+                                                              int nout, float* o0, float* o1, float* o2,
+                                                              int width_out) {
   __shared__ float red[4][64];
   const int c = blockIdx.x * 64 + (threadIdx.x & 63);
   const int slice = threadIdx.x >> 6;
-  const long width = (long)nout * ncols;
+  const long width = (long)nout * ncols;   // stride between partial rows; only c < width_out is produced
   float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-  if (c < width) {
+  if (c < width_out) {
     int p = slice;
     for (; p + 12 < nparts; p += 16) {
       a0 += partial[(long)p * width + c];
@@ -399,7 +380,7 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
   }
   red[slice][threadIdx.x & 63] = (a0 + a1) + (a2 + a3);
   __syncthreads();
-  if (slice == 0 && c < width) {
+  if (slice == 0 && c < width_out) {
     const float acc = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
     const int k = c / ncols, cc = c % ncols;
     float* o = k == 0 ? o0 : (k == 1 ? o1 : o2);
@@ -531,18 +512,20 @@ size_t ln_bwd_partial_floats(int hidden, int64_t rows) {
 raf_status launch_ln_bwd(const raf_layer_desc& d, int site, int64_t rows, const void* dout, const void* dout2,
                          const void* z, const float* mu, const float* rstd, const float* gamma, const void* dres,
                          void* dz, void* da, float* dgamma, float* dbeta, float* dbias, float* partial,
-                         uint64_t step, hipStream_t st) {
+                         uint64_t step, hipStream_t st, int site_in) {
   if (!dout || !partial || rows <= 0) return RAF_EINVAL;
   if (gamma && (!z || !mu || !rstd || !dgamma || !dbeta)) return RAF_EINVAL;
   if (!dz && !da) return RAF_EINVAL;
   if (da && !dbias) return RAF_EINVAL;
   if (site != 0 && site != 2 && site != 3) return RAF_EINVAL;
+  if (site_in != 0 && site_in != 4) return RAF_EINVAL;
   if (!aligned16(dout) || !aligned16(dout2) || !aligned16(z) || !aligned16(gamma) || !aligned16(dres) ||
       !aligned16(dz) || !aligned16(da))
     return RAF_EINVAL;
   if (!row_shape_ok(d.hidden)) return RAF_ENOTSUP;
   if ((uint64_t)rows * d.hidden / 4 > 0xffffffffull) return RAF_ENOTSUP;
   const DropSite drop = make_drop_site(d, site, step);
+  const DropSite drop_in = make_drop_site(d, site_in, step);
   const int H = d.hidden;
   const int nb = ln_bwd_blocks(H, rows);
   const size_t shm = (size_t)3 * H * sizeof(float);
@@ -552,20 +535,20 @@ raf_status launch_ln_bwd(const raf_layer_desc& d, int site, int64_t rows, const 
       if (gamma)                                                                                                    \
         hipLaunchKernelGGL((ln_bwd_kernel<float, LPR, NV, true>), dim3(nb), dim3(256), shm, st, (const float*)dout, \
                            (const float*)dout2, (const float*)z, mu, rstd, gamma, (const float*)dres, (float*)dz,   \
-                           (float*)da, partial, (long)rows, H, drop);                                               \
+                           (float*)da, partial, (long)rows, H, drop, drop_in);                                               \
       else                                                                                                          \
         hipLaunchKernelGGL((ln_bwd_kernel<float, LPR, NV, false>), dim3(nb), dim3(256), shm, st,                    \
                            (const float*)dout, (const float*)dout2, (const float*)z, mu, rstd, gamma,               \
-                           (const float*)dres, (float*)dz, (float*)da, partial, (long)rows, H, drop);               \
+                           (const float*)dres, (float*)dz, (float*)da, partial, (long)rows, H, drop, drop_in);               \
     } else {                                                                                                        \
       if (gamma)                                                                                                    \
         hipLaunchKernelGGL((ln_bwd_kernel<bf16_t, LPR, NV, true>), dim3(nb), dim3(256), shm, st,                    \
                            (const bf16_t*)dout, (const bf16_t*)dout2, (const bf16_t*)z, mu, rstd, gamma,            \
-                           (const bf16_t*)dres, (bf16_t*)dz, (bf16_t*)da, partial, (long)rows, H, drop);            \
+                           (const bf16_t*)dres, (bf16_t*)dz, (bf16_t*)da, partial, (long)rows, H, drop, drop_in);   \
       else                                                                                                          \
         hipLaunchKernelGGL((ln_bwd_kernel<bf16_t, LPR, NV, false>), dim3(nb), dim3(256), shm, st,                   \
                            (const bf16_t*)dout, (const bf16_t*)dout2, (const bf16_t*)z, mu, rstd, gamma,            \
-                           (const bf16_t*)dres, (bf16_t*)dz, (bf16_t*)da, partial, (long)rows, H, drop);            \
+                           (const bf16_t*)dres, (bf16_t*)dz, (bf16_t*)da, partial, (long)rows, H, drop, drop_in);   \
     }                                                                                                               \
   }
   RAF_DISPATCH_GEOM(row_geom(H), CALL);
@@ -573,7 +556,7 @@ raf_status launch_ln_bwd(const raf_layer_desc& d, int site, int64_t rows, const 
   raf_status rc = check_launch();
   if (rc != RAF_OK) return rc;
   hipLaunchKernelGGL(reduce_partials_kernel, dim3((3 * H + 63) / 64), dim3(256), 0, st, partial, nb, H, 3,
-                     gamma ? dgamma : nullptr, gamma ? dbeta : nullptr, da ? dbias : nullptr);
+                     gamma ? dgamma : nullptr, gamma ? dbeta : nullptr, da ? dbias : nullptr, 3 * H);
   return check_launch();
 }
 
@@ -586,7 +569,8 @@ static int colsum_parts(int64_t rows) {
 size_t colsum_partial_floats(int cols, int64_t rows) { return (size_t)colsum_parts(rows) * (size_t)cols; }
 
 raf_status launch_colsum(int precision, const void* x, int64_t rows, int cols, long ld, float* out, float* partial,
-                         hipStream_t st) {
+                         hipStream_t st, int out_cols) {
+  if (out_cols <= 0 || out_cols > cols) out_cols = cols;
   if (!x || !out || !partial || rows <= 0 || cols <= 0) return RAF_EINVAL;
   if ((cols % 8) || (ld % 8) || !aligned16(x)) return RAF_EINVAL;
   const int parts = colsum_parts(rows);
@@ -598,8 +582,8 @@ raf_status launch_colsum(int precision, const void* x, int64_t rows, int cols, l
                        partial);
   raf_status rc = check_launch();
   if (rc != RAF_OK) return rc;
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3((cols + 63) / 64), dim3(256), 0, st, partial, parts, cols, 1, out,
-                     nullptr, nullptr);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((out_cols + 63) / 64), dim3(256), 0, st, partial, parts, cols, 1,
+                     out, nullptr, nullptr, out_cols);
   return check_launch();
 }
 

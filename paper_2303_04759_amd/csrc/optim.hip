@@ -113,6 +113,12 @@ __global__ __launch_bounds__(256) void loss_final_kernel(const float* __restrict
   if (threadIdx.x == 0) *loss_out = red[0];
 }
 
+raf_status launch_sum_partials(const float* partial, int nparts, float* out, hipStream_t st) {
+  if (!partial || !out || nparts <= 0) return RAF_EINVAL;
+  hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(256), 0, st, partial, nparts, out);
+  return check_launch();
+}
+
 // ------------------------------------------------------- mask test hook ---
 __global__ __launch_bounds__(256) void dropout_mask_kernel(uint8_t* __restrict__ out, long n, DropSite drop) {
   const long i8 = ((long)blockIdx.x * 256 + threadIdx.x) * 8;

@@ -75,3 +75,106 @@ class DeviceLayer:
 
     def host(self, t):
         return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+class DeviceModel:
+    """Embedding + L layers + MLM head on the device: buffers and the step-ordered C-ABI calls."""
+
+    EMBED = ("word", "pos", "emb_ln_g", "emb_ln_b")
+    HEAD = ("head_w", "head_b", "head_ln_g", "head_ln_b", "dec_b")
+
+    def __init__(self, cfg, inputs, adam, device="cuda:0"):
+        from . import (make_embed_desc, make_mlm_desc, make_mlm_tensors, raf_embed_workspace, raf_mlm_workspace)
+        if not torch.cuda.is_available():
+            raise RuntimeError("DeviceModel needs a GPU; there is no CPU path")
+        self.cfg, self.adam = dict(cfg), dict(adam)
+        dev = self.dev = torch.device(device)
+        self.amp = cfg["precision"] == RAF_BF16_AMP
+        cd = self.cdtype = torch.bfloat16 if self.amp else torch.float32
+        B, S, H = cfg["batch"], cfg["seq"], cfg["hidden"]
+        self.T, self.H, self.L = B * S, H, cfg["layers"]
+        f32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev).contiguous()
+        i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev).contiguous()
+        self.ids, self.seq_lens = i32(inputs["ids"].reshape(-1)), i32(inputs["seq_lens"])
+        self.sel, self.labels = i32(inputs["sel"]), i32(inputs["labels"])
+        self.n_sel = int(self.sel.numel())
+        # parameters: master (f32), optional bf16 copy for matrices/tables, Adam state, gradients
+        self.master, self.lowp, self.m, self.v, self.grads = {}, {}, {}, {}, {}
+        matrices = {"word", "pos", "head_w"}
+        for k in self.EMBED + self.HEAD:
+            self._add_param(k, f32(inputs["P"][k]), k in matrices)
+        self.layer_keys = []
+        for l, lp in enumerate(inputs["layers"]):
+            for k in PARAM_NAMES:
+                self._add_param((l, k), f32(lp[k]), k.startswith("w_"))
+            self.layer_keys.append([(l, k) for k in PARAM_NAMES])
+        # descriptors and workspaces
+        self.edesc = make_embed_desc(cfg)
+        self.mdesc = make_mlm_desc(cfg, self.n_sel)
+        self.ldesc = []
+        for l in range(self.L):
+            c = dict(cfg)
+            c["layer_id"] = cfg["layer_id_base"] + l
+            self.ldesc.append(make_desc(c))
+        esv, esc = raf_embed_workspace(self.edesc)
+        lsv, lsc = raf_layer_workspace(self.ldesc[0]) if self.L else (256, 256)
+        msc = raf_mlm_workspace(self.mdesc)
+        u8 = lambda n: torch.empty(max(int(n), 256), dtype=torch.uint8, device=dev)
+        self.esaved, self.scratch = u8(esv), u8(max(esc, lsc, msc))
+        self.lsaved = [u8(lsv) for _ in range(self.L)]
+        act = lambda: torch.empty(self.T, H, dtype=cd, device=dev)
+        self.x = [act() for _ in range(self.L + 1)]       # x[0] = embedding output, x[l+1] = layer l output
+        self.dx = [act(), act()]                          # ping-pong gradient buffers
+        self.loss = torch.zeros(1, dtype=torch.float32, device=dev)
+        w = lambda k: self.lowp[k] if self.lowp[k] is not None else self.master[k]
+        self.lw = [make_tensors({k: w((l, k)) for k in PARAM_NAMES}) for l in range(self.L)]
+        self.lg = [make_tensors({k: self.grads[(l, k)] for k in PARAM_NAMES}) for l in range(self.L)]
+        names = dict(head_w="head_w", head_b="head_b", ln_g="head_ln_g", ln_b="head_ln_b", word="word", dec_b="dec_b")
+        self.mw = make_mlm_tensors({a: w(b) for a, b in names.items()})
+        self.mg = make_mlm_tensors({a: self.grads[b] for a, b in names.items()})
+        keys = list(self.master)
+        self.adam_list, self.adam_count = make_adam_list(
+            (self.master[k], self.grads[k], self.m[k], self.v[k], self.lowp[k]) for k in keys)
+
+    def _add_param(self, key, master, has_lowp):
+        self.master[key] = master
+        self.lowp[key] = master.to(torch.bfloat16) if (self.amp and has_lowp) else None
+        self.m[key] = torch.zeros_like(master)
+        self.v[key] = torch.zeros_like(master)
+        self.grads[key] = torch.zeros_like(master)
+
+    def _w(self, k):
+        return self.lowp[k] if self.lowp[k] is not None else self.master[k]
+
+    def forward(self, step, stream=None):
+        from . import raf_embed_fwd
+        raf_embed_fwd(self.edesc, self.ids, self._w("word"), self._w("pos"), self.master["emb_ln_g"],
+                      self.master["emb_ln_b"], self.x[0], self.esaved, step, stream)
+        for l in range(self.L):
+            raf_layer_fwd(self.ldesc[l], self.lw[l], self.x[l], self.seq_lens, self.x[l + 1], self.lsaved[l],
+                          self.scratch, step, stream)
+
+    def head_and_backward(self, step, stream=None):
+        from . import raf_embed_bwd, raf_mlm_head_fwd_bwd
+        cur = 0
+        raf_mlm_head_fwd_bwd(self.mdesc, self.mw, self.x[self.L], self.sel, self.labels, self.cfg["loss_scale"],
+                             self.loss, self.dx[cur], self.mg, self.scratch, stream)
+        for l in reversed(range(self.L)):
+            raf_layer_bwd(self.ldesc[l], self.lw[l], self.x[l], self.dx[cur], self.seq_lens, self.lsaved[l],
+                          self.dx[cur ^ 1], self.lg[l], self.scratch, step, stream)
+            cur ^= 1
+        raf_embed_bwd(self.edesc, self.ids, self.dx[cur], self.esaved, self.master["emb_ln_g"], self.grads["word"],
+                      self.grads["pos"], self.grads["emb_ln_g"], self.grads["emb_ln_b"], self.scratch, step, stream)
+
+    def adam_step(self, t, stream=None):
+        a = self.adam
+        raf_adam_step(self.adam_list, self.adam_count, a["lr"], a["beta1"], a["beta2"], a["eps"],
+                      a.get("weight_decay", 0.0), t, 1.0 / self.cfg["loss_scale"], stream)
+
+    def train_step(self, t, stream=None):
+        self.forward(t, stream)
+        self.head_and_backward(t, stream)
+        self.adam_step(t, stream)
+
+    def host(self, t):
+        return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
