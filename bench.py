@@ -40,6 +40,55 @@ def gemm_launches(cfg):
     ]
 
 
+def bench_model(args, cfg):
+    """Whole 12-layer model step (embedding, layers, MLM head, backward, Adam over all tensors)."""
+    import numpy as np
+    import torch
+    from paper_2303_04759_amd.harness import DeviceModel
+    from workloads.synthetic import ADAM, make_model_inputs
+    inp = make_model_inputs(cfg, seed=0)
+    mod = DeviceModel(cfg, inp, ADAM)
+    stream = torch.cuda.Stream()
+    K, W = args.steps, args.warmup
+    with torch.cuda.stream(stream):
+        t_step = 1
+        for _ in range(max(W, 1)):
+            mod.train_step(t_step, stream)
+            t_step += 1
+        stream.synchronize()
+        graph = None
+        if not args.no_graph:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                mod.train_step(t_step, stream)
+            graph.replay()
+            stream.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for _ in range(K):
+            if graph is not None:
+                graph.replay()
+            else:
+                mod.train_step(t_step, stream)
+                t_step += 1
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / K
+    n_params = sum(v.numel() for v in mod.master.values())
+    out = {"metric": "train samples/sec, 12-layer BERT-base + MLM head fwd+bwd+Adam (bf16 AMP, 1 GPU)",
+           "value": cfg["batch"] / (ms * 1e-3), "unit": "samples/s", "n_gpus": 1, "steps": K, "warmup": W,
+           "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16" if cfg["precision"] == 1 else "f32", "data": "synthetic",
+           "config": {"workload": args.workload, "batch": cfg["batch"], "seq_len": cfg["seq"], "layers": cfg["layers"],
+                      "hidden": cfg["hidden"], "vocab": cfg["vocab"], "selected_positions": int(len(inp["sel"])),
+                      "parameters": int(n_params), "launch": "eager" if graph is None else "hip_graph",
+                      "parallelism": "single GPU"},
+           "tokens_per_s_padded": mod.T / (ms * 1e-3),
+           "tokens_per_s_valid": int(np.sum(inp["seq_lens"])) / (ms * 1e-3)}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -58,8 +107,10 @@ def main():
         sys.exit("bench.py needs a GPU; there is no CPU path for the library")
     import paper_2303_04759_amd as raf
     from paper_2303_04759_amd.harness import DeviceLayer
-    from workloads.synthetic import ADAM, CONFIGS, make_layer_inputs
+    from workloads.synthetic import ADAM, CONFIGS, MODEL_CONFIGS, make_layer_inputs
 
+    if args.workload in MODEL_CONFIGS:
+        return bench_model(args, MODEL_CONFIGS[args.workload])
     cfg = CONFIGS[args.workload]
     inp = make_layer_inputs(cfg, seed=0)
     lay = DeviceLayer(cfg, inp, ADAM)

@@ -103,6 +103,11 @@ def test_bert_base_model_reduced_depth_bf16_amp():
     run_model(cfg, seed=3, check_weights=False)
 
 
+def test_full_bert_base_12_layer_model_bf16_amp():
+    announce("model full size: 12 layers, batch 64, vocab 30522")
+    run_model(MODEL_CONFIGS["bert_base_12l_mlm"], seed=0, check_weights=False)
+
+
 def test_model_is_deterministic():
     announce("model determinism")
     cfg = dict(MODEL_CONFIGS["bert_base_12l_mlm"], batch=8, layers=2, vocab=2000)   # many duplicate ids
