@@ -249,6 +249,11 @@ raf_status launch_softmax_fwd(const raf_layer_desc& d, const void* s, const int3
                               uint64_t step, hipStream_t st);
 raf_status launch_softmax_bwd(const raf_layer_desc& d, const void* prob, const void* prob_d, const void* dprob_d,
                               void* ds, float scale_out, hipStream_t st);
+// bf16 AMP only: scores + mask + softmax + dropout in one kernel (no S x S score tensor), and its adjoint
+raf_status launch_attn_prob_fwd(const raf_layer_desc& d, const void* qkv, const int32_t* lens, void* prob, void* prob_d,
+                                uint64_t step, hipStream_t st);
+raf_status launch_attn_prob_bwd(const raf_layer_desc& d, const void* dc, const void* qkv, const void* prob,
+                                const void* prob_d, void* ds, hipStream_t st);
 raf_status launch_ln_fwd(const raf_layer_desc& d, int site, int64_t rows, const void* a, const void* res,
                          const float* gamma, const float* beta, void* out, void* z_out, float* mu, float* rstd,
                          uint64_t step, hipStream_t st);

@@ -211,10 +211,11 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ a, co
 // sums for dgamma, dbeta and dbias in registers; a block reduces them through
 // LDS and writes one partial row; a second kernel sums the partial rows in a
 // fixed order, so the result does not depend on scheduling.
-constexpr int LN_BWD_MAX_BLOCKS = 256;
+constexpr int LN_BWD_MAX_BLOCKS = 512;
+constexpr int LN_BWD_THREADS = 512;   // 8 wavefronts: two workgroups per CU keep 16 rows in flight
 
 template <typename T, int LPR, int NV, bool HAS_LN>
-__global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dout, const T* __restrict__ dout2,
+__global__ __launch_bounds__(LN_BWD_THREADS) void ln_bwd_kernel(const T* __restrict__ dout, const T* __restrict__ dout2,
                                                      const T* __restrict__ z, const float* __restrict__ mu,
                                                      const float* __restrict__ rstd, const float* __restrict__ gamma,
                                                      const T* __restrict__ dres, T* __restrict__ dz,
@@ -222,7 +223,7 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dout,
                                                      int H, DropSite drop, DropSite drop_in) {
   extern __shared__ float red[];   // [3][H]
   const int lane = threadIdx.x & (LPR - 1);
-  const int groups_per_block = 256 / LPR;
+  const int groups_per_block = LN_BWD_THREADS / LPR;
   const long group = (long)blockIdx.x * groups_per_block + threadIdx.x / LPR;
   const long ngroups = (long)gridDim.x * groups_per_block;
   const int nvec = H / 8;
@@ -327,10 +328,10 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dout,
         cd[t][e] += __shfl_xor(cd[t][e], o, WAVE);
       }
     }
-  // the four waves add their sums into LDS one after the other (fixed order)
+  // the waves add their sums into LDS one after the other (fixed order)
   const int wave = threadIdx.x >> 6;
   const int wlane = threadIdx.x & 63;
-  for (int w = 0; w < 4; ++w) {
+  for (int w = 0; w < LN_BWD_THREADS / 64; ++w) {
     if (wave == w && wlane < LPR) {
 #pragma unroll
       for (int t = 0; t < NV; ++t) {
@@ -354,7 +355,7 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dout,
     }
     __syncthreads();
   }
-  for (int c = threadIdx.x; c < 3 * H; c += 256) partial[(long)blockIdx.x * 3 * H + c] = red[c];
+  for (int c = threadIdx.x; c < 3 * H; c += LN_BWD_THREADS) partial[(long)blockIdx.x * 3 * H + c] = red[c];
 }
 
 // out_k[c] = sum_p partial[p][k][c], k < nout.  64 columns per block; the
@@ -497,8 +498,8 @@ raf_status launch_ln_fwd(const raf_layer_desc& d, int site, int64_t rows, const 
 
 static int ln_bwd_blocks(int hidden, int64_t rows) {
   const RowGeom g = row_geom(hidden);
-  const long groups_per_block = 256 / g.lpr;
-  long nb = (rows + groups_per_block * 4 - 1) / (groups_per_block * 4);   // >= 4 rows per group
+  const long groups_per_block = LN_BWD_THREADS / g.lpr;
+  long nb = (rows + groups_per_block - 1) / groups_per_block;   // one row per group until the block cap
   if (nb < 1) nb = 1;
   if (nb > LN_BWD_MAX_BLOCKS) nb = LN_BWD_MAX_BLOCKS;
   return (int)nb;
@@ -533,20 +534,20 @@ raf_status launch_ln_bwd(const raf_layer_desc& d, int site, int64_t rows, const 
   {                                                                                                                 \
     if (d.precision == RAF_F32) {                                                                                   \
       if (gamma)                                                                                                    \
-        hipLaunchKernelGGL((ln_bwd_kernel<float, LPR, NV, true>), dim3(nb), dim3(256), shm, st, (const float*)dout, \
+        hipLaunchKernelGGL((ln_bwd_kernel<float, LPR, NV, true>), dim3(nb), dim3(LN_BWD_THREADS), shm, st, (const float*)dout, \
                            (const float*)dout2, (const float*)z, mu, rstd, gamma, (const float*)dres, (float*)dz,   \
                            (float*)da, partial, (long)rows, H, drop, drop_in);                                               \
       else                                                                                                          \
-        hipLaunchKernelGGL((ln_bwd_kernel<float, LPR, NV, false>), dim3(nb), dim3(256), shm, st,                    \
+        hipLaunchKernelGGL((ln_bwd_kernel<float, LPR, NV, false>), dim3(nb), dim3(LN_BWD_THREADS), shm, st,                    \
                            (const float*)dout, (const float*)dout2, (const float*)z, mu, rstd, gamma,               \
                            (const float*)dres, (float*)dz, (float*)da, partial, (long)rows, H, drop, drop_in);               \
     } else {                                                                                                        \
       if (gamma)                                                                                                    \
-        hipLaunchKernelGGL((ln_bwd_kernel<bf16_t, LPR, NV, true>), dim3(nb), dim3(256), shm, st,                    \
+        hipLaunchKernelGGL((ln_bwd_kernel<bf16_t, LPR, NV, true>), dim3(nb), dim3(LN_BWD_THREADS), shm, st,                    \
                            (const bf16_t*)dout, (const bf16_t*)dout2, (const bf16_t*)z, mu, rstd, gamma,            \
                            (const bf16_t*)dres, (bf16_t*)dz, (bf16_t*)da, partial, (long)rows, H, drop, drop_in);   \
       else                                                                                                          \
-        hipLaunchKernelGGL((ln_bwd_kernel<bf16_t, LPR, NV, false>), dim3(nb), dim3(256), shm, st,                   \
+        hipLaunchKernelGGL((ln_bwd_kernel<bf16_t, LPR, NV, false>), dim3(nb), dim3(LN_BWD_THREADS), shm, st,                   \
                            (const bf16_t*)dout, (const bf16_t*)dout2, (const bf16_t*)z, mu, rstd, gamma,            \
                            (const bf16_t*)dres, (bf16_t*)dz, (bf16_t*)da, partial, (long)rows, H, drop, drop_in);   \
     }                                                                                                               \

@@ -16,10 +16,11 @@ namespace raf {
 
 constexpr int PBK = 64;
 
-template <int ROWS, bool KMAJOR>
+template <int ROWS, bool KMAJOR, int NW>
 struct PipeTile {
   static constexpr int BYTES = ROWS * PBK * 2;
-  static constexpr int LOADS = BYTES / 1024 / 4;        // direct-load instructions per wave per stage
+  static constexpr int LOADS = BYTES / 1024 / NW;       // direct-load instructions per wave per stage
+  static_assert(LOADS >= 1 && LOADS * NW * 1024 == BYTES, "tile must split evenly over the waves");
   static constexpr int CPR = KMAJOR ? 8 : ROWS / 8;     // 16-byte chunks per LDS row
   static __device__ __forceinline__ int swz_k(int r) { return (r >> 1) & 7; }
   static __device__ __forceinline__ int swz_mn(int k) { return CPR >= 16 ? ((k & 3) << 2) : ((k & 1) << 2); }
@@ -28,10 +29,10 @@ struct PipeTile {
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
 // per-lane global source addresses of this wave's direct loads for k-step 0
-template <int ROWS, bool KMAJOR>
+template <int ROWS, bool KMAJOR, int NW>
 __device__ __forceinline__ void pipe_src_init(const bf16_t* base, long ld, int row0, int nrows,
-                                              const bf16_t* (&src)[PipeTile<ROWS, KMAJOR>::LOADS]) {
-  typedef PipeTile<ROWS, KMAJOR> PT;
+                                              const bf16_t* (&src)[PipeTile<ROWS, KMAJOR, NW>::LOADS]) {
+  typedef PipeTile<ROWS, KMAJOR, NW> PT;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
 #pragma unroll
   for (int i = 0; i < PT::LOADS; ++i) {
@@ -53,9 +54,10 @@ __device__ __forceinline__ void pipe_src_init(const bf16_t* base, long ld, int r
   }
 }
 
-template <int ROWS, bool KMAJOR>
-__device__ __forceinline__ void pipe_issue(const bf16_t* (&src)[PipeTile<ROWS, KMAJOR>::LOADS], long koff, char* lds_tile) {
-  typedef PipeTile<ROWS, KMAJOR> PT;
+template <int ROWS, bool KMAJOR, int NW>
+__device__ __forceinline__ void pipe_issue(const bf16_t* (&src)[PipeTile<ROWS, KMAJOR, NW>::LOADS], long koff,
+                                           char* lds_tile) {
+  typedef PipeTile<ROWS, KMAJOR, NW> PT;
   const int wave = threadIdx.x >> 6;
 #pragma unroll
   for (int i = 0; i < PT::LOADS; ++i) {
@@ -67,7 +69,7 @@ __device__ __forceinline__ void pipe_issue(const bf16_t* (&src)[PipeTile<ROWS, K
 
 template <int ROWS, bool KMAJOR>
 __device__ __forceinline__ bf16x8_t pipe_fragment(const char* lds_tile, int row, int kk) {
-  typedef PipeTile<ROWS, KMAJOR> PT;
+  typedef PipeTile<ROWS, KMAJOR, 1> PT;
   const int lane = threadIdx.x & 63;
   if (KMAJOR) {
     const int r = row + (lane & 31);
@@ -92,12 +94,14 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
 
-template <int BM, int BN, bool A_KMAJOR, bool B_KMAJOR, typename TC, int NS>
-__global__ __launch_bounds__(256) void gemm_bf16_pipe_kernel(GemmDev g, int tiles_m, int tiles_n) {
-  constexpr int WM = BM / 2, WN = BN / 2;   // 2 x 2 waves
+template <int BM, int BN, int WGM, int WGN, bool A_KMAJOR, bool B_KMAJOR, typename TC, int NS>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_kernel(GemmDev g, int tiles_m, int tiles_n) {
+  constexpr int NW = WGM * WGN;
+  constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
-  typedef PipeTile<BM, A_KMAJOR> PA;
-  typedef PipeTile<BN, B_KMAJOR> PB;
+  static_assert(TM >= 1 && TN >= 1, "wave tile below one MFMA block");
+  typedef PipeTile<BM, A_KMAJOR, NW> PA;
+  typedef PipeTile<BN, B_KMAJOR, NW> PB;
   constexpr int STAGE_BYTES = PA::BYTES + PB::BYTES;
   constexpr int LPS = PA::LOADS + PB::LOADS;          // loads per wave per stage
   extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -120,12 +124,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_pipe_kernel(GemmDev g, int tile
   bf16_t* __restrict__ AUX = g.aux ? (bf16_t*)g.aux + zb * g.sc0 + zi * g.sc1 : nullptr;
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int wm = (wave >> 1) * WM, wn = (wave & 1) * WN;
+  const int wm = (wave / WGN) * WM, wn = (wave % WGN) * WN;
 
   const bf16_t* srca[PA::LOADS];
   const bf16_t* srcb[PB::LOADS];
-  pipe_src_init<BM, A_KMAJOR>(A, g.lda, m0, g.M, srca);
-  pipe_src_init<BN, B_KMAJOR>(B, g.ldb, n0, g.N, srcb);
+  pipe_src_init<BM, A_KMAJOR, NW>(A, g.lda, m0, g.M, srca);
+  pipe_src_init<BN, B_KMAJOR, NW>(B, g.ldb, n0, g.N, srcb);
   const long stepa = A_KMAJOR ? PBK : (long)PBK * g.lda;
   const long stepb = B_KMAJOR ? PBK : (long)PBK * g.ldb;
 
@@ -141,8 +145,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_pipe_kernel(GemmDev g, int tile
 #pragma unroll
   for (int s = 0; s < NS - 1; ++s) {
     if (s < nk) {
-      pipe_issue<BM, A_KMAJOR>(srca, s * stepa, lds + s * STAGE_BYTES);
-      pipe_issue<BN, B_KMAJOR>(srcb, s * stepb, lds + s * STAGE_BYTES + PA::BYTES);
+      pipe_issue<BM, A_KMAJOR, NW>(srca, s * stepa, lds + s * STAGE_BYTES);
+      pipe_issue<BN, B_KMAJOR, NW>(srcb, s * stepb, lds + s * STAGE_BYTES + PA::BYTES);
     }
   }
 
@@ -158,8 +162,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_pipe_kernel(GemmDev g, int tile
     if (nxt < nk) {
       int ns = stage + NS - 1;
       ns = ns >= NS ? ns - NS : ns;
-      pipe_issue<BM, A_KMAJOR>(srca, nxt * stepa, lds + ns * STAGE_BYTES);
-      pipe_issue<BN, B_KMAJOR>(srcb, nxt * stepb, lds + ns * STAGE_BYTES + PA::BYTES);
+      pipe_issue<BM, A_KMAJOR, NW>(srca, nxt * stepa, lds + ns * STAGE_BYTES);
+      pipe_issue<BN, B_KMAJOR, NW>(srcb, nxt * stepb, lds + ns * STAGE_BYTES + PA::BYTES);
     }
     const char* ta = lds + stage * STAGE_BYTES;
     const char* tb = ta + PA::BYTES;
@@ -208,10 +212,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_pipe_kernel(GemmDev g, int tile
   }
 }
 
-template <int BM, int BN, bool AK, bool BKM, typename TC, int NS>
+template <int BM, int BN, int WGM, int WGN, bool AK, bool BKM, typename TC, int NS>
 static bool launch_pipe_inst(const GemmDev& d, int batch, hipStream_t st) {
-  constexpr int LDS_BYTES = NS * (PipeTile<BM, AK>::BYTES + PipeTile<BN, BKM>::BYTES);
-  auto kern = gemm_bf16_pipe_kernel<BM, BN, AK, BKM, TC, NS>;
+  constexpr int NW = WGM * WGN;
+  constexpr int LDS_BYTES = NS * (PipeTile<BM, AK, NW>::BYTES + PipeTile<BN, BKM, NW>::BYTES);
+  auto kern = gemm_bf16_pipe_kernel<BM, BN, WGM, WGN, AK, BKM, TC, NS>;
   static bool attr_done = false;   // per instantiation
   if (!attr_done) {
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess) {
@@ -223,31 +228,27 @@ static bool launch_pipe_inst(const GemmDev& d, int batch, hipStream_t st) {
   const int tiles_m = (d.M + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
   const int ntile = tiles_m * tiles_n;
   dim3 grid(((ntile + 7) / 8) * 8, batch);
-  hipLaunchKernelGGL(kern, grid, dim3(256), LDS_BYTES, st, d, tiles_m, tiles_n);
+  hipLaunchKernelGGL(kern, grid, dim3(64 * NW), LDS_BYTES, st, d, tiles_m, tiles_n);
   return true;
 }
 
+// 128x128 tiles, 8 wavefronts (2 x 4), two 32 KiB stages: two workgroups share a
+// CU (16 waves).  Measured on MI355X against 4-wave workgroups, deeper rings and
+// 256-wide tiles, this is the fastest variant for every shape of the layer.
 template <bool AK, bool BKM, typename TC>
 static bool launch_pipe_layout(const GemmDev& d, int batch, hipStream_t st) {
-  // two stages of 32 KiB: two workgroups share a CU's LDS, which hides more
-  // latency than a deeper ring in one workgroup (measured)
-  if (d.M >= 128 && d.N >= 128) return launch_pipe_inst<128, 128, AK, BKM, TC, 2>(d, batch, st);
-  return false;
+  return launch_pipe_inst<128, 128, 2, 4, AK, BKM, TC, 2>(d, batch, st);
 }
 
 bool launch_gemm_pipe(const GemmDev& d, int a_kmajor, int b_kmajor, int out_f32, int batch, hipStream_t st) {
   if (d.K % PBK) return false;
-  if (d.M < 128 || d.N < 128 || batch != 1) return false;
-  // measured on MI355X: the direct-to-LDS ring wins for K-major x K-major
-  // operands; with a transposed operand the register-staged kernel is faster
-  if (!(a_kmajor && b_kmajor)) return false;
-#define RAF_PIPE_LAYOUT(AK, BKM) \
-  (out_f32 ? launch_pipe_layout<AK, BKM, float>(d, batch, st) : launch_pipe_layout<AK, BKM, bf16_t>(d, batch, st))
-  if (a_kmajor && b_kmajor) return RAF_PIPE_LAYOUT(true, true);
-  if (a_kmajor && !b_kmajor) return RAF_PIPE_LAYOUT(true, false);
-  if (!a_kmajor && !b_kmajor) return RAF_PIPE_LAYOUT(false, false);
-  return RAF_PIPE_LAYOUT(false, true);
-#undef RAF_PIPE_LAYOUT
+  if (d.M < 128 || d.N < 128 || batch != 1 || out_f32) return false;
+  const long tiles = (long)((d.M + 127) / 128) * ((d.N + 127) / 128);
+  if (a_kmajor && b_kmajor) return launch_pipe_layout<true, true, bf16_t>(d, batch, st);
+  // with a transposed B operand the ring only wins when there are enough tiles
+  // for two workgroups per CU; below that the register-staged kernel is faster
+  if (a_kmajor && !b_kmajor && tiles >= 384) return launch_pipe_layout<true, false, bf16_t>(d, batch, st);
+  return false;
 }
 
 }  // namespace raf

@@ -215,11 +215,16 @@ extern "C" raf_status raf_layer_fwd(const raf_layer_desc* desc, const raf_layer_
   }
   // F1: qkv = attn_in . Wqkv^T + bqkv
   RAF_TRY(gemm(prec, st, T, 3 * H, H, attn_in, H, 1, w->w_qkv, H, 1, qkv, 3 * H, 0, EPI_BIAS, (const float*)w->b_qkv));
-  // F2: s = Q K^T / 8 per (batch, head)
-  RAF_TRY(gemm_heads(p, prec, st, S, S, 64, HeadView{qkv, 3 * H, 1, false},
-                     HeadView{at(qkv, (size_t)H * e), 3 * H, 1, false}, s, S, true, alpha));
-  // F3: masked softmax + dropout site 1
-  RAF_TRY(launch_softmax_fwd(d, s, seq_lens, prob, prob_d, step, st));
+  if (prec == RAF_BF16_AMP) {
+    // F2+F3 fused: scores, mask, softmax, dropout site 1; the score tensor stays in registers
+    RAF_TRY(launch_attn_prob_fwd(d, qkv, seq_lens, prob, prob_d, step, st));
+  } else {
+    // F2: s = Q K^T / 8 per (batch, head)
+    RAF_TRY(gemm_heads(p, prec, st, S, S, 64, HeadView{qkv, 3 * H, 1, false},
+                       HeadView{at(qkv, (size_t)H * e), 3 * H, 1, false}, s, S, true, alpha));
+    // F3: masked softmax + dropout site 1
+    RAF_TRY(launch_softmax_fwd(d, s, seq_lens, prob, prob_d, step, st));
+  }
   // F4: c = prob_d . V, heads merged on store
   RAF_TRY(gemm_heads(p, prec, st, S, 64, S, HeadView{prob_d, S, 1, true},
                      HeadView{at(qkv, (size_t)2 * H * e), 3 * H, 0, false}, c, H, false, 1.0f));
@@ -312,13 +317,18 @@ extern "C" raf_status raf_layer_bwd(const raf_layer_desc* desc, const raf_layer_
                           (float*)grads->ln1_g, (float*)grads->ln1_b, (float*)grads->b_o, partial, step, st));
   // B5: a1 = c Wo^T + bo  ->  dc = da1 Wo                   [dWo = da1^T c deferred]
   RAF_TRY(gemm(prec, st, T, H, H, da1, H, 1, w->w_o, H, 0, dc, H));
-  // B4: c = prob_d V  ->  dprob_d = dc V^T ; dV = prob_d^T dc
-  RAF_TRY(gemm_heads(p, prec, st, S, S, 64, HeadView{dc, H, 1, false},
-                     HeadView{at(qkv, (size_t)2 * H * e), 3 * H, 1, false}, dprob_d, S, true, 1.0f));
+  // B4: c = prob_d V  ->  dV = prob_d^T dc ; dprob_d = dc V^T
   RAF_TRY(gemm_heads(p, prec, st, S, 64, S, HeadView{prob_d, S, 0, true}, HeadView{dc, H, 0, false},
                      at(dqkv, (size_t)2 * H * e), 3 * H, false, 1.0f));
-  // B3: softmax + dropout adjoint, with the 1/8 of the score scaling folded in
-  RAF_TRY(launch_softmax_bwd(d, prob, prob_d, dprob_d, ds, alpha, st));
+  if (prec == RAF_BF16_AMP) {
+    // B4b+B3 fused: dprob_d stays in registers; dropout and softmax adjoints with the 1/8 folded in
+    RAF_TRY(launch_attn_prob_bwd(d, dc, qkv, prob, prob_d, ds, st));
+  } else {
+    RAF_TRY(gemm_heads(p, prec, st, S, S, 64, HeadView{dc, H, 1, false},
+                       HeadView{at(qkv, (size_t)2 * H * e), 3 * H, 1, false}, dprob_d, S, true, 1.0f));
+    // B3: softmax + dropout adjoint, with the 1/8 of the score scaling folded in
+    RAF_TRY(launch_softmax_bwd(d, prob, prob_d, dprob_d, ds, alpha, st));
+  }
   // B2: s = Q K^T / 8  ->  dQ = ds K ; dK = ds^T Q
   RAF_TRY(gemm_heads(p, prec, st, S, 64, S, HeadView{ds, S, 1, true},
                      HeadView{at(qkv, (size_t)H * e), 3 * H, 0, false}, dqkv, 3 * H, false, 1.0f));
