@@ -212,7 +212,7 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ a, co
 // LDS and writes one partial row; a second kernel sums the partial rows in a
 // fixed order, so the result does not depend on scheduling.
 constexpr int LN_BWD_MAX_BLOCKS = 512;
-constexpr int LN_BWD_THREADS = 512;   // 8 wavefronts: two workgroups per CU keep 16 rows in flight
+constexpr int LN_BWD_THREADS = 256;
 
 template <typename T, int LPR, int NV, bool HAS_LN>
 __global__ __launch_bounds__(LN_BWD_THREADS) void ln_bwd_kernel(const T* __restrict__ dout, const T* __restrict__ dout2,
@@ -221,7 +221,7 @@ __global__ __launch_bounds__(LN_BWD_THREADS) void ln_bwd_kernel(const T* __restr
                                                      const T* __restrict__ dres, T* __restrict__ dz,
                                                      T* __restrict__ da, float* __restrict__ partial, long nrows,
                                                      int H, DropSite drop, DropSite drop_in) {
-  extern __shared__ float red[];   // [3][H]
+  extern __shared__ float red[];   // [3][8][H/8]: column vec*8+e of sum k sits at k*H + e*(H/8) + vec
   const int lane = threadIdx.x & (LPR - 1);
   const int groups_per_block = LN_BWD_THREADS / LPR;
   const long group = (long)blockIdx.x * groups_per_block + threadIdx.x / LPR;
@@ -339,7 +339,7 @@ __global__ __launch_bounds__(LN_BWD_THREADS) void ln_bwd_kernel(const T* __restr
         if (vec < nvec) {
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
-            const int c = vec * 8 + e;
+            const int c = e * nvec + vec;   // element-major: consecutive lanes hit consecutive banks
             if (w == 0) {
               red[c] = cg[t][e];
               red[H + c] = cb[t][e];
@@ -358,32 +358,38 @@ __global__ __launch_bounds__(LN_BWD_THREADS) void ln_bwd_kernel(const T* __restr
   for (int c = threadIdx.x; c < 3 * H; c += LN_BWD_THREADS) partial[(long)blockIdx.x * 3 * H + c] = red[c];
 }
 
-// out_k[c] = sum_p partial[p][k][c], k < nout.  64 columns per block; the
-// four 64-lane slices of a block take parts p = slice, slice+4, ... and are
+// out_k[c] = sum_p partial[p][k][c], k < nout.  32 columns per block; the
+// eight 32-lane slices of a block take parts p = slice, slice+8, ... and are
 // combined in a fixed order, so the sum is reproducible.
+constexpr int RED_COLS = 32, RED_SLICES = 8;
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int nparts, int ncols,
                                                               int nout, float* o0, float* o1, float* o2,
-                                                              int width_out) {
-  __shared__ float red[4][64];
-  const int c = blockIdx.x * 64 + (threadIdx.x & 63);
-  const int slice = threadIdx.x >> 6;
+                                                              int width_out, int perm_nvec) {
+  __shared__ float red[RED_SLICES][RED_COLS];
+  const int cl = threadIdx.x % RED_COLS;
+  const int c = blockIdx.x * RED_COLS + cl;
+  const int slice = threadIdx.x / RED_COLS;
   const long width = (long)nout * ncols;   // stride between partial rows; only c < width_out is produced
   float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
   if (c < width_out) {
     int p = slice;
-    for (; p + 12 < nparts; p += 16) {
+    for (; p + 3 * RED_SLICES < nparts; p += 4 * RED_SLICES) {
       a0 += partial[(long)p * width + c];
-      a1 += partial[(long)(p + 4) * width + c];
-      a2 += partial[(long)(p + 8) * width + c];
-      a3 += partial[(long)(p + 12) * width + c];
+      a1 += partial[(long)(p + RED_SLICES) * width + c];
+      a2 += partial[(long)(p + 2 * RED_SLICES) * width + c];
+      a3 += partial[(long)(p + 3 * RED_SLICES) * width + c];
     }
-    for (; p < nparts; p += 4) a0 += partial[(long)p * width + c];
+    for (; p < nparts; p += RED_SLICES) a0 += partial[(long)p * width + c];
   }
-  red[slice][threadIdx.x & 63] = (a0 + a1) + (a2 + a3);
+  red[slice][cl] = (a0 + a1) + (a2 + a3);
   __syncthreads();
   if (slice == 0 && c < width_out) {
-    const float acc = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
-    const int k = c / ncols, cc = c % ncols;
+    float acc = 0.f;
+#pragma unroll
+    for (int s = 0; s < RED_SLICES; ++s) acc += red[s][cl];
+    const int k = c / ncols;
+    int cc = c % ncols;
+    if (perm_nvec > 0) cc = (cc % perm_nvec) * 8 + cc / perm_nvec;   // partial rows stored element-major
     float* o = k == 0 ? o0 : (k == 1 ? o1 : o2);
     if (o) o[cc] = acc;
   }
@@ -499,7 +505,7 @@ raf_status launch_ln_fwd(const raf_layer_desc& d, int site, int64_t rows, const 
 static int ln_bwd_blocks(int hidden, int64_t rows) {
   const RowGeom g = row_geom(hidden);
   const long groups_per_block = LN_BWD_THREADS / g.lpr;
-  long nb = (rows + groups_per_block - 1) / groups_per_block;   // one row per group until the block cap
+  long nb = (rows + groups_per_block * 2 - 1) / (groups_per_block * 2);   // two rows per group until the block cap
   if (nb < 1) nb = 1;
   if (nb > LN_BWD_MAX_BLOCKS) nb = LN_BWD_MAX_BLOCKS;
   return (int)nb;
@@ -556,8 +562,8 @@ raf_status launch_ln_bwd(const raf_layer_desc& d, int site, int64_t rows, const 
 #undef CALL
   raf_status rc = check_launch();
   if (rc != RAF_OK) return rc;
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3((3 * H + 63) / 64), dim3(256), 0, st, partial, nb, H, 3,
-                     gamma ? dgamma : nullptr, gamma ? dbeta : nullptr, da ? dbias : nullptr, 3 * H);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((3 * H + RED_COLS - 1) / RED_COLS), dim3(256), 0, st, partial, nb, H, 3,
+                     gamma ? dgamma : nullptr, gamma ? dbeta : nullptr, da ? dbias : nullptr, 3 * H, H / 8);
   return check_launch();
 }
 
@@ -583,8 +589,8 @@ raf_status launch_colsum(int precision, const void* x, int64_t rows, int cols, l
                        partial);
   raf_status rc = check_launch();
   if (rc != RAF_OK) return rc;
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3((out_cols + 63) / 64), dim3(256), 0, st, partial, parts, cols, 1,
-                     out, nullptr, nullptr, out_cols);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((out_cols + RED_COLS - 1) / RED_COLS), dim3(256), 0, st, partial, parts, cols, 1,
+                     out, nullptr, nullptr, out_cols, 0);
   return check_launch();
 }
 
