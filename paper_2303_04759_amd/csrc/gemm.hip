@@ -365,10 +365,8 @@ raf_status launch_gemm_group_wgrad(int precision, const GemmArgs* gs, int count,
   for (int i = count; i <= GEMM_GROUP_MAX; ++i) grp.tile_start[i] = tiles;
   for (int i = count; i < GEMM_GROUP_MAX; ++i) { grp.p[i] = grp.p[0]; grp.tiles_n[i] = 1; }
   dim3 grid(((tiles + 7) / 8) * 8);
-  if (tiles < 384)
-    hipLaunchKernelGGL((gemm_bf16_group_kernel<128, 128, 2, 4, false, false, float>), grid, dim3(512), 0, st, grp);
-  else
-    hipLaunchKernelGGL((gemm_bf16_group_kernel<128, 128, 2, 2, false, false, float>), grid, dim3(256), 0, st, grp);
+  // 8 wavefronts per workgroup measured faster than 4 even with ~1.7 workgroups per CU
+  hipLaunchKernelGGL((gemm_bf16_group_kernel<128, 128, 2, 4, false, false, float>), grid, dim3(512), 0, st, grp);
   return check_launch();
 }
 
