@@ -20,6 +20,10 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+# HBM bytes per launch of the dominant kernel on the bert_base workload, from the two rocprofv3 --pmc
+# runs summarised in profiles/bench_bert_base_hbm_traffic.txt (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00,
+# factors from a plain 256 MiB copy): 53.0 MB read + 24.4 MB written.
+DOMINANT_KERNEL_TRAFFIC_BYTES = {"bert_base": 77.4e6}
 
 
 def gemm_launches(cfg):
@@ -97,6 +101,8 @@ def main():
     ap.add_argument("--workload", default="bert_base")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline leg")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy (5x) so FETCH_SIZE/WRITE_SIZE counters can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU by design (no collectives, no sharding); run with --gpus 1")
@@ -176,6 +182,13 @@ def main():
         dom_flops = sum(2.0 * M * N * Kd for (_, M, N, Kd, *_r) in dom) / len(dom)
         achieved = dom_flops / (dom_ms * 1e-3) / 1e12
 
+    if args.calibrate_copy:
+        src = torch.zeros(128 * 1024 * 1024, dtype=torch.bfloat16, device="cuda")     # 256 MiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
     samples_per_s = cfg["batch"] / (ms_per_step * 1e-3)
     valid_tokens = int(np.sum(inp["seq_lens"])) if inp["seq_lens"] is not None else lay.T
     total_flops = sum(2.0 * M * N * Kd * b for (_, M, N, Kd, _a, _b, _f, _e, b) in gemm_launches(cfg))
@@ -191,10 +204,11 @@ def main():
         "tokens_per_s_valid": valid_tokens / (ms_per_step * 1e-3),
         "step_gemm_tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
         "wall_ms_per_step": wall * 1e3 / K,
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel<128,128,K-major A,K-major B> (forward weight GEMMs)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_pipe_kernel<128,128,2x4 waves,K-major A,K-major B,2 stages> (forward weight GEMMs)",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "avg_launch_us": dom_ms * 1e3,
-                     "flops_per_launch": dom_flops, "traffic": None},
+                     "flops_per_launch": dom_flops,
+                     "traffic": DOMINANT_KERNEL_TRAFFIC_BYTES.get(args.workload), "traffic_unit": "bytes/launch"},
     }
     if not args.no_cpu:
         from oracle.step import train_step
