@@ -34,8 +34,12 @@ def smoke():
     ref = train_step(cfg, p, z, z, inp["x"], inp["G"], inp["seq_lens"], 1, dict(ADAM, loss_scale=cfg["loss_scale"]))
     errs = {"y": rel_fro(lay.host(lay.y), ref["y"]), "dx": rel_fro(lay.host(lay.dx), ref["dx"])}
     for k in PARAM_NAMES:
-        errs["g_" + k] = rel_fro(lay.host(lay.grads[k]), ref["grads"][k])
-        errs["w_" + k] = rel_fro(lay.host(lay.master[k]), ref["params"][k])
+        g_ref = ref["grads"][k].reshape(inp["params"][k].shape)
+        errs["g_" + k] = rel_fro(lay.host(lay.grads[k]), g_ref)
+        # Adam's first step is sign-like: where the true gradient vanishes (the key bias) its sign is
+        # rounding noise on either side, so updated weights are compared where |g| is not negligible
+        cond = np.abs(g_ref) > 1e-4 * np.sqrt(np.mean(g_ref ** 2))
+        errs["w_" + k] = rel_fro(lay.host(lay.master[k])[cond], ref["params"][k][cond])
     worst_fwd = errs["y"]
     worst_bwd = max(v for k, v in errs.items() if k != "y")
     print("smoke: fwd rel err %.3e, worst grad/weight rel err %.3e" % (worst_fwd, worst_bwd))
