@@ -232,6 +232,180 @@ static bool launch_pipe_inst(const GemmDev& d, int batch, hipStream_t st) {
   return true;
 }
 
+// ---------------------------------------------------------------------------
+// Tiles of 64*WGM x 48*WGN outputs for K-major operands.  The widths 48, 96,
+// 144 and 192 let the launcher pick a tile count that fills the 256 CUs in
+// whole rounds when 128-wide tiles would leave most of the last round idle
+// (N = 2304: 16 x 16 tiles of 256x144, one per CU, instead of 576 of 128x128),
+// and the tall variants halve the bytes fetched per flop, which is what bounds
+// these kernels (about 40 bytes/clock/CU arrive from L2).  Each of the
+// WGM x WGN wavefronts owns 64 x 48 outputs as 4 x 3 blocks of
+// v_mfma_f32_16x16x32_bf16.  Same direct-to-LDS ring and swizzle as above, NS
+// stages deep; the KiB chunks of a stage are dealt round-robin to the waves, so
+// some waves issue one load more than others and each wave counts its own.
+template <int CHUNKS, int NW>
+__device__ __forceinline__ void w48_src_init(const bf16_t* base, long ld, int row0, int nrows, int first,
+                                             const bf16_t* (&src)[(CHUNKS + NW - 1) / NW + 1]) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+#pragma unroll
+  for (int i = 0; i < (CHUNKS + NW - 1) / NW + 1; ++i) {
+    int q = i * NW + wave - first;            // which KiB (8 rows) of the tile
+    q = q < 0 ? 0 : (q < CHUNKS ? q : CHUNKS - 1);   // out-of-range slots keep a valid address they never use
+    const int r = q * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ ((r >> 1) & 7);
+    int gr = row0 + r;
+    gr = gr < nrows ? gr : nrows - 1;
+    src[i] = base + (long)gr * ld + c * 8;
+  }
+}
+
+// `first` shifts the dealing so that the B chunks continue where the A chunks stopped
+template <int CHUNKS, int NW>
+__device__ __forceinline__ void w48_issue(const bf16_t* (&src)[(CHUNKS + NW - 1) / NW + 1], long koff, char* lds_tile,
+                                          int first) {
+  const int wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int i = 0; i < (CHUNKS + NW - 1) / NW + 1; ++i) {
+    const int q = i * NW + wave - first;
+    if (q >= 0 && q < CHUNKS)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src[i] + koff),
+                                       (lds_void_ptr)(lds_tile + q * 1024), 16, 0, 0);
+  }
+}
+
+// 16 rows x 32 contraction values of a K-major tile: lane l holds row l&15, elements 8*(l>>4) .. +7 of k-half kk
+__device__ __forceinline__ bf16x8_t w48_fragment(const char* lds_tile, int row0, int kk) {
+  const int lane = threadIdx.x & 63;
+  const int r = row0 + (lane & 15);
+  const int c = kk * 4 + (lane >> 4);
+  return *reinterpret_cast<const bf16x8_t*>(lds_tile + r * 128 + ((c ^ ((r >> 1) & 7)) << 4));
+}
+
+// s_waitcnt vmcnt(n) for a wave-uniform run-time n (conservative above 24)
+__device__ __forceinline__ void wait_vmcnt_dyn(int n) {
+  switch (n) {
+#define RAF_VMCNT_CASE(N) case N: wait_vmcnt<N>(); break;
+    RAF_VMCNT_CASE(1) RAF_VMCNT_CASE(2) RAF_VMCNT_CASE(3) RAF_VMCNT_CASE(4) RAF_VMCNT_CASE(5) RAF_VMCNT_CASE(6)
+    RAF_VMCNT_CASE(7) RAF_VMCNT_CASE(8) RAF_VMCNT_CASE(9) RAF_VMCNT_CASE(10) RAF_VMCNT_CASE(11) RAF_VMCNT_CASE(12)
+    RAF_VMCNT_CASE(13) RAF_VMCNT_CASE(14) RAF_VMCNT_CASE(15) RAF_VMCNT_CASE(16) RAF_VMCNT_CASE(17) RAF_VMCNT_CASE(18)
+    RAF_VMCNT_CASE(19) RAF_VMCNT_CASE(20) RAF_VMCNT_CASE(21) RAF_VMCNT_CASE(22) RAF_VMCNT_CASE(23) RAF_VMCNT_CASE(24)
+#undef RAF_VMCNT_CASE
+    default: wait_vmcnt<0>(); break;
+  }
+}
+
+template <int WGM, int WGN, int NS, typename TC>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_w48_kernel(GemmDev g, int tiles_m, int tiles_n) {
+  constexpr int NW = WGM * WGN, BM = 64 * WGM, BN = 48 * WGN;
+  constexpr int ACH = BM / 8, BCH = BN / 8;           // KiB per operand tile
+  constexpr int STAGE_BYTES = (ACH + BCH) * 1024;
+  constexpr int BFIRST = ACH % NW;                    // wave that takes B chunk 0
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+
+  const int ntile = tiles_m * tiles_n;
+  const int per = (ntile + 7) >> 3;
+  const int t = (int)(blockIdx.x & 7) * per + (int)(blockIdx.x >> 3);   // XCD x takes tiles [x*per, (x+1)*per)
+  if (t >= ntile) return;
+  const int m0 = (t / tiles_n) * BM, n0 = (t % tiles_n) * BN;
+
+  const bf16_t* __restrict__ A = (const bf16_t*)g.a;
+  const bf16_t* __restrict__ B = (const bf16_t*)g.b;
+  TC* __restrict__ C = (TC*)g.c;
+  bf16_t* __restrict__ AUX = (bf16_t*)g.aux;
+
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wm = (wave / WGN) * 64, wn = (wave % WGN) * 48;
+
+  const bf16_t* srca[(ACH + NW - 1) / NW + 1];
+  const bf16_t* srcb[(BCH + NW - 1) / NW + 1];
+  w48_src_init<ACH, NW>(A, g.lda, m0, g.M, 0, srca);
+  w48_src_init<BCH, NW>(B, g.ldb, n0, g.N, BFIRST, srcb);
+  // loads this wave issues per stage: chunk f of the ACH+BCH goes to wave f % NW
+  const int my_loads = (ACH + BCH) / NW + (wave < (ACH + BCH) % NW ? 1 : 0);
+
+  f32x4_t acc[4][3];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 3; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  const int nk = g.K / PBK;
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s)
+    if (s < nk) {
+      w48_issue<ACH, NW>(srca, (long)s * PBK, lds + s * STAGE_BYTES, 0);
+      w48_issue<BCH, NW>(srcb, (long)s * PBK, lds + s * STAGE_BYTES + ACH * 1024, BFIRST);
+    }
+  int stage = 0;
+  for (int it = 0; it < nk; ++it) {
+    // k-steps it+1 .. it+NS-2 may stay in flight; k-step `it` must have landed
+    const int ahead = nk - 1 - it < NS - 2 ? nk - 1 - it : NS - 2;
+    wait_vmcnt_dyn(ahead * my_loads);
+    __builtin_amdgcn_s_barrier();   // stage `it` is complete for every wave; stage it-1 is free
+    if (it + NS - 1 < nk) {
+      int ns = stage + NS - 1;
+      ns = ns >= NS ? ns - NS : ns;
+      char* nxt = lds + ns * STAGE_BYTES;
+      w48_issue<ACH, NW>(srca, (long)(it + NS - 1) * PBK, nxt, 0);
+      w48_issue<BCH, NW>(srcb, (long)(it + NS - 1) * PBK, nxt + ACH * 1024, BFIRST);
+    }
+    const char* ta = lds + stage * STAGE_BYTES;
+    const char* tb = ta + ACH * 1024;
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+      bf16x8_t fa[4], fb[3];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) fa[i] = w48_fragment(ta, wm + i * 16, kk);
+#pragma unroll
+      for (int j = 0; j < 3; ++j) fb[j] = w48_fragment(tb, wn + j * 16, kk);
+      // operands swapped: a lane ends with output row (l & 15) and 4 consecutive columns 4*(l>>4) + r
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 3; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+    }
+    stage = stage + 1 == NS ? 0 : stage + 1;
+  }
+
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = m0 + wm + i * 16 + (lane & 15);
+    if (row < g.M) {
+#pragma unroll
+      for (int j = 0; j < 3; ++j) {
+        const int col = n0 + wn + j * 16 + 4 * (lane >> 4);
+        if (col < g.N) {
+          float v[4] = {acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]};
+          epilogue_store4<TC>(g, C, AUX, row, col, v);
+        }
+      }
+    }
+  }
+}
+
+template <int WGM, int WGN, int NS, typename TC>
+static bool launch_w48_inst(const GemmDev& d, hipStream_t st) {
+  constexpr int BM = 64 * WGM, BN = 48 * WGN;
+  constexpr int LDS_BYTES = NS * (BM / 8 + BN / 8) * 1024;
+  static_assert(LDS_BYTES <= 160 * 1024, "ring exceeds the LDS of a CU");
+  static_assert((NS - 2) * ((BM / 8 + BN / 8 + WGM * WGN - 1) / (WGM * WGN)) <= 24, "in-flight loads exceed wait_vmcnt_dyn");
+  auto kern = gemm_bf16_w48_kernel<WGM, WGN, NS, TC>;
+  static bool attr_done = false;   // per instantiation
+  if (!attr_done) {
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess) {
+      (void)hipGetLastError();
+      return false;
+    }
+    attr_done = true;
+  }
+  const int tiles_m = (d.M + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
+  const int ntile = tiles_m * tiles_n;
+  dim3 grid(((ntile + 7) / 8) * 8);
+  hipLaunchKernelGGL(kern, grid, dim3(64 * WGM * WGN), LDS_BYTES, st, d, tiles_m, tiles_n);
+  return true;
+}
+
 // 128x128 tiles, 8 wavefronts (2 x 4), two 32 KiB stages: two workgroups share a
 // CU (16 waves).  Measured on MI355X against 4-wave workgroups, deeper rings and
 // 256-wide tiles, this is the fastest variant for every shape of the layer.
@@ -244,7 +418,32 @@ bool launch_gemm_pipe(const GemmDev& d, int a_kmajor, int b_kmajor, int out_f32,
   if (d.K % PBK) return false;
   if (d.M < 128 || d.N < 128 || batch != 1 || out_f32) return false;
   const long tiles = (long)((d.M + 127) / 128) * ((d.N + 127) / 128);
-  if (a_kmajor && b_kmajor) return launch_pipe_layout<true, true, bf16_t>(d, batch, st);
+  if (a_kmajor && b_kmajor) {
+    // Tile choice.  Every CU has to work through ceil(tiles / 256) tiles, so the cost of a tiling is that count
+    // times the tile area; among equals the larger tile fetches fewer bytes per flop, then the squarer one.
+    struct Cand { int bm, bn; };
+    static const Cand cands[] = {{128, 128}, {128, 96}, {128, 144}, {128, 192}, {256, 144}, {256, 192}};
+    int best = 0;
+    long best_cost = 0, best_area = 0, best_perim = 0;
+    for (int i = 0; i < 6; ++i) {
+      const Cand& c = cands[i];
+      if (i > 0 && d.N % c.bn) continue;
+      const long tl = (long)((d.M + c.bm - 1) / c.bm) * ((d.N + c.bn - 1) / c.bn);
+      const long area = (long)c.bm * c.bn, cost = ((tl + 255) / 256) * area, perim = c.bm + c.bn;
+      if (i == 0 || cost < best_cost || (cost == best_cost && (area > best_area || (area == best_area && perim < best_perim)))) {
+        best = i; best_cost = cost; best_area = area; best_perim = perim;
+      }
+    }
+    switch (best) {
+      case 1: return launch_w48_inst<2, 2, 2, bf16_t>(d, st);
+      case 2: return launch_w48_inst<2, 3, 2, bf16_t>(d, st);
+      case 3: return launch_w48_inst<2, 4, 2, bf16_t>(d, st);
+      case 4: return launch_w48_inst<4, 3, 2, bf16_t>(d, st);
+      case 5: return launch_w48_inst<4, 4, 2, bf16_t>(d, st);
+      default: break;
+    }
+    return launch_pipe_layout<true, true, bf16_t>(d, batch, st);
+  }
   // with a transposed B operand the ring only wins when there are enough tiles
   // for two workgroups per CU; below that the register-staged kernel is faster
   if (a_kmajor && !b_kmajor && tiles >= 384) return launch_pipe_layout<true, false, bf16_t>(d, batch, st);
