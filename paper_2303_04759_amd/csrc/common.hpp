@@ -198,13 +198,19 @@ inline RowGeom row_geom(int len) {
   while (lpr < 64 && lpr < nvec) lpr <<= 1;
   int nv = 1;
   while (lpr * nv < nvec) nv <<= 1;
+  // three vectors per lane keep every lane busy for rows of 3 * 2^k vectors (768 = 32 lanes x 3 x 8)
+  if (lpr * nv != nvec && lpr >= 32 && (lpr / 2) * 3 == nvec) return RowGeom{lpr / 2, 3};
+  if (lpr * nv != nvec && lpr == 64 && nvec == 192) return RowGeom{64, 3};
   return RowGeom{lpr, nv};
 }
 
 #define RAF_DISPATCH_GEOM(GEOM, CALL)                   \
   do {                                                  \
     const RowGeom _g = (GEOM);                          \
-    if (_g.lpr == 4) { CALL(4, 1); }                    \
+    if (_g.nv == 3 && _g.lpr == 16) { CALL(16, 3); }    \
+    else if (_g.nv == 3 && _g.lpr == 32) { CALL(32, 3); } \
+    else if (_g.nv == 3) { CALL(64, 3); }               \
+    else if (_g.lpr == 4) { CALL(4, 1); }               \
     else if (_g.lpr == 8) { CALL(8, 1); }               \
     else if (_g.lpr == 16) { CALL(16, 1); }             \
     else if (_g.lpr == 32) { CALL(32, 1); }             \
@@ -244,6 +250,11 @@ inline GemmArgs gemm_args_default() {
 raf_status launch_gemm(int precision, const GemmArgs& g, hipStream_t st);
 // up to 4 independent weight-gradient GEMMs (A, B MN-major, float out) in one launch
 raf_status launch_gemm_group_wgrad(int precision, const GemmArgs* gs, int count, hipStream_t st);
+// dst[c][r] = src[r][c] for up to 4 dense row-major bf16 matrices (rows, cols multiples of 8) in one launch
+struct TransposeJob {
+  const void* src; void* dst; int rows, cols;
+};
+raf_status launch_transpose_bf16(const TransposeJob* jobs, int count, hipStream_t st);
 
 raf_status launch_softmax_fwd(const raf_layer_desc& d, const void* s, const int32_t* lens, void* prob, void* prob_d,
                               uint64_t step, hipStream_t st);

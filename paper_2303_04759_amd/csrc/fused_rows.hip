@@ -220,8 +220,8 @@ __global__ __launch_bounds__(LN_BWD_THREADS) void ln_bwd_kernel(const T* __restr
                                                      const float* __restrict__ rstd, const float* __restrict__ gamma,
                                                      const T* __restrict__ dres, T* __restrict__ dz,
                                                      T* __restrict__ da, float* __restrict__ partial, long nrows,
-                                                     int H, DropSite drop, DropSite drop_in) {
-  extern __shared__ float red[];   // [3][8][H/8]: column vec*8+e of sum k sits at k*H + e*(H/8) + vec
+                                                     int H, DropSite drop, DropSite drop_in, int slices) {
+  extern __shared__ float red[];   // [slices][3][8][H/8]: column vec*8+e of sum k sits at k*H + e*(H/8) + vec
   const int lane = threadIdx.x & (LPR - 1);
   const int groups_per_block = LN_BWD_THREADS / LPR;
   const long group = (long)blockIdx.x * groups_per_block + threadIdx.x / LPR;
@@ -328,26 +328,30 @@ __global__ __launch_bounds__(LN_BWD_THREADS) void ln_bwd_kernel(const T* __restr
         cd[t][e] += __shfl_xor(cd[t][e], o, WAVE);
       }
     }
-  // the waves add their sums into LDS one after the other (fixed order)
+  // The waves deposit their sums in `slices` LDS copies ([slice][3][H], element-major columns so that consecutive
+  // lanes hit consecutive banks): wave w owns copy w % slices in round w / slices, and the copies are then added in
+  // a fixed order.  With one copy per wave (small H) this is a single barrier.
   const int wave = threadIdx.x >> 6;
   const int wlane = threadIdx.x & 63;
-  for (int w = 0; w < LN_BWD_THREADS / 64; ++w) {
-    if (wave == w && wlane < LPR) {
+  constexpr int NWAVE = LN_BWD_THREADS / 64;
+  float* mine = red + (wave % slices) * 3 * H;
+  for (int round = 0; round < NWAVE / slices; ++round) {
+    if (wave / slices == round && wlane < LPR) {
 #pragma unroll
       for (int t = 0; t < NV; ++t) {
         const int vec = lane + LPR * t;
         if (vec < nvec) {
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
-            const int c = e * nvec + vec;   // element-major: consecutive lanes hit consecutive banks
-            if (w == 0) {
-              red[c] = cg[t][e];
-              red[H + c] = cb[t][e];
-              red[2 * H + c] = cd[t][e];
+            const int c = e * nvec + vec;
+            if (round == 0) {
+              mine[c] = cg[t][e];
+              mine[H + c] = cb[t][e];
+              mine[2 * H + c] = cd[t][e];
             } else {
-              red[c] += cg[t][e];
-              red[H + c] += cb[t][e];
-              red[2 * H + c] += cd[t][e];
+              mine[c] += cg[t][e];
+              mine[H + c] += cb[t][e];
+              mine[2 * H + c] += cd[t][e];
             }
           }
         }
@@ -355,13 +359,17 @@ __global__ __launch_bounds__(LN_BWD_THREADS) void ln_bwd_kernel(const T* __restr
     }
     __syncthreads();
   }
-  for (int c = threadIdx.x; c < 3 * H; c += LN_BWD_THREADS) partial[(long)blockIdx.x * 3 * H + c] = red[c];
+  for (int c = threadIdx.x; c < 3 * H; c += LN_BWD_THREADS) {
+    float v = red[c];
+    for (int sl = 1; sl < slices; ++sl) v += red[sl * 3 * H + c];
+    partial[(long)blockIdx.x * 3 * H + c] = v;
+  }
 }
 
-// out_k[c] = sum_p partial[p][k][c], k < nout.  32 columns per block; the
-// eight 32-lane slices of a block take parts p = slice, slice+8, ... and are
-// combined in a fixed order, so the sum is reproducible.
-constexpr int RED_COLS = 32, RED_SLICES = 8;
+// out_k[c] = sum_p partial[p][k][c], k < nout.  16 columns per block; the 16
+// slices of a block take parts p = slice, slice+16, ... eight loads at a time
+// and are combined in a fixed order, so the sum is reproducible.
+constexpr int RED_COLS = 16, RED_SLICES = 16, RED_UNROLL = 8;
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int nparts, int ncols,
                                                               int nout, float* o0, float* o1, float* o2,
                                                               int width_out, int perm_nvec) {
@@ -370,28 +378,31 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
   const int c = blockIdx.x * RED_COLS + cl;
   const int slice = threadIdx.x / RED_COLS;
   const long width = (long)nout * ncols;   // stride between partial rows; only c < width_out is produced
-  float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+  float acc[RED_UNROLL];
+#pragma unroll
+  for (int u = 0; u < RED_UNROLL; ++u) acc[u] = 0.f;
   if (c < width_out) {
     int p = slice;
-    for (; p + 3 * RED_SLICES < nparts; p += 4 * RED_SLICES) {
-      a0 += partial[(long)p * width + c];
-      a1 += partial[(long)(p + RED_SLICES) * width + c];
-      a2 += partial[(long)(p + 2 * RED_SLICES) * width + c];
-      a3 += partial[(long)(p + 3 * RED_SLICES) * width + c];
+    for (; p + (RED_UNROLL - 1) * RED_SLICES < nparts; p += RED_UNROLL * RED_SLICES) {
+      float v[RED_UNROLL];
+#pragma unroll
+      for (int u = 0; u < RED_UNROLL; ++u) v[u] = partial[(long)(p + u * RED_SLICES) * width + c];
+#pragma unroll
+      for (int u = 0; u < RED_UNROLL; ++u) acc[u] += v[u];
     }
-    for (; p < nparts; p += RED_SLICES) a0 += partial[(long)p * width + c];
+    for (; p < nparts; p += RED_SLICES) acc[0] += partial[(long)p * width + c];
   }
-  red[slice][cl] = (a0 + a1) + (a2 + a3);
+  red[slice][cl] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
   __syncthreads();
   if (slice == 0 && c < width_out) {
-    float acc = 0.f;
+    float sum = 0.f;
 #pragma unroll
-    for (int s = 0; s < RED_SLICES; ++s) acc += red[s][cl];
+    for (int sl = 0; sl < RED_SLICES; ++sl) sum += red[sl][cl];
     const int k = c / ncols;
     int cc = c % ncols;
     if (perm_nvec > 0) cc = (cc % perm_nvec) * 8 + cc / perm_nvec;   // partial rows stored element-major
     float* o = k == 0 ? o0 : (k == 1 ? o1 : o2);
-    if (o) o[cc] = acc;
+    if (o) o[cc] = sum;
   }
 }
 
@@ -405,7 +416,19 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ x, lo
   const int rl = threadIdx.x >> 6;
   float acc[8] = {};
   if (cv * 8 < cols) {
-    for (long r = (long)blockIdx.y * 4 + rl; r < rows; r += (long)gridDim.y * 4) {
+    const long stride = (long)gridDim.y * 4;
+    long r = (long)blockIdx.y * 4 + rl;
+    // eight independent 16-byte loads in flight per lane
+    for (; r + 7 * stride < rows; r += 8 * stride) {
+      float v[8][8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) Vec8<T>::load(x + (r + u * stride) * ld + cv * 8, v[u]);
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] += v[u][e];
+    }
+    for (; r < rows; r += stride) {
       float v[8];
       Vec8<T>::load(x + r * ld + cv * 8, v);
 #pragma unroll
@@ -505,7 +528,7 @@ raf_status launch_ln_fwd(const raf_layer_desc& d, int site, int64_t rows, const 
 static int ln_bwd_blocks(int hidden, int64_t rows) {
   const RowGeom g = row_geom(hidden);
   const long groups_per_block = LN_BWD_THREADS / g.lpr;
-  long nb = (rows + groups_per_block * 2 - 1) / (groups_per_block * 2);   // two rows per group until the block cap
+  long nb = (rows + groups_per_block - 1) / groups_per_block;   // one row per group until the block cap
   if (nb < 1) nb = 1;
   if (nb > LN_BWD_MAX_BLOCKS) nb = LN_BWD_MAX_BLOCKS;
   return (int)nb;
@@ -535,27 +558,28 @@ raf_status launch_ln_bwd(const raf_layer_desc& d, int site, int64_t rows, const 
   const DropSite drop_in = make_drop_site(d, site_in, step);
   const int H = d.hidden;
   const int nb = ln_bwd_blocks(H, rows);
-  const size_t shm = (size_t)3 * H * sizeof(float);
+  const int slices = H <= 1024 ? 4 : (H <= 2048 ? 2 : 1);   // LDS copies of the column sums: at most 48 KiB
+  const size_t shm = (size_t)slices * 3 * H * sizeof(float);
 #define CALL(LPR, NV)                                                                                               \
   {                                                                                                                 \
     if (d.precision == RAF_F32) {                                                                                   \
       if (gamma)                                                                                                    \
         hipLaunchKernelGGL((ln_bwd_kernel<float, LPR, NV, true>), dim3(nb), dim3(LN_BWD_THREADS), shm, st, (const float*)dout, \
                            (const float*)dout2, (const float*)z, mu, rstd, gamma, (const float*)dres, (float*)dz,   \
-                           (float*)da, partial, (long)rows, H, drop, drop_in);                                               \
+                           (float*)da, partial, (long)rows, H, drop, drop_in, slices);                                               \
       else                                                                                                          \
         hipLaunchKernelGGL((ln_bwd_kernel<float, LPR, NV, false>), dim3(nb), dim3(LN_BWD_THREADS), shm, st,                    \
                            (const float*)dout, (const float*)dout2, (const float*)z, mu, rstd, gamma,               \
-                           (const float*)dres, (float*)dz, (float*)da, partial, (long)rows, H, drop, drop_in);               \
+                           (const float*)dres, (float*)dz, (float*)da, partial, (long)rows, H, drop, drop_in, slices);               \
     } else {                                                                                                        \
       if (gamma)                                                                                                    \
         hipLaunchKernelGGL((ln_bwd_kernel<bf16_t, LPR, NV, true>), dim3(nb), dim3(LN_BWD_THREADS), shm, st,                    \
                            (const bf16_t*)dout, (const bf16_t*)dout2, (const bf16_t*)z, mu, rstd, gamma,            \
-                           (const bf16_t*)dres, (bf16_t*)dz, (bf16_t*)da, partial, (long)rows, H, drop, drop_in);   \
+                           (const bf16_t*)dres, (bf16_t*)dz, (bf16_t*)da, partial, (long)rows, H, drop, drop_in, slices);   \
       else                                                                                                          \
         hipLaunchKernelGGL((ln_bwd_kernel<bf16_t, LPR, NV, false>), dim3(nb), dim3(LN_BWD_THREADS), shm, st,                   \
                            (const bf16_t*)dout, (const bf16_t*)dout2, (const bf16_t*)z, mu, rstd, gamma,            \
-                           (const bf16_t*)dres, (bf16_t*)dz, (bf16_t*)da, partial, (long)rows, H, drop, drop_in);   \
+                           (const bf16_t*)dres, (bf16_t*)dz, (bf16_t*)da, partial, (long)rows, H, drop, drop_in, slices);   \
     }                                                                                                               \
   }
   RAF_DISPATCH_GEOM(row_geom(H), CALL);

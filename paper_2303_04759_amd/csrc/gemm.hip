@@ -335,6 +335,76 @@ static GemmDev to_dev(const GemmArgs& g) {
   return d;
 }
 
+// ------------------------------------------------------- bf16 transposes --
+// The input-gradient products dX = dY . W contract over the rows of the
+// row-major weight, i.e. over its strided dimension.  With a transposed copy of
+// W both operands are contiguous along the contraction and the product runs on
+// the K-major kernels, the fastest ones; writing the copy costs about as much as
+// reading the weight once.  64x64 tiles through LDS, 16-byte accesses both ways.
+constexpr int TRANSPOSE_MAX = 4;
+struct TransposeDev {
+  const uint16_t* src[TRANSPOSE_MAX];
+  uint16_t* dst[TRANSPOSE_MAX];
+  int rows[TRANSPOSE_MAX], cols[TRANSPOSE_MAX], tiles_c[TRANSPOSE_MAX];
+  int tile_start[TRANSPOSE_MAX + 1];
+};
+
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(TransposeDev g) {
+  __shared__ uint16_t tile[64][64 + 2];
+  int j = 0;
+  while (j + 1 < TRANSPOSE_MAX && (int)blockIdx.x >= g.tile_start[j + 1]) ++j;
+  const int t = blockIdx.x - g.tile_start[j];
+  const int r0 = (t / g.tiles_c[j]) * 64, c0 = (t % g.tiles_c[j]) * 64;
+  const int rows = g.rows[j], cols = g.cols[j];
+  const uint16_t* __restrict__ src = g.src[j];
+  uint16_t* __restrict__ dst = g.dst[j];
+  const int chunk = threadIdx.x & 7, line = threadIdx.x >> 3;   // 8 chunks of 8 elements per 64-wide line
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+    const int r = line + 32 * pass;
+    if (r0 + r < rows && c0 + chunk * 8 < cols) {
+      const uint4 v = *reinterpret_cast<const uint4*>(src + (long)(r0 + r) * cols + c0 + chunk * 8);
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        tile[r][chunk * 8 + 2 * e] = (uint16_t)(w[e] & 0xffffu);
+        tile[r][chunk * 8 + 2 * e + 1] = (uint16_t)(w[e] >> 16);
+      }
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+    const int c = line + 32 * pass;             // output row = input column
+    if (c0 + c < cols && r0 + chunk * 8 < rows) {
+      uint32_t w[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        w[e] = (uint32_t)tile[chunk * 8 + 2 * e][c] | ((uint32_t)tile[chunk * 8 + 2 * e + 1][c] << 16);
+      *reinterpret_cast<uint4*>(dst + (long)(c0 + c) * rows + r0 + chunk * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+  }
+}
+
+raf_status launch_transpose_bf16(const TransposeJob* jobs, int count, hipStream_t st) {
+  if (!jobs || count <= 0 || count > TRANSPOSE_MAX) return RAF_EINVAL;
+  TransposeDev g{};
+  int tiles = 0;
+  for (int i = 0; i < count; ++i) {
+    if (!jobs[i].src || !jobs[i].dst || jobs[i].rows <= 0 || jobs[i].cols <= 0) return RAF_EINVAL;
+    if ((jobs[i].rows % 8) || (jobs[i].cols % 8) || !aligned16(jobs[i].src) || !aligned16(jobs[i].dst)) return RAF_EINVAL;
+    g.src[i] = (const uint16_t*)jobs[i].src; g.dst[i] = (uint16_t*)jobs[i].dst;
+    g.rows[i] = jobs[i].rows; g.cols[i] = jobs[i].cols;
+    g.tiles_c[i] = (jobs[i].cols + 63) / 64;
+    g.tile_start[i] = tiles;
+    tiles += ((jobs[i].rows + 63) / 64) * g.tiles_c[i];
+  }
+  for (int i = count; i <= TRANSPOSE_MAX; ++i) g.tile_start[i] = tiles;
+  for (int i = count; i < TRANSPOSE_MAX; ++i) { g.src[i] = g.src[0]; g.dst[i] = g.dst[0]; g.rows[i] = g.cols[i] = 8; g.tiles_c[i] = 1; }
+  hipLaunchKernelGGL(transpose_bf16_kernel, dim3(tiles), dim3(256), 0, st, g);
+  return check_launch();
+}
+
 // Weight-gradient form only: A and B both MN-major, float output, no batch.
 raf_status launch_gemm_group_wgrad(int precision, const GemmArgs* gs, int count, hipStream_t st) {
   if (count <= 0 || count > GEMM_GROUP_MAX || !gs) return RAF_EINVAL;

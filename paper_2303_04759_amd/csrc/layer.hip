@@ -45,7 +45,7 @@ struct Plan {
   // scratch, forward
   size_t s, a;
   // scratch, backward
-  size_t dz2, da, da1, du, dffn, dz1, dc, dprob_d, ds, dqkv, dattn, partial;
+  size_t dz2, da, da1, du, dffn, dz1, dc, dprob_d, ds, dqkv, dattn, partial, wt_qkv, wt_o, wt_1, wt_2;
   size_t scratch_bytes;
 };
 
@@ -98,6 +98,12 @@ static Plan make_plan(const raf_layer_desc& d) {
   if (c1 > pf) pf = c1;
   if (c2 > pf) pf = c2;
   p.partial = bump(b, pf * 4);
+  if (d.precision == RAF_BF16_AMP) {   // transposed bf16 weight copies for the input-gradient products
+    p.wt_qkv = bump(b, (size_t)3 * p.H * p.H * 2);
+    p.wt_o = bump(b, (size_t)p.H * p.H * 2);
+    p.wt_1 = bump(b, (size_t)p.F * p.H * 2);
+    p.wt_2 = bump(b, (size_t)p.H * p.F * 2);
+  }
   p.scratch_bytes = f > b ? f : b;
   return p;
 }
@@ -294,6 +300,17 @@ extern "C" raf_status raf_layer_bwd(const raf_layer_desc* desc, const raf_layer_
   void* dattn = at(scratch, p.dattn);
   float* partial = (float*)at(scratch, p.partial);
 
+  // bf16: the input-gradient products below use K-major transposed copies of the four weights
+  const bool wt = prec == RAF_BF16_AMP;
+  const void* wt_qkv = at(scratch, p.wt_qkv);   // [H][3H]
+  const void* wt_o = at(scratch, p.wt_o);       // [H][H]
+  const void* wt_1 = at(scratch, p.wt_1);       // [H][F]
+  const void* wt_2 = at(scratch, p.wt_2);       // [F][H]
+  if (wt) {
+    const TransposeJob jobs[4] = {{w->w_qkv, (void*)wt_qkv, 3 * H, H}, {w->w_o, (void*)wt_o, H, H},
+                                  {w->w_1, (void*)wt_1, F, H}, {w->w_2, (void*)wt_2, H, F}};
+    RAF_TRY(launch_transpose_bf16(jobs, 4, st));
+  }
   // B9: adjoint of the output block
   if (d.pre_ln)   // y = z1 + drop3(a2): da2 = dy * keep3/(1-p)
     RAF_TRY(launch_ln_bwd(d, 3, T, dy, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, da, nullptr,
@@ -304,10 +321,11 @@ extern "C" raf_status raf_layer_bwd(const raf_layer_desc* desc, const raf_layer_
   // The four weight gradients (dW = dY^T X) are deferred to one grouped launch
   // at the end: each alone has too few output tiles to fill 256 CUs.
   // B8: a2 = g W2^T + b2  ->  du = (da2 W2) * gelu'(u)      [dW2 = da2^T g deferred]
-  RAF_TRY(gemm(prec, st, T, F, H, da, H, 1, w->w_2, F, 0, du, F, 0, EPI_MUL_GELU_GRAD, nullptr, u, F, d.gelu_tanh));
+  RAF_TRY(gemm(prec, st, T, F, H, da, H, 1, wt ? wt_2 : w->w_2, wt ? H : F, wt ? 1 : 0, du, F, 0, EPI_MUL_GELU_GRAD,
+               nullptr, u, F, d.gelu_tanh));
   // B7: u = ffn_in W1^T + b1  ->  db1 ; dffn = du W1          [dW1 = du^T ffn_in deferred]
   RAF_TRY(launch_colsum(prec, du, T, F, F, (float*)grads->b_1, partial, st));
-  RAF_TRY(gemm(prec, st, T, H, F, du, F, 1, w->w_1, H, 0, dffn, H));
+  RAF_TRY(gemm(prec, st, T, H, F, du, F, 1, wt ? wt_1 : w->w_1, wt ? F : H, wt ? 1 : 0, dffn, H));
   // B6: the LayerNorm between the two halves, the residual, dropout site 2
   if (d.pre_ln)   // ffn_in = LN2(z1); dz1 = dy + LN2'(dffn); da1 = dz1 * keep2/(1-p)
     RAF_TRY(launch_ln_bwd(d, 2, T, dffn, nullptr, z1, mu2, rstd2, (const float*)w->ln2_g, dy, dz1, da1,
@@ -316,7 +334,7 @@ extern "C" raf_status raf_layer_bwd(const raf_layer_desc* desc, const raf_layer_
     RAF_TRY(launch_ln_bwd(d, 2, T, dz2, dffn, z1, mu1, rstd1, (const float*)w->ln1_g, nullptr, dz1, da1,
                           (float*)grads->ln1_g, (float*)grads->ln1_b, (float*)grads->b_o, partial, step, st));
   // B5: a1 = c Wo^T + bo  ->  dc = da1 Wo                   [dWo = da1^T c deferred]
-  RAF_TRY(gemm(prec, st, T, H, H, da1, H, 1, w->w_o, H, 0, dc, H));
+  RAF_TRY(gemm(prec, st, T, H, H, da1, H, 1, wt ? wt_o : w->w_o, H, wt ? 1 : 0, dc, H));
   // B4: c = prob_d V  ->  dV = prob_d^T dc ; dprob_d = dc V^T
   RAF_TRY(gemm_heads(p, prec, st, S, 64, S, HeadView{prob_d, S, 0, true}, HeadView{dc, H, 0, false},
                      at(dqkv, (size_t)2 * H * e), 3 * H, false, 1.0f));
@@ -337,13 +355,14 @@ extern "C" raf_status raf_layer_bwd(const raf_layer_desc* desc, const raf_layer_
   // B1: qkv = attn_in Wqkv^T + bqkv
   RAF_TRY(launch_colsum(prec, dqkv, T, 3 * H, 3 * H, (float*)grads->b_qkv, partial, st));
   if (d.pre_ln) {
-    RAF_TRY(gemm(prec, st, T, H, 3 * H, dqkv, 3 * H, 1, w->w_qkv, H, 0, dattn, H));
+    RAF_TRY(gemm(prec, st, T, H, 3 * H, dqkv, 3 * H, 1, wt ? wt_qkv : w->w_qkv, wt ? 3 * H : H, wt ? 1 : 0, dattn, H));
     // attn_in = LN1(x); dx = dz1 + LN1'(dattn)
     RAF_TRY(launch_ln_bwd(d, 0, T, dattn, nullptr, x, mu1, rstd1, (const float*)w->ln1_g, dz1, dx, nullptr,
                           (float*)grads->ln1_g, (float*)grads->ln1_b, nullptr, partial, step, st));
   } else {
     // dx = dz1 + dqkv Wqkv (residual add in the epilogue)
-    RAF_TRY(gemm(prec, st, T, H, 3 * H, dqkv, 3 * H, 1, w->w_qkv, H, 0, dx, H, 0, EPI_ADD_RES, nullptr, dz1, H));
+    RAF_TRY(gemm(prec, st, T, H, 3 * H, dqkv, 3 * H, 1, wt ? wt_qkv : w->w_qkv, wt ? 3 * H : H, wt ? 1 : 0, dx, H, 0,
+                 EPI_ADD_RES, nullptr, dz1, H));
   }
   // dW2 = da2^T g ; dW1 = du^T ffn_in ; dWqkv = dqkv^T attn_in ; dWo = da1^T c   (float outputs)
   GemmArgs wg[4];
