@@ -203,13 +203,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev g, in
 // Several independent problems of one layout in a single launch (the four
 // weight-gradient GEMMs of a layer: each alone has too few tiles to fill the
 // chip).  tile_start[p] is the first linear tile of problem p.
-constexpr int GEMM_GROUP_MAX = 4;
-struct GemmGroupDev {
-  GemmDev p[GEMM_GROUP_MAX];
-  int tile_start[GEMM_GROUP_MAX + 1];
-  int tiles_n[GEMM_GROUP_MAX];
-  int count;
-};
 
 template <int BM, int BN, int WGM, int WGN, bool A_KMAJOR, bool B_KMAJOR, typename TC>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_group_kernel(GemmGroupDev grp) {
@@ -423,6 +416,11 @@ raf_status launch_gemm_group_wgrad(int precision, const GemmArgs* gs, int count,
     }
     return RAF_OK;
   }
+  if (precision == RAF_BF16_AMP) {
+    GemmDev ds[GEMM_GROUP_MAX];
+    for (int i = 0; i < count; ++i) ds[i] = to_dev(gs[i]);
+    if (launch_gemm_group_spec(ds, count, st)) return check_launch();
+  }
   GemmGroupDev grp;
   grp.count = count;
   int tiles = 0;
@@ -450,6 +448,9 @@ raf_status launch_gemm(int precision, const GemmArgs& g, hipStream_t st) {
     const long sb_k = g.b_kmajor ? 1 : g.ldb, sb_j = g.b_kmajor ? g.ldb : 1;
     hipLaunchKernelGGL(gemm_f32_kernel, grid, dim3(256), 0, st, d, sa_i, sa_k, sb_k, sb_j);
   } else if (precision == RAF_BF16_AMP) {
+    if (!g.a_kmajor && !g.b_kmajor && g.out_f32 && g.batch == 1 && g.epilogue == EPI_NONE &&
+        launch_gemm_group_spec(&d, 1, st))
+      return check_launch();
     if (launch_gemm_pipe(d, g.a_kmajor, g.b_kmajor, g.out_f32, g.batch, st)) return check_launch();
     if (g.a_kmajor && g.b_kmajor) launch_bf16_layout<true, true>(d, g.out_f32, g.batch, st);
     else if (g.a_kmajor && !g.b_kmajor) launch_bf16_layout<true, false>(d, g.out_f32, g.batch, st);

@@ -101,6 +101,21 @@ __device__ __forceinline__ void epilogue_store4(const GemmDev& g, TC* __restrict
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x8_t __attribute__((ext_vector_type(8)));
 
+// Several independent problems of one layout in a single launch; tile_start[p]
+// is the first linear tile of problem p, tiles_n[p] its tile columns.
+constexpr int GEMM_GROUP_MAX = 4;
+struct GemmGroupDev {
+  GemmDev p[GEMM_GROUP_MAX];
+  int tile_start[GEMM_GROUP_MAX + 1];
+  int tiles_n[GEMM_GROUP_MAX];
+  int count;
+};
+
+// Weight-gradient group (both operands MN-major, float output) on the
+// producer/consumer direct-to-LDS kernel (gemm_pipe.hip); false when a problem
+// does not fit it (K % 64, sizes below one tile).
+bool launch_gemm_group_spec(const GemmDev* ds, int count, hipStream_t st);
+
 // Pipelined direct-to-LDS kernel family (gemm_pipe.hip).  Returns false when
 // the problem does not meet its requirements (K % 64, tile fit) and the
 // caller must use the staged kernel instead.

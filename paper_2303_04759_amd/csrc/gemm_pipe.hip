@@ -31,9 +31,9 @@ typedef __attribute__((address_space(3))) void* lds_void_ptr;
 // per-lane global source addresses of this wave's direct loads for k-step 0
 template <int ROWS, bool KMAJOR, int NW>
 __device__ __forceinline__ void pipe_src_init(const bf16_t* base, long ld, int row0, int nrows,
-                                              const bf16_t* (&src)[PipeTile<ROWS, KMAJOR, NW>::LOADS]) {
+                                              const bf16_t* (&src)[PipeTile<ROWS, KMAJOR, NW>::LOADS], int wave) {
   typedef PipeTile<ROWS, KMAJOR, NW> PT;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int lane = threadIdx.x & 63;
 #pragma unroll
   for (int i = 0; i < PT::LOADS; ++i) {
     const int q = wave * PT::LOADS + i;       // which KiB of the tile
@@ -56,9 +56,8 @@ __device__ __forceinline__ void pipe_src_init(const bf16_t* base, long ld, int r
 
 template <int ROWS, bool KMAJOR, int NW>
 __device__ __forceinline__ void pipe_issue(const bf16_t* (&src)[PipeTile<ROWS, KMAJOR, NW>::LOADS], long koff,
-                                           char* lds_tile) {
+                                           char* lds_tile, int wave) {
   typedef PipeTile<ROWS, KMAJOR, NW> PT;
-  const int wave = threadIdx.x >> 6;
 #pragma unroll
   for (int i = 0; i < PT::LOADS; ++i) {
     char* dst = lds_tile + (wave * PT::LOADS + i) * 1024;
@@ -92,6 +91,19 @@ __device__ __forceinline__ bf16x8_t pipe_fragment(const char* lds_tile, int row,
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
+// s_waitcnt vmcnt(n) for a wave-uniform run-time n (conservative above 24)
+__device__ __forceinline__ void wait_vmcnt_dyn(int n) {
+  switch (n) {
+#define RAF_VMCNT_CASE(N) case N: wait_vmcnt<N>(); break;
+    RAF_VMCNT_CASE(1) RAF_VMCNT_CASE(2) RAF_VMCNT_CASE(3) RAF_VMCNT_CASE(4) RAF_VMCNT_CASE(5) RAF_VMCNT_CASE(6)
+    RAF_VMCNT_CASE(7) RAF_VMCNT_CASE(8) RAF_VMCNT_CASE(9) RAF_VMCNT_CASE(10) RAF_VMCNT_CASE(11) RAF_VMCNT_CASE(12)
+    RAF_VMCNT_CASE(13) RAF_VMCNT_CASE(14) RAF_VMCNT_CASE(15) RAF_VMCNT_CASE(16) RAF_VMCNT_CASE(17) RAF_VMCNT_CASE(18)
+    RAF_VMCNT_CASE(19) RAF_VMCNT_CASE(20) RAF_VMCNT_CASE(21) RAF_VMCNT_CASE(22) RAF_VMCNT_CASE(23) RAF_VMCNT_CASE(24)
+#undef RAF_VMCNT_CASE
+    default: wait_vmcnt<0>(); break;
+  }
 }
 
 template <int BM, int BN, int WGM, int WGN, bool A_KMAJOR, bool B_KMAJOR, typename TC, int NS>
@@ -128,8 +140,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_kernel(GemmDev 
 
   const bf16_t* srca[PA::LOADS];
   const bf16_t* srcb[PB::LOADS];
-  pipe_src_init<BM, A_KMAJOR, NW>(A, g.lda, m0, g.M, srca);
-  pipe_src_init<BN, B_KMAJOR, NW>(B, g.ldb, n0, g.N, srcb);
+  pipe_src_init<BM, A_KMAJOR, NW>(A, g.lda, m0, g.M, srca, wave);
+  pipe_src_init<BN, B_KMAJOR, NW>(B, g.ldb, n0, g.N, srcb, wave);
   const long stepa = A_KMAJOR ? PBK : (long)PBK * g.lda;
   const long stepb = B_KMAJOR ? PBK : (long)PBK * g.ldb;
 
@@ -145,8 +157,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_kernel(GemmDev 
 #pragma unroll
   for (int s = 0; s < NS - 1; ++s) {
     if (s < nk) {
-      pipe_issue<BM, A_KMAJOR, NW>(srca, s * stepa, lds + s * STAGE_BYTES);
-      pipe_issue<BN, B_KMAJOR, NW>(srcb, s * stepb, lds + s * STAGE_BYTES + PA::BYTES);
+      pipe_issue<BM, A_KMAJOR, NW>(srca, s * stepa, lds + s * STAGE_BYTES, wave);
+      pipe_issue<BN, B_KMAJOR, NW>(srcb, s * stepb, lds + s * STAGE_BYTES + PA::BYTES, wave);
     }
   }
 
@@ -162,8 +174,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_kernel(GemmDev 
     if (nxt < nk) {
       int ns = stage + NS - 1;
       ns = ns >= NS ? ns - NS : ns;
-      pipe_issue<BM, A_KMAJOR, NW>(srca, nxt * stepa, lds + ns * STAGE_BYTES);
-      pipe_issue<BN, B_KMAJOR, NW>(srcb, nxt * stepb, lds + ns * STAGE_BYTES + PA::BYTES);
+      pipe_issue<BM, A_KMAJOR, NW>(srca, nxt * stepa, lds + ns * STAGE_BYTES, wave);
+      pipe_issue<BN, B_KMAJOR, NW>(srcb, nxt * stepb, lds + ns * STAGE_BYTES + PA::BYTES, wave);
     }
     const char* ta = lds + stage * STAGE_BYTES;
     const char* tb = ta + PA::BYTES;
@@ -233,6 +245,170 @@ static bool launch_pipe_inst(const GemmDev& d, int batch, hipStream_t st) {
 }
 
 // ---------------------------------------------------------------------------
+// Producer/consumer form of the ring for a group of problems (the four weight
+// gradients of a layer: long contraction, operands contiguous along M and N).
+// A wave is held for roughly a hundred cycles per 1-KiB direct load, so loads
+// issued by the computing waves serialise with their MFMAs, and loads that go
+// through registers are capped near 16 bytes/clock/CU.  Here NP producer waves
+// do nothing but issue the direct-to-LDS loads, NS-1 k-steps ahead, while the
+// WGM*WGN consumer waves only read fragments and issue MFMAs.  One workgroup
+// barrier per k-step keeps both sides in step: after barrier `it` the consumers
+// work on stage it while the producers refill the stage that was just freed
+// and then wait until stage it+1 has landed.
+template <int BM, int BN, int WGM, int WGN, bool A_KMAJOR, bool B_KMAJOR, typename TC, int NS, int NP>
+__global__ __launch_bounds__(64 * (WGM * WGN + NP)) void gemm_bf16_spec_kernel(GemmGroupDev grp) {
+  constexpr int NC = WGM * WGN;
+  constexpr int WM = BM / WGM, WN = BN / WGN;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  static_assert(TM >= 1 && TN >= 1, "wave tile below one MFMA block");
+  static_assert(NS >= 3, "the producers need a stage to fill while one is read and one is in flight");
+  typedef PipeTile<BM, A_KMAJOR, NP> PA;
+  typedef PipeTile<BN, B_KMAJOR, NP> PB;
+  constexpr int STAGE_BYTES = PA::BYTES + PB::BYTES;
+  constexpr int LPS = PA::LOADS + PB::LOADS;          // loads per producer wave per stage
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+
+  const int ntile = grp.tile_start[grp.count];
+  const int per = (ntile + 7) >> 3;
+  const int t = (int)(blockIdx.x & 7) * per + (int)(blockIdx.x >> 3);   // XCD x takes tiles [x*per, (x+1)*per)
+  if (t >= ntile) return;
+  int pi = 0;
+#pragma unroll
+  for (int q = 1; q < GEMM_GROUP_MAX; ++q)
+    if (q < grp.count && t >= grp.tile_start[q]) pi = q;
+  const GemmDev& g = grp.p[pi];                        // selected with wave-uniform scalar loads
+  const int lt = t - grp.tile_start[pi];
+  const int tn = grp.tiles_n[pi];
+  const int m0 = (lt / tn) * BM, n0 = (lt % tn) * BN;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int nk = g.K / PBK;
+
+  if (wave >= NC) {
+    // ------------------------------------------------------------ producer
+    const int pw = wave - NC;
+    const bf16_t* srca[PA::LOADS];
+    const bf16_t* srcb[PB::LOADS];
+    pipe_src_init<BM, A_KMAJOR, NP>((const bf16_t*)g.a, g.lda, m0, g.M, srca, pw);
+    pipe_src_init<BN, B_KMAJOR, NP>((const bf16_t*)g.b, g.ldb, n0, g.N, srcb, pw);
+    const long stepa = A_KMAJOR ? PBK : (long)PBK * g.lda;
+    const long stepb = B_KMAJOR ? PBK : (long)PBK * g.ldb;
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+      if (s < nk) {
+        pipe_issue<BM, A_KMAJOR, NP>(srca, s * stepa, lds + s * STAGE_BYTES, pw);
+        pipe_issue<BN, B_KMAJOR, NP>(srcb, s * stepb, lds + s * STAGE_BYTES + PA::BYTES, pw);
+      }
+    int stage = 0;
+    for (int it = 0; it < nk; ++it) {
+      // k-steps it+1 .. it+NS-2 may stay in flight; k-step `it` must have landed
+      const int ahead = nk - 1 - it < NS - 2 ? nk - 1 - it : NS - 2;
+      wait_vmcnt_dyn(ahead * LPS);
+      __builtin_amdgcn_s_barrier();   // stage `it` handed to the consumers; stage it-1 is free
+      const int nxt = it + NS - 1;
+      if (nxt < nk) {
+        int ns = stage + NS - 1;
+        ns = ns >= NS ? ns - NS : ns;
+        pipe_issue<BM, A_KMAJOR, NP>(srca, nxt * stepa, lds + ns * STAGE_BYTES, pw);
+        pipe_issue<BN, B_KMAJOR, NP>(srcb, nxt * stepb, lds + ns * STAGE_BYTES + PA::BYTES, pw);
+      }
+      stage = stage + 1 == NS ? 0 : stage + 1;
+    }
+    return;
+  }
+
+  // -------------------------------------------------------------- consumer
+  const int wm = (wave / WGN) * WM, wn = (wave % WGN) * WN;
+  f32x16_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  int stage = 0;
+  for (int it = 0; it < nk; ++it) {
+    __builtin_amdgcn_s_barrier();   // stage `it` is complete
+    const char* ta = lds + stage * STAGE_BYTES;
+    const char* tb = ta + PA::BYTES;
+    // fragment loads run one sub-step ahead of the MFMAs that consume them
+    bf16x8_t fa[2][TM], fb[2][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[0][i] = pipe_fragment<BM, A_KMAJOR>(ta, wm + i * 32, 0);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[0][j] = pipe_fragment<BN, B_KMAJOR>(tb, wn + j * 32, 0);
+#pragma unroll
+    for (int kk = 0; kk < PBK / 16; ++kk) {
+      const int cur = kk & 1, nx = cur ^ 1;
+      if (kk + 1 < PBK / 16) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[nx][i] = pipe_fragment<BM, A_KMAJOR>(ta, wm + i * 32, kk + 1);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[nx][j] = pipe_fragment<BN, B_KMAJOR>(tb, wn + j * 32, kk + 1);
+      }
+      // operands swapped: a lane holds 4 consecutive output columns per register group
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[cur][j], fa[cur][i], acc[i][j], 0, 0, 0);
+    }
+    stage = stage + 1 == NS ? 0 : stage + 1;
+  }
+
+  TC* __restrict__ C = (TC*)g.c;
+  bf16_t* __restrict__ AUX = (bf16_t*)g.aux;
+  // register r of lane l holds output row (l & 31), column 8*(r/4) + 4*(l/32) + r%4 of its 32x32 block
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int row = m0 + wm + i * 32 + (lane & 31);
+    if (row < g.M) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int col = n0 + wn + j * 32 + 8 * q + 4 * (lane >> 5);
+          if (col < g.N) {
+            float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+            epilogue_store4<TC>(g, C, AUX, row, col, v);
+          }
+        }
+    }
+  }
+}
+
+bool launch_gemm_group_spec(const GemmDev* ds, int count, hipStream_t st) {
+  constexpr int BM = 256, BN = 128, WGM = 4, WGN = 2, NS = 3, NP = 8;
+  if (!ds || count <= 0 || count > GEMM_GROUP_MAX) return false;
+  GemmGroupDev grp;
+  grp.count = count;
+  int tiles = 0;
+  for (int i = 0; i < count; ++i) {
+    if (ds[i].K % PBK || ds[i].M < BM || ds[i].N < BN || (ds[i].M % 8) || (ds[i].N % 8)) return false;
+    grp.p[i] = ds[i];
+    grp.tile_start[i] = tiles;
+    grp.tiles_n[i] = (ds[i].N + BN - 1) / BN;
+    tiles += ((ds[i].M + BM - 1) / BM) * grp.tiles_n[i];
+  }
+  for (int i = count; i <= GEMM_GROUP_MAX; ++i) grp.tile_start[i] = tiles;
+  for (int i = count; i < GEMM_GROUP_MAX; ++i) { grp.p[i] = grp.p[0]; grp.tiles_n[i] = 1; }
+  constexpr int LDS_BYTES = NS * (BM + BN) * PBK * 2;
+  static_assert(LDS_BYTES <= 160 * 1024, "ring exceeds the LDS of a CU");
+  auto kern = gemm_bf16_spec_kernel<BM, BN, WGM, WGN, false, false, float, NS, NP>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess) {
+      (void)hipGetLastError();
+      return false;
+    }
+    attr_done = true;
+  }
+  dim3 grid(((tiles + 7) / 8) * 8);
+  hipLaunchKernelGGL(kern, grid, dim3(64 * (WGM * WGN + NP)), LDS_BYTES, st, grp);
+  return true;
+}
+
+// ---------------------------------------------------------------------------
 // Tiles of 64*WGM x 48*WGN outputs for K-major operands.  The widths 48, 96,
 // 144 and 192 let the launcher pick a tile count that fills the 256 CUs in
 // whole rounds when 128-wide tiles would leave most of the last round idle
@@ -281,25 +457,17 @@ __device__ __forceinline__ bf16x8_t w48_fragment(const char* lds_tile, int row0,
   return *reinterpret_cast<const bf16x8_t*>(lds_tile + r * 128 + ((c ^ ((r >> 1) & 7)) << 4));
 }
 
-// s_waitcnt vmcnt(n) for a wave-uniform run-time n (conservative above 24)
-__device__ __forceinline__ void wait_vmcnt_dyn(int n) {
-  switch (n) {
-#define RAF_VMCNT_CASE(N) case N: wait_vmcnt<N>(); break;
-    RAF_VMCNT_CASE(1) RAF_VMCNT_CASE(2) RAF_VMCNT_CASE(3) RAF_VMCNT_CASE(4) RAF_VMCNT_CASE(5) RAF_VMCNT_CASE(6)
-    RAF_VMCNT_CASE(7) RAF_VMCNT_CASE(8) RAF_VMCNT_CASE(9) RAF_VMCNT_CASE(10) RAF_VMCNT_CASE(11) RAF_VMCNT_CASE(12)
-    RAF_VMCNT_CASE(13) RAF_VMCNT_CASE(14) RAF_VMCNT_CASE(15) RAF_VMCNT_CASE(16) RAF_VMCNT_CASE(17) RAF_VMCNT_CASE(18)
-    RAF_VMCNT_CASE(19) RAF_VMCNT_CASE(20) RAF_VMCNT_CASE(21) RAF_VMCNT_CASE(22) RAF_VMCNT_CASE(23) RAF_VMCNT_CASE(24)
-#undef RAF_VMCNT_CASE
-    default: wait_vmcnt<0>(); break;
-  }
-}
-
-template <int WGM, int WGN, int NS, typename TC>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_w48_kernel(GemmDev g, int tiles_m, int tiles_n) {
-  constexpr int NW = WGM * WGN, BM = 64 * WGM, BN = 48 * WGN;
+// KS = 2 doubles the waves of a workgroup without adding LDS traffic: waves w and w + WGM*WGN share one 64x48
+// output block, each takes one 32-deep half of every k-step, and the halves are added through LDS at the end (each
+// wave of the pair then finishes half of the rows).  For tiles with only 4-8 waves this gives every SIMD a second
+// wave to issue MFMAs while the first waits for its LDS fragments.
+template <int WGM, int WGN, int NS, int KS, typename TC>
+__global__ __launch_bounds__(64 * WGM * WGN * KS) void gemm_bf16_w48_kernel(GemmDev g, int tiles_m, int tiles_n) {
+  constexpr int NT = WGM * WGN, NW = NT * KS, BM = 64 * WGM, BN = 48 * WGN;
   constexpr int ACH = BM / 8, BCH = BN / 8;           // KiB per operand tile
   constexpr int STAGE_BYTES = (ACH + BCH) * 1024;
   constexpr int BFIRST = ACH % NW;                    // wave that takes B chunk 0
+  static_assert(KS == 1 || KS == 2, "one or two waves per output block");
   extern __shared__ __attribute__((aligned(1024))) char lds[];
 
   const int ntile = tiles_m * tiles_n;
@@ -314,7 +482,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_w48_kernel(GemmDev g
   bf16_t* __restrict__ AUX = (bf16_t*)g.aux;
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int wm = (wave / WGN) * 64, wn = (wave % WGN) * 48;
+  const int wt = wave % NT, kg = wave / NT;           // output block of this wave, its half of each k-step
+  const int wm = (wt / WGN) * 64, wn = (wt % WGN) * 48;
 
   const bf16_t* srca[(ACH + NW - 1) / NW + 1];
   const bf16_t* srcb[(BCH + NW - 1) / NW + 1];
@@ -352,7 +521,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_w48_kernel(GemmDev g
     const char* ta = lds + stage * STAGE_BYTES;
     const char* tb = ta + ACH * 1024;
 #pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
+    for (int kh = 0; kh < 2 / KS; ++kh) {
+      const int kk = KS == 2 ? kg : kh;
       bf16x8_t fa[4], fb[3];
 #pragma unroll
       for (int i = 0; i < 4; ++i) fa[i] = w48_fragment(ta, wm + i * 16, kk);
@@ -368,8 +538,33 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_w48_kernel(GemmDev g
     stage = stage + 1 == NS ? 0 : stage + 1;
   }
 
+  int i_begin = 0, i_end = 4;
+  if (KS == 2) {
+    // exchange: the wave with kg = 0 finishes row blocks 0-1, its partner row blocks 2-3; each sends the other half
+    __builtin_amdgcn_s_barrier();   // every wave is done with the ring
+    f32x4_t* xch = reinterpret_cast<f32x4_t*>(lds) + (wt * 2 + (kg ^ 1)) * 6 * 64;   // slot read by the partner
+#pragma unroll
+    for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+      for (int j = 0; j < 3; ++j) xch[(ii * 3 + j) * 64 + lane] = kg ? acc[ii][j] : acc[2 + ii][j];   // static indices: no scratch
+    __syncthreads();
+    const f32x4_t* got = reinterpret_cast<const f32x4_t*>(lds) + (wt * 2 + kg) * 6 * 64;
+#pragma unroll
+    for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+      for (int j = 0; j < 3; ++j) {
+        const f32x4_t o = got[(ii * 3 + j) * 64 + lane];
+        // fixed order: first k-half plus second k-half
+        if (kg == 0) acc[ii][j] = acc[ii][j] + o;
+        else acc[2 + ii][j] = o + acc[2 + ii][j];
+      }
+    i_begin = kg * 2;
+    i_end = i_begin + 2;
+  }
+
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
+    if (i < i_begin || i >= i_end) continue;
     const int row = m0 + wm + i * 16 + (lane & 15);
     if (row < g.M) {
 #pragma unroll
@@ -384,13 +579,182 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_w48_kernel(GemmDev g
   }
 }
 
-template <int WGM, int WGN, int NS, typename TC>
-static bool launch_w48_inst(const GemmDev& d, hipStream_t st) {
+// Same tiles with the waves specialised: NP producer waves only issue the direct-to-LDS loads (a wave is held for
+// roughly a hundred cycles per 1-KiB load instruction, so loads issued by the computing waves serialise with their
+// MFMAs), the WGM*WGN*KS consumer waves only read fragments and issue MFMAs.  One workgroup barrier per k-step keeps
+// both sides in step: after barrier `it` the consumers work on stage it while the producers refill the stage that was
+// freed and then wait until stage it+1 has landed.
+template <int WGM, int WGN, int NS, int KS, int NP, typename TC>
+__global__ __launch_bounds__(64 * (WGM * WGN * KS + NP)) void gemm_bf16_w48s_kernel(GemmDev g, int tiles_m, int tiles_n) {
+  constexpr int NT = WGM * WGN, NC = NT * KS, BM = 64 * WGM, BN = 48 * WGN;
+  constexpr int ACH = BM / 8, BCH = BN / 8;           // KiB per operand tile
+  constexpr int STAGE_BYTES = (ACH + BCH) * 1024;
+  constexpr int BFIRST = ACH % NP;                    // producer that takes B chunk 0
+  static_assert(KS == 1 || KS == 2, "one or two waves per output block");
+  static_assert(NS >= 3, "the producers need a stage to fill while one is read and one is in flight");
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+
+  const int ntile = tiles_m * tiles_n;
+  const int per = (ntile + 7) >> 3;
+  const int t = (int)(blockIdx.x & 7) * per + (int)(blockIdx.x >> 3);   // XCD x takes tiles [x*per, (x+1)*per)
+  if (t >= ntile) return;
+  const int m0 = (t / tiles_n) * BM, n0 = (t % tiles_n) * BN;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int nk = g.K / PBK;
+
+  if (wave >= NC) {
+    // ------------------------------------------------------------ producer
+    const int pw = wave - NC;
+    const bf16_t* __restrict__ A = (const bf16_t*)g.a;
+    const bf16_t* __restrict__ B = (const bf16_t*)g.b;
+    constexpr int LA = (ACH + NP - 1) / NP + 1, LB = (BCH + NP - 1) / NP + 1;
+    const bf16_t* srca[LA];
+    const bf16_t* srcb[LB];
+#pragma unroll
+    for (int i = 0; i < LA; ++i) {
+      int q = i * NP + pw;
+      q = q < ACH ? q : ACH - 1;
+      const int r = q * 8 + (lane >> 3);
+      int gr = m0 + r;
+      gr = gr < g.M ? gr : g.M - 1;
+      srca[i] = A + (long)gr * g.lda + (((lane & 7) ^ ((r >> 1) & 7)) << 3);
+    }
+#pragma unroll
+    for (int i = 0; i < LB; ++i) {
+      int q = i * NP + pw - BFIRST;
+      q = q < 0 ? 0 : (q < BCH ? q : BCH - 1);
+      const int r = q * 8 + (lane >> 3);
+      int gr = n0 + r;
+      gr = gr < g.N ? gr : g.N - 1;
+      srcb[i] = B + (long)gr * g.ldb + (((lane & 7) ^ ((r >> 1) & 7)) << 3);
+    }
+    const int my_loads = (ACH + BCH) / NP + (pw < (ACH + BCH) % NP ? 1 : 0);
+    auto issue = [&](int kstep, int stage) {
+      char* base = lds + stage * STAGE_BYTES;
+      const long koff = (long)kstep * PBK;
+#pragma unroll
+      for (int i = 0; i < LA; ++i) {
+        const int q = i * NP + pw;
+        if (q < ACH)
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(srca[i] + koff),
+                                           (lds_void_ptr)(base + q * 1024), 16, 0, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < LB; ++i) {
+        const int q = i * NP + pw - BFIRST;
+        if (q >= 0 && q < BCH)
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(srcb[i] + koff),
+                                           (lds_void_ptr)(base + (ACH + q) * 1024), 16, 0, 0);
+      }
+    };
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+      if (s < nk) issue(s, s);
+    int stage = 0;
+    for (int it = 0; it < nk; ++it) {
+      // k-steps it+1 .. it+NS-2 may stay in flight; k-step `it` must have landed
+      const int ahead = nk - 1 - it < NS - 2 ? nk - 1 - it : NS - 2;
+      wait_vmcnt_dyn(ahead * my_loads);
+      __builtin_amdgcn_s_barrier();   // stage `it` handed to the consumers; stage it-1 is free
+      if (it + NS - 1 < nk) {
+        int ns = stage + NS - 1;
+        ns = ns >= NS ? ns - NS : ns;
+        issue(it + NS - 1, ns);
+      }
+      stage = stage + 1 == NS ? 0 : stage + 1;
+    }
+    if (KS == 2) {   // the consumers' exchange has two more barriers
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_s_barrier();
+    }
+    return;
+  }
+
+  // -------------------------------------------------------------- consumer
+  TC* __restrict__ C = (TC*)g.c;
+  bf16_t* __restrict__ AUX = (bf16_t*)g.aux;
+  const int wt = wave % NT, kg = wave / NT;           // output block of this wave, its half of each k-step
+  const int wm = (wt / WGN) * 64, wn = (wt % WGN) * 48;
+  f32x4_t acc[4][3];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 3; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  int stage = 0;
+  for (int it = 0; it < nk; ++it) {
+    __builtin_amdgcn_s_barrier();   // stage `it` is complete
+    const char* ta = lds + stage * STAGE_BYTES;
+    const char* tb = ta + ACH * 1024;
+#pragma unroll
+    for (int kh = 0; kh < 2 / KS; ++kh) {
+      const int kk = KS == 2 ? kg : kh;
+      bf16x8_t fa[4], fb[3];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) fa[i] = w48_fragment(ta, wm + i * 16, kk);
+#pragma unroll
+      for (int j = 0; j < 3; ++j) fb[j] = w48_fragment(tb, wn + j * 16, kk);
+      // operands swapped: a lane ends with output row (l & 15) and 4 consecutive columns 4*(l>>4) + r
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 3; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+    }
+    stage = stage + 1 == NS ? 0 : stage + 1;
+  }
+
+  int i_begin = 0, i_end = 4;
+  if (KS == 2) {
+    // exchange: the wave with kg = 0 finishes row blocks 0-1, its partner row blocks 2-3; each sends the other half
+    __builtin_amdgcn_s_barrier();   // every wave is done with the ring
+    f32x4_t* xch = reinterpret_cast<f32x4_t*>(lds) + (wt * 2 + (kg ^ 1)) * 6 * 64;   // slot read by the partner
+#pragma unroll
+    for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+      for (int j = 0; j < 3; ++j) xch[(ii * 3 + j) * 64 + lane] = kg ? acc[ii][j] : acc[2 + ii][j];   // static indices: no scratch
+    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): the writes above have reached LDS
+    __builtin_amdgcn_s_barrier();
+    const f32x4_t* got = reinterpret_cast<const f32x4_t*>(lds) + (wt * 2 + kg) * 6 * 64;
+#pragma unroll
+    for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+      for (int j = 0; j < 3; ++j) {
+        const f32x4_t o = got[(ii * 3 + j) * 64 + lane];
+        // fixed order: first k-half plus second k-half
+        if (kg == 0) acc[ii][j] = acc[ii][j] + o;
+        else acc[2 + ii][j] = o + acc[2 + ii][j];
+      }
+    i_begin = kg * 2;
+    i_end = i_begin + 2;
+  }
+
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (i < i_begin || i >= i_end) continue;
+    const int row = m0 + wm + i * 16 + (lane & 15);
+    if (row < g.M) {
+#pragma unroll
+      for (int j = 0; j < 3; ++j) {
+        const int col = n0 + wn + j * 16 + 4 * (lane >> 4);
+        if (col < g.N) {
+          float v[4] = {acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]};
+          epilogue_store4<TC>(g, C, AUX, row, col, v);
+        }
+      }
+    }
+  }
+}
+
+template <int WGM, int WGN, int NS, int KS, int NP, typename TC>
+static bool launch_w48s_inst(const GemmDev& d, hipStream_t st) {
   constexpr int BM = 64 * WGM, BN = 48 * WGN;
-  constexpr int LDS_BYTES = NS * (BM / 8 + BN / 8) * 1024;
+  constexpr int RING_BYTES = NS * (BM / 8 + BN / 8) * 1024;
+  constexpr int XCH_BYTES = KS == 2 ? WGM * WGN * 2 * 6 * 64 * 16 : 0;   // accumulator exchange of the wave pairs
+  constexpr int LDS_BYTES = RING_BYTES > XCH_BYTES ? RING_BYTES : XCH_BYTES;
   static_assert(LDS_BYTES <= 160 * 1024, "ring exceeds the LDS of a CU");
-  static_assert((NS - 2) * ((BM / 8 + BN / 8 + WGM * WGN - 1) / (WGM * WGN)) <= 24, "in-flight loads exceed wait_vmcnt_dyn");
-  auto kern = gemm_bf16_w48_kernel<WGM, WGN, NS, TC>;
+  static_assert((NS - 2) * ((BM / 8 + BN / 8 + NP - 1) / NP) <= 24, "in-flight loads exceed wait_vmcnt_dyn");
+  static_assert(64 * (WGM * WGN * KS + NP) <= 1024, "workgroup too large");
+  auto kern = gemm_bf16_w48s_kernel<WGM, WGN, NS, KS, NP, TC>;
   static bool attr_done = false;   // per instantiation
   if (!attr_done) {
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess) {
@@ -402,7 +766,31 @@ static bool launch_w48_inst(const GemmDev& d, hipStream_t st) {
   const int tiles_m = (d.M + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
   const int ntile = tiles_m * tiles_n;
   dim3 grid(((ntile + 7) / 8) * 8);
-  hipLaunchKernelGGL(kern, grid, dim3(64 * WGM * WGN), LDS_BYTES, st, d, tiles_m, tiles_n);
+  hipLaunchKernelGGL(kern, grid, dim3(64 * (WGM * WGN * KS + NP)), LDS_BYTES, st, d, tiles_m, tiles_n);
+  return true;
+}
+
+template <int WGM, int WGN, int NS, int KS, typename TC>
+static bool launch_w48_inst(const GemmDev& d, hipStream_t st) {
+  constexpr int BM = 64 * WGM, BN = 48 * WGN;
+  constexpr int RING_BYTES = NS * (BM / 8 + BN / 8) * 1024;
+  constexpr int XCH_BYTES = KS == 2 ? WGM * WGN * 2 * 6 * 64 * 16 : 0;   // accumulator exchange of the wave pairs
+  constexpr int LDS_BYTES = RING_BYTES > XCH_BYTES ? RING_BYTES : XCH_BYTES;
+  static_assert(LDS_BYTES <= 160 * 1024, "ring exceeds the LDS of a CU");
+  static_assert((NS - 2) * ((BM / 8 + BN / 8 + WGM * WGN * KS - 1) / (WGM * WGN * KS)) <= 24, "in-flight loads exceed wait_vmcnt_dyn");
+  auto kern = gemm_bf16_w48_kernel<WGM, WGN, NS, KS, TC>;
+  static bool attr_done = false;   // per instantiation
+  if (!attr_done) {
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess) {
+      (void)hipGetLastError();
+      return false;
+    }
+    attr_done = true;
+  }
+  const int tiles_m = (d.M + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
+  const int ntile = tiles_m * tiles_n;
+  dim3 grid(((ntile + 7) / 8) * 8);
+  hipLaunchKernelGGL(kern, grid, dim3(64 * WGM * WGN * KS), LDS_BYTES, st, d, tiles_m, tiles_n);
   return true;
 }
 
@@ -416,7 +804,8 @@ static bool launch_pipe_layout(const GemmDev& d, int batch, hipStream_t st) {
 
 bool launch_gemm_pipe(const GemmDev& d, int a_kmajor, int b_kmajor, int out_f32, int batch, hipStream_t st) {
   if (d.K % PBK) return false;
-  if (d.M < 128 || d.N < 128 || batch != 1 || out_f32) return false;
+  if (d.M < 128 || d.N < 128 || batch != 1) return false;
+  if (out_f32) return false;
   const long tiles = (long)((d.M + 127) / 128) * ((d.N + 127) / 128);
   if (a_kmajor && b_kmajor) {
     // Tile choice.  Every CU has to work through ceil(tiles / 256) tiles, so the cost of a tiling is that count
@@ -435,11 +824,13 @@ bool launch_gemm_pipe(const GemmDev& d, int a_kmajor, int b_kmajor, int out_f32,
       }
     }
     switch (best) {
-      case 1: return launch_w48_inst<2, 2, 2, bf16_t>(d, st);
-      case 2: return launch_w48_inst<2, 3, 2, bf16_t>(d, st);
-      case 3: return launch_w48_inst<2, 4, 2, bf16_t>(d, st);
-      case 4: return launch_w48_inst<4, 3, 2, bf16_t>(d, st);
-      case 5: return launch_w48_inst<4, 4, 2, bf16_t>(d, st);
+      // one 128x96 tile per CU: 8 consumer + 8 producer waves, three stages (measured 24 us against 33 us for the
+      // 4096x768x3072 product)
+      case 1: return launch_w48s_inst<2, 2, 3, 2, 8, bf16_t>(d, st);
+      case 2: return launch_w48_inst<2, 3, 2, 2, bf16_t>(d, st);
+      case 3: return launch_w48_inst<2, 4, 2, 1, bf16_t>(d, st);
+      case 4: return launch_w48_inst<4, 3, 2, 1, bf16_t>(d, st);
+      case 5: return launch_w48_inst<4, 4, 2, 1, bf16_t>(d, st);
       default: break;
     }
     return launch_pipe_layout<true, true, bf16_t>(d, batch, st);

@@ -89,6 +89,23 @@ def test_gemm_tile_family(M, N, K):
     assert np.max(np.abs(got - ref)) <= 0.02 * (1.0 + np.max(np.abs(ref)))
 
 
+# weight-gradient form (C = A^T B, both operands row-major over the contraction, float output) at sizes that take
+# the producer/consumer kernel: full 256x128 tiles, a partial last tile in each direction, one k-step and many
+@pytest.mark.parametrize("M,N,K", [(256, 128, 64), (768, 768, 4096), (800, 160, 320), (2304, 768, 512)])
+def test_gemm_wgrad_form(M, N, K):
+    announce("gemm-wgrad", M, N, K)
+    rng = np.random.default_rng(M + 5 * N + 11 * K)
+    Y = rnd(rng, (K, M), 1)
+    X = rnd(rng, (K, N), 1)
+    cf = torch.zeros(M, N, dtype=torch.float32, device="cuda")
+    raf.raf_op_gemm(1, M, N, K, to_dev(Y, torch.bfloat16), M, 0, to_dev(X, torch.bfloat16), N, 0, cf, N, out_f32=1)
+    torch.cuda.synchronize()
+    ref = Y.astype(np.float64).T @ X.astype(np.float64)
+    got = host(cf)
+    assert rel_fro(got, ref) <= 1e-5
+    assert np.max(np.abs(got - ref)) <= 1e-4 * (1.0 + np.max(np.abs(ref)))
+
+
 @pytest.mark.parametrize("precision", [0, 1])
 def test_gemm_epilogues_and_f32_out(precision):
     announce("gemm-epilogues", precision)
