@@ -107,7 +107,7 @@ __device__ __forceinline__ void wait_vmcnt_dyn(int n) {
 }
 
 template <int BM, int BN, int WGM, int WGN, bool A_KMAJOR, bool B_KMAJOR, typename TC, int NS>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_kernel(GemmDev g, int tiles_m, int tiles_n) {
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_kernel(GemmDev g, int tiles_m, int tiles_n, int remap) {
   constexpr int NW = WGM * WGN;
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -124,7 +124,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_kernel(GemmDev 
   // columns meet in one L2.
   const int ntile = tiles_m * tiles_n;
   const int per = (ntile + 7) >> 3;
-  const int t = (int)(blockIdx.x & 7) * per + (int)(blockIdx.x >> 3);
+  // batched launches (many problems of a few tiles) keep the plain order: consecutive workgroups already spread
+  // over the XCDs
+  const int t = remap ? (int)(blockIdx.x & 7) * per + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
   if (t >= ntile) return;
   const int m0 = (t / tiles_n) * BM, n0 = (t % tiles_n) * BN;
 
@@ -239,8 +241,9 @@ static bool launch_pipe_inst(const GemmDev& d, int batch, hipStream_t st) {
   }
   const int tiles_m = (d.M + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
   const int ntile = tiles_m * tiles_n;
-  dim3 grid(((ntile + 7) / 8) * 8, batch);
-  hipLaunchKernelGGL(kern, grid, dim3(64 * NW), LDS_BYTES, st, d, tiles_m, tiles_n);
+  const int remap = batch == 1 ? 1 : 0;
+  dim3 grid(remap ? ((ntile + 7) / 8) * 8 : ntile, batch);
+  hipLaunchKernelGGL(kern, grid, dim3(64 * NW), LDS_BYTES, st, d, tiles_m, tiles_n, remap);
   return true;
 }
 
@@ -804,8 +807,14 @@ static bool launch_pipe_layout(const GemmDev& d, int batch, hipStream_t st) {
 
 bool launch_gemm_pipe(const GemmDev& d, int a_kmajor, int b_kmajor, int out_f32, int batch, hipStream_t st) {
   if (d.K % PBK) return false;
-  if (d.M < 128 || d.N < 128 || batch != 1) return false;
   if (out_f32) return false;
+  // per-head attention products (N = 64, contraction <= 128): the whole problem fits the ring, so every load is
+  // issued before the first barrier instead of one memory round trip per k-step
+  if (!b_kmajor && d.N == 64 && d.K <= 2 * PBK && d.M >= 128 && d.M % 128 == 0) {
+    if (a_kmajor) return launch_pipe_inst<128, 64, 2, 2, true, false, bf16_t, 3>(d, batch, st);
+    return launch_pipe_inst<128, 64, 2, 2, false, false, bf16_t, 3>(d, batch, st);
+  }
+  if (d.M < 128 || d.N < 128 || batch != 1) return false;
   const long tiles = (long)((d.M + 127) / 128) * ((d.N + 127) / 128);
   if (a_kmajor && b_kmajor) {
     // Tile choice.  Every CU has to work through ceil(tiles / 256) tiles, so the cost of a tiling is that count
