@@ -268,11 +268,29 @@ raf_status launch_attn_prob_bwd(const raf_layer_desc& d, const void* dc, const v
 raf_status launch_ln_fwd(const raf_layer_desc& d, int site, int64_t rows, const void* a, const void* res,
                          const float* gamma, const float* beta, void* out, void* z_out, float* mu, float* rstd,
                          uint64_t step, hipStream_t st);
+// Deferred second stages.  The column sums that only the optimizer reads (LayerNorm and bias gradients) are
+// produced in two stages: per-block partial rows, then a reduction over the partial rows.  A caller with several of
+// them can collect the second stages (and whole column-sum problems) and run each kind in one launch at the end of
+// its schedule instead of one small launch after every producer.
+struct ReduceJob {
+  const float* partial; int nparts, ncols, nout;
+  float *o0, *o1, *o2;
+  int width_out, perm_nvec;
+};
+struct ColsumJob {
+  int precision; const void* x; int64_t rows; int cols; long ld; float* out; float* partial; int out_cols;
+};
+constexpr int REDUCE_GROUP_MAX = 6, COLSUM_GROUP_MAX = 2;
+raf_status launch_reduce_group(const ReduceJob* jobs, int count, hipStream_t st);
+// first stage of up to COLSUM_GROUP_MAX column sums in one launch; their second stages are appended to reduce_jobs
+raf_status launch_colsum_group(const ColsumJob* jobs, int count, ReduceJob* reduce_jobs, int* nreduce, hipStream_t st);
+
 size_t ln_bwd_partial_floats(int hidden, int64_t rows);
+// defer != nullptr: the reduction of the partial sums is not launched but described in *defer
 raf_status launch_ln_bwd(const raf_layer_desc& d, int site, int64_t rows, const void* dout, const void* dout2,
                          const void* z, const float* mu, const float* rstd, const float* gamma, const void* dres,
                          void* dz, void* da, float* dgamma, float* dbeta, float* dbias, float* partial,
-                         uint64_t step, hipStream_t st, int site_in = 0);
+                         uint64_t step, hipStream_t st, int site_in = 0, ReduceJob* defer = nullptr);
 // out[j] = sum_i x[i*ld + j], x in compute dtype, rows x cols; partial scratch
 size_t colsum_partial_floats(int cols, int64_t rows);
 // only the first out_cols (<= cols, 0 = all) sums are written

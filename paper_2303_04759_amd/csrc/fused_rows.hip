@@ -370,14 +370,23 @@ __global__ __launch_bounds__(LN_BWD_THREADS) void ln_bwd_kernel(const T* __restr
 // slices of a block take parts p = slice, slice+16, ... eight loads at a time
 // and are combined in a fixed order, so the sum is reproducible.
 constexpr int RED_COLS = 16, RED_SLICES = 16, RED_UNROLL = 8;
-__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int nparts, int ncols,
-                                                              int nout, float* o0, float* o1, float* o2,
-                                                              int width_out, int perm_nvec) {
+struct ReduceGroupDev {
+  ReduceJob j[REDUCE_GROUP_MAX];
+  int block_start[REDUCE_GROUP_MAX + 1];
+};
+__global__ __launch_bounds__(256) void reduce_partials_kernel(ReduceGroupDev grp) {
   __shared__ float red[RED_SLICES][RED_COLS];
+  int ji = 0;
+#pragma unroll
+  for (int q = 1; q < REDUCE_GROUP_MAX; ++q)
+    if ((int)blockIdx.x >= grp.block_start[q]) ji = q;
+  const ReduceJob& job = grp.j[ji];                 // wave-uniform selection
+  const float* __restrict__ partial = job.partial;
+  const int nparts = job.nparts, ncols = job.ncols, width_out = job.width_out;
   const int cl = threadIdx.x % RED_COLS;
-  const int c = blockIdx.x * RED_COLS + cl;
+  const int c = ((int)blockIdx.x - grp.block_start[ji]) * RED_COLS + cl;
   const int slice = threadIdx.x / RED_COLS;
-  const long width = (long)nout * ncols;   // stride between partial rows; only c < width_out is produced
+  const long width = (long)job.nout * ncols;   // stride between partial rows; only c < width_out is produced
   float acc[RED_UNROLL];
 #pragma unroll
   for (int u = 0; u < RED_UNROLL; ++u) acc[u] = 0.f;
@@ -400,23 +409,54 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
     for (int sl = 0; sl < RED_SLICES; ++sl) sum += red[sl][cl];
     const int k = c / ncols;
     int cc = c % ncols;
-    if (perm_nvec > 0) cc = (cc % perm_nvec) * 8 + cc / perm_nvec;   // partial rows stored element-major
-    float* o = k == 0 ? o0 : (k == 1 ? o1 : o2);
+    if (job.perm_nvec > 0) cc = (cc % job.perm_nvec) * 8 + cc / job.perm_nvec;   // partial rows stored element-major
+    float* o = k == 0 ? job.o0 : (k == 1 ? job.o1 : job.o2);
     if (o) o[cc] = sum;
   }
 }
 
+raf_status launch_reduce_group(const ReduceJob* jobs, int count, hipStream_t st) {
+  if (!jobs || count <= 0 || count > REDUCE_GROUP_MAX) return RAF_EINVAL;
+  ReduceGroupDev g{};
+  int blocks = 0;
+  for (int i = 0; i < count; ++i) {
+    if (!jobs[i].partial || jobs[i].nparts <= 0 || jobs[i].ncols <= 0 || jobs[i].nout < 1 || jobs[i].nout > 3) return RAF_EINVAL;
+    g.j[i] = jobs[i];
+    g.block_start[i] = blocks;
+    blocks += (jobs[i].width_out + RED_COLS - 1) / RED_COLS;
+  }
+  for (int i = count; i <= REDUCE_GROUP_MAX; ++i) g.block_start[i] = blocks;
+  for (int i = count; i < REDUCE_GROUP_MAX; ++i) g.j[i] = g.j[0];
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks), dim3(256), 0, st, g);
+  return check_launch();
+}
+
 // ------------------------------------------------------------ column sum --
 constexpr int COLSUM_MAX_PARTS = 64;
+struct ColsumGroupDev {
+  const void* x[COLSUM_GROUP_MAX];
+  float* partial[COLSUM_GROUP_MAX];
+  long rows[COLSUM_GROUP_MAX], ld[COLSUM_GROUP_MAX];
+  int cols[COLSUM_GROUP_MAX], parts[COLSUM_GROUP_MAX];
+  int block_start[COLSUM_GROUP_MAX + 1];
+};
 template <typename T>
-__global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ x, long rows, int cols, long ld,
-                                                     float* __restrict__ partial) {
+__global__ __launch_bounds__(256) void colsum_kernel(ColsumGroupDev g) {
   __shared__ float red[4][64 * 8];
-  const int cv = blockIdx.x * 64 + (threadIdx.x & 63);
+  int ji = 0;
+#pragma unroll
+  for (int q = 1; q < COLSUM_GROUP_MAX; ++q)
+    if ((int)blockIdx.x >= g.block_start[q]) ji = q;
+  if ((int)blockIdx.y >= g.parts[ji]) return;
+  const T* __restrict__ x = (const T*)g.x[ji];
+  const long rows = g.rows[ji], ld = g.ld[ji];
+  const int cols = g.cols[ji], nparts = g.parts[ji];
+  const int bx = (int)blockIdx.x - g.block_start[ji];
+  const int cv = bx * 64 + (threadIdx.x & 63);
   const int rl = threadIdx.x >> 6;
   float acc[8] = {};
   if (cv * 8 < cols) {
-    const long stride = (long)gridDim.y * 4;
+    const long stride = (long)nparts * 4;
     long r = (long)blockIdx.y * 4 + rl;
     // eight independent 16-byte loads in flight per lane
     for (; r + 7 * stride < rows; r += 8 * stride) {
@@ -439,8 +479,8 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ x, lo
   for (int e = 0; e < 8; ++e) red[rl][(threadIdx.x & 63) * 8 + e] = acc[e];
   __syncthreads();
   for (int c = threadIdx.x; c < 64 * 8; c += 256) {
-    const int col = blockIdx.x * 512 + c;
-    if (col < cols) partial[(long)blockIdx.y * cols + col] = red[0][c] + red[1][c] + red[2][c] + red[3][c];
+    const int col = bx * 512 + c;
+    if (col < cols) g.partial[ji][(long)blockIdx.y * cols + col] = red[0][c] + red[1][c] + red[2][c] + red[3][c];
   }
 }
 
@@ -542,7 +582,7 @@ size_t ln_bwd_partial_floats(int hidden, int64_t rows) {
 raf_status launch_ln_bwd(const raf_layer_desc& d, int site, int64_t rows, const void* dout, const void* dout2,
                          const void* z, const float* mu, const float* rstd, const float* gamma, const void* dres,
                          void* dz, void* da, float* dgamma, float* dbeta, float* dbias, float* partial,
-                         uint64_t step, hipStream_t st, int site_in) {
+                         uint64_t step, hipStream_t st, int site_in, ReduceJob* defer) {
   if (!dout || !partial || rows <= 0) return RAF_EINVAL;
   if (gamma && (!z || !mu || !rstd || !dgamma || !dbeta)) return RAF_EINVAL;
   if (!dz && !da) return RAF_EINVAL;
@@ -586,9 +626,12 @@ raf_status launch_ln_bwd(const raf_layer_desc& d, int site, int64_t rows, const 
 #undef CALL
   raf_status rc = check_launch();
   if (rc != RAF_OK) return rc;
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3((3 * H + RED_COLS - 1) / RED_COLS), dim3(256), 0, st, partial, nb, H, 3,
-                     gamma ? dgamma : nullptr, gamma ? dbeta : nullptr, da ? dbias : nullptr, 3 * H, H / 8);
-  return check_launch();
+  const ReduceJob job{partial, nb, H, 3, gamma ? dgamma : nullptr, gamma ? dbeta : nullptr, da ? dbias : nullptr, 3 * H, H / 8};
+  if (defer) {
+    *defer = job;
+    return RAF_OK;
+  }
+  return launch_reduce_group(&job, 1, st);
 }
 
 static int colsum_parts(int64_t rows) {
@@ -599,23 +642,38 @@ static int colsum_parts(int64_t rows) {
 }
 size_t colsum_partial_floats(int cols, int64_t rows) { return (size_t)colsum_parts(rows) * (size_t)cols; }
 
+raf_status launch_colsum_group(const ColsumJob* jobs, int count, ReduceJob* reduce_jobs, int* nreduce, hipStream_t st) {
+  if (!jobs || count <= 0 || count > COLSUM_GROUP_MAX || !reduce_jobs || !nreduce) return RAF_EINVAL;
+  ColsumGroupDev g{};
+  int blocks = 0, max_parts = 0;
+  for (int i = 0; i < count; ++i) {
+    const ColsumJob& j = jobs[i];
+    if (!j.x || !j.out || !j.partial || j.rows <= 0 || j.cols <= 0) return RAF_EINVAL;
+    if ((j.cols % 8) || (j.ld % 8) || !aligned16(j.x) || j.precision != jobs[0].precision) return RAF_EINVAL;
+    const int out_cols = (j.out_cols <= 0 || j.out_cols > j.cols) ? j.cols : j.out_cols;
+    g.x[i] = j.x; g.partial[i] = j.partial; g.rows[i] = (long)j.rows; g.ld[i] = j.ld; g.cols[i] = j.cols;
+    g.parts[i] = colsum_parts(j.rows);
+    g.block_start[i] = blocks;
+    blocks += (j.cols + 511) / 512;
+    max_parts = g.parts[i] > max_parts ? g.parts[i] : max_parts;
+    reduce_jobs[(*nreduce)++] = ReduceJob{j.partial, g.parts[i], j.cols, 1, j.out, nullptr, nullptr, out_cols, 0};
+  }
+  for (int i = count; i <= COLSUM_GROUP_MAX; ++i) g.block_start[i] = blocks;
+  for (int i = count; i < COLSUM_GROUP_MAX; ++i) { g.x[i] = g.x[0]; g.partial[i] = g.partial[0]; g.rows[i] = g.rows[0]; g.ld[i] = g.ld[0]; g.cols[i] = g.cols[0]; g.parts[i] = 0; }
+  dim3 grid(blocks, max_parts);
+  if (jobs[0].precision == RAF_F32) hipLaunchKernelGGL((colsum_kernel<float>), grid, dim3(256), 0, st, g);
+  else hipLaunchKernelGGL((colsum_kernel<bf16_t>), grid, dim3(256), 0, st, g);
+  return check_launch();
+}
+
 raf_status launch_colsum(int precision, const void* x, int64_t rows, int cols, long ld, float* out, float* partial,
                          hipStream_t st, int out_cols) {
-  if (out_cols <= 0 || out_cols > cols) out_cols = cols;
-  if (!x || !out || !partial || rows <= 0 || cols <= 0) return RAF_EINVAL;
-  if ((cols % 8) || (ld % 8) || !aligned16(x)) return RAF_EINVAL;
-  const int parts = colsum_parts(rows);
-  dim3 grid((cols + 511) / 512, parts);
-  if (precision == RAF_F32)
-    hipLaunchKernelGGL((colsum_kernel<float>), grid, dim3(256), 0, st, (const float*)x, (long)rows, cols, ld, partial);
-  else
-    hipLaunchKernelGGL((colsum_kernel<bf16_t>), grid, dim3(256), 0, st, (const bf16_t*)x, (long)rows, cols, ld,
-                       partial);
-  raf_status rc = check_launch();
+  const ColsumJob job{precision, x, rows, cols, ld, out, partial, out_cols};
+  ReduceJob rj[1];
+  int nr = 0;
+  raf_status rc = launch_colsum_group(&job, 1, rj, &nr, st);
   if (rc != RAF_OK) return rc;
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3((out_cols + RED_COLS - 1) / RED_COLS), dim3(256), 0, st, partial, parts, cols, 1,
-                     out, nullptr, nullptr, out_cols, 0);
-  return check_launch();
+  return launch_reduce_group(rj, nr, st);
 }
 
 }  // namespace raf

@@ -45,7 +45,7 @@ struct Plan {
   // scratch, forward
   size_t s, a;
   // scratch, backward
-  size_t dz2, da, da1, du, dffn, dz1, dc, dprob_d, ds, dqkv, dattn, partial, wt_qkv, wt_o, wt_1, wt_2;
+  size_t dz2, da, da1, du, dffn, dz1, dc, dprob_d, ds, dqkv, dattn, partial_ln[3], partial_cs[2], wt_qkv, wt_o, wt_1, wt_2;
   size_t scratch_bytes;
 };
 
@@ -93,11 +93,10 @@ static Plan make_plan(const raf_layer_desc& d) {
   p.ds = bump(b, PSb);
   p.dqkv = bump(b, 3 * TH);
   p.dattn = bump(b, TH);
-  size_t pf = ln_bwd_partial_floats((int)p.H, p.T);
-  const size_t c1 = colsum_partial_floats((int)(3 * p.H), p.T), c2 = colsum_partial_floats((int)p.F, p.T);
-  if (c1 > pf) pf = c1;
-  if (c2 > pf) pf = c2;
-  p.partial = bump(b, pf * 4);
+  // one partial-sum buffer per producer: their second stages run together at the end of the backward pass
+  for (int i = 0; i < 3; ++i) p.partial_ln[i] = bump(b, ln_bwd_partial_floats((int)p.H, p.T) * 4);
+  p.partial_cs[0] = bump(b, colsum_partial_floats((int)p.F, p.T) * 4);
+  p.partial_cs[1] = bump(b, colsum_partial_floats((int)(3 * p.H), p.T) * 4);
   if (d.precision == RAF_BF16_AMP) {   // transposed bf16 weight copies for the input-gradient products
     p.wt_qkv = bump(b, (size_t)3 * p.H * p.H * 2);
     p.wt_o = bump(b, (size_t)p.H * p.H * 2);
@@ -298,7 +297,12 @@ extern "C" raf_status raf_layer_bwd(const raf_layer_desc* desc, const raf_layer_
   void* ds = at(scratch, p.ds);
   void* dqkv = at(scratch, p.dqkv);
   void* dattn = at(scratch, p.dattn);
-  float* partial = (float*)at(scratch, p.partial);
+  float* partial_ln[3] = {(float*)at(scratch, p.partial_ln[0]), (float*)at(scratch, p.partial_ln[1]),
+                          (float*)at(scratch, p.partial_ln[2])};
+  // second stages of the LayerNorm / bias gradient sums and the two bias column sums, launched together at the end
+  ReduceJob rj[REDUCE_GROUP_MAX];
+  int nr = 0;
+  ColsumJob cj[COLSUM_GROUP_MAX];
 
   // bf16: the input-gradient products below use K-major transposed copies of the four weights
   const bool wt = prec == RAF_BF16_AMP;
@@ -314,25 +318,28 @@ extern "C" raf_status raf_layer_bwd(const raf_layer_desc* desc, const raf_layer_
   // B9: adjoint of the output block
   if (d.pre_ln)   // y = z1 + drop3(a2): da2 = dy * keep3/(1-p)
     RAF_TRY(launch_ln_bwd(d, 3, T, dy, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, da, nullptr,
-                          nullptr, (float*)grads->b_2, partial, step, st));
+                          nullptr, (float*)grads->b_2, partial_ln[0], step, st, 0, &rj[nr++]));
   else            // y = LN2(z2), z2 = ffn_in + drop3(a2)
     RAF_TRY(launch_ln_bwd(d, 3, T, dy, nullptr, z2, mu2, rstd2, (const float*)w->ln2_g, nullptr, dz2, da,
-                          (float*)grads->ln2_g, (float*)grads->ln2_b, (float*)grads->b_2, partial, step, st));
+                          (float*)grads->ln2_g, (float*)grads->ln2_b, (float*)grads->b_2, partial_ln[0], step, st, 0,
+                          &rj[nr++]));
   // The four weight gradients (dW = dY^T X) are deferred to one grouped launch
   // at the end: each alone has too few output tiles to fill 256 CUs.
   // B8: a2 = g W2^T + b2  ->  du = (da2 W2) * gelu'(u)      [dW2 = da2^T g deferred]
   RAF_TRY(gemm(prec, st, T, F, H, da, H, 1, wt ? wt_2 : w->w_2, wt ? H : F, wt ? 1 : 0, du, F, 0, EPI_MUL_GELU_GRAD,
                nullptr, u, F, d.gelu_tanh));
   // B7: u = ffn_in W1^T + b1  ->  db1 ; dffn = du W1          [dW1 = du^T ffn_in deferred]
-  RAF_TRY(launch_colsum(prec, du, T, F, F, (float*)grads->b_1, partial, st));
+  cj[0] = ColsumJob{prec, du, T, F, F, (float*)grads->b_1, (float*)at(scratch, p.partial_cs[0]), 0};
   RAF_TRY(gemm(prec, st, T, H, F, du, F, 1, wt ? wt_1 : w->w_1, wt ? F : H, wt ? 1 : 0, dffn, H));
   // B6: the LayerNorm between the two halves, the residual, dropout site 2
   if (d.pre_ln)   // ffn_in = LN2(z1); dz1 = dy + LN2'(dffn); da1 = dz1 * keep2/(1-p)
     RAF_TRY(launch_ln_bwd(d, 2, T, dffn, nullptr, z1, mu2, rstd2, (const float*)w->ln2_g, dy, dz1, da1,
-                          (float*)grads->ln2_g, (float*)grads->ln2_b, (float*)grads->b_o, partial, step, st));
+                          (float*)grads->ln2_g, (float*)grads->ln2_b, (float*)grads->b_o, partial_ln[1], step, st, 0,
+                          &rj[nr++]));
   else            // ffn_in = LN1(z1) feeds the ffn and the residual: g_in = dz2 + dffn
     RAF_TRY(launch_ln_bwd(d, 2, T, dz2, dffn, z1, mu1, rstd1, (const float*)w->ln1_g, nullptr, dz1, da1,
-                          (float*)grads->ln1_g, (float*)grads->ln1_b, (float*)grads->b_o, partial, step, st));
+                          (float*)grads->ln1_g, (float*)grads->ln1_b, (float*)grads->b_o, partial_ln[1], step, st, 0,
+                          &rj[nr++]));
   // B5: a1 = c Wo^T + bo  ->  dc = da1 Wo                   [dWo = da1^T c deferred]
   RAF_TRY(gemm(prec, st, T, H, H, da1, H, 1, wt ? wt_o : w->w_o, H, wt ? 1 : 0, dc, H));
   // B4: c = prob_d V  ->  dV = prob_d^T dc ; dprob_d = dc V^T
@@ -353,12 +360,12 @@ extern "C" raf_status raf_layer_bwd(const raf_layer_desc* desc, const raf_layer_
   RAF_TRY(gemm_heads(p, prec, st, S, 64, S, HeadView{ds, S, 0, true}, HeadView{qkv, 3 * H, 0, false},
                      at(dqkv, (size_t)H * e), 3 * H, false, 1.0f));
   // B1: qkv = attn_in Wqkv^T + bqkv
-  RAF_TRY(launch_colsum(prec, dqkv, T, 3 * H, 3 * H, (float*)grads->b_qkv, partial, st));
+  cj[1] = ColsumJob{prec, dqkv, T, 3 * H, 3 * H, (float*)grads->b_qkv, (float*)at(scratch, p.partial_cs[1]), 0};
   if (d.pre_ln) {
     RAF_TRY(gemm(prec, st, T, H, 3 * H, dqkv, 3 * H, 1, wt ? wt_qkv : w->w_qkv, wt ? 3 * H : H, wt ? 1 : 0, dattn, H));
     // attn_in = LN1(x); dx = dz1 + LN1'(dattn)
     RAF_TRY(launch_ln_bwd(d, 0, T, dattn, nullptr, x, mu1, rstd1, (const float*)w->ln1_g, dz1, dx, nullptr,
-                          (float*)grads->ln1_g, (float*)grads->ln1_b, nullptr, partial, step, st));
+                          (float*)grads->ln1_g, (float*)grads->ln1_b, nullptr, partial_ln[2], step, st, 0, &rj[nr++]));
   } else {
     // dx = dz1 + dqkv Wqkv (residual add in the epilogue)
     RAF_TRY(gemm(prec, st, T, H, 3 * H, dqkv, 3 * H, 1, wt ? wt_qkv : w->w_qkv, wt ? 3 * H : H, wt ? 1 : 0, dx, H, 0,
@@ -370,7 +377,10 @@ extern "C" raf_status raf_layer_bwd(const raf_layer_desc* desc, const raf_layer_
   wg[1] = wgrad_args(F, H, T, du, F, ffn_in, H, grads->w_1, H);
   wg[2] = wgrad_args(3 * H, H, T, dqkv, 3 * H, d.pre_ln ? n1 : x, H, grads->w_qkv, H);
   wg[3] = wgrad_args(H, H, T, da1, H, c, H, grads->w_o, H);
-  return launch_gemm_group_wgrad(prec, wg, 4, st);
+  RAF_TRY(launch_gemm_group_wgrad(prec, wg, 4, st));
+  // db1 = column sums of du, dbqkv = column sums of dqkv (both still intact), then every deferred reduction
+  RAF_TRY(launch_colsum_group(cj, 2, rj, &nr, st));
+  return launch_reduce_group(rj, nr, st);
 }
 
 // ------------------------------------------------------ single operators --
