@@ -22,12 +22,18 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel on the bert_base workload, from the two rocprofv3 --pmc
 # runs summarised in profiles/bench_bert_base_hbm_traffic.txt (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00,
-# factors from a plain 256 MiB copy): 53.0 MB read + 24.4 MB written.
-DOMINANT_KERNEL_TRAFFIC_BYTES = {"bert_base": 77.4e6}
+# factors from a plain 256 MiB copy): 42.7 MB read + 6.3 MB written.
+DOMINANT_KERNEL_TRAFFIC_BYTES = {"bert_base": 49.0e6}
+DOMINANT_KERNEL_NAME = {"bert_base": "gemm_bf16_w48s_kernel<128x96 tiles, 8 consumer + 8 producer waves, 3 stages, K-major "
+                                     "operands> (the five products with N = hidden: out/ffn2 forward, ffn1/out/qkv "
+                                     "input gradients)"}
 
 
 def gemm_launches(cfg):
-    """The dense contractions of one step as (name, M, N, K, a_kmajor, b_kmajor, out_f32, epilogue, batch)."""
+    """The dense contractions of one step as (name, M, N, K, a_kmajor, b_kmajor, out_f32, epilogue, batch).
+
+    In bf16 AMP the input-gradient products read K-major transposed weight copies, so they have the same
+    layout as the forward products."""
     B, S, H, F, nh = cfg["batch"], cfg["seq"], cfg["hidden"], cfg["ffn"], cfg["heads"]
     T = B * S
     z = B * nh
@@ -35,12 +41,12 @@ def gemm_launches(cfg):
         ("qkv_fwd", T, 3 * H, H, 1, 1, 0, 1, 1), ("scores_fwd", S, S, 64, 1, 1, 0, 0, z),
         ("context_fwd", S, 64, S, 1, 0, 0, 0, z), ("out_fwd", T, H, H, 1, 1, 0, 1, 1),
         ("ffn1_fwd", T, F, H, 1, 1, 0, 2, 1), ("ffn2_fwd", T, H, F, 1, 1, 0, 1, 1),
-        ("ffn2_wgrad", H, F, T, 0, 0, 1, 0, 1), ("ffn2_dgrad", T, F, H, 1, 0, 0, 3, 1),
-        ("ffn1_wgrad", F, H, T, 0, 0, 1, 0, 1), ("ffn1_dgrad", T, H, F, 1, 0, 0, 0, 1),
-        ("out_wgrad", H, H, T, 0, 0, 1, 0, 1), ("out_dgrad", T, H, H, 1, 0, 0, 0, 1),
+        ("ffn2_wgrad", H, F, T, 0, 0, 1, 0, 1), ("ffn2_dgrad", T, F, H, 1, 1, 0, 3, 1),
+        ("ffn1_wgrad", F, H, T, 0, 0, 1, 0, 1), ("ffn1_dgrad", T, H, F, 1, 1, 0, 0, 1),
+        ("out_wgrad", H, H, T, 0, 0, 1, 0, 1), ("out_dgrad", T, H, H, 1, 1, 0, 0, 1),
         ("dprob", S, S, 64, 1, 1, 0, 0, z), ("dv", S, 64, S, 0, 0, 0, 0, z),
         ("dq", S, 64, S, 1, 0, 0, 0, z), ("dk", S, 64, S, 0, 0, 0, 0, z),
-        ("qkv_wgrad", 3 * H, H, T, 0, 0, 1, 0, 1), ("qkv_dgrad", T, H, 3 * H, 1, 0, 0, 4, 1),
+        ("qkv_wgrad", 3 * H, H, T, 0, 0, 1, 0, 1), ("qkv_dgrad", T, H, 3 * H, 1, 1, 0, 4, 1),
     ]
 
 
@@ -153,8 +159,9 @@ def main():
         wall = time.perf_counter() - t0
         ms_per_step = e0.elapsed_time(e1) / K
 
-        # ---- roofline of the dominant kernel: the K-major x K-major bf16 MFMA GEMM instantiation
-        # (the four forward weight GEMMs), timed with events on the launch stream
+        # ---- roofline of the dominant kernel, timed with events on the launch stream: the K-major bf16 MFMA GEMM
+        # instantiation that takes the most time per step, i.e. the one behind the five products with N = hidden
+        # (out / ffn2 forward, ffn1 / out / qkv input gradients; 128x96 tiles on the bert_base workload)
         dt = lay.cdtype
         T, H, F = lay.T, cfg["hidden"], cfg["ffn"]
         big = max(3 * H, F)
@@ -163,13 +170,13 @@ def main():
         c_buf = torch.empty(T, big, dtype=dt, device="cuda")
         u_buf = torch.empty(T, big, dtype=dt, device="cuda")
         bias = torch.zeros(big, device="cuda")
-        dom = [g for g in gemm_launches(cfg) if g[4] == 1 and g[5] == 1 and g[8] == 1]
+        dom = [g for g in gemm_launches(cfg) if g[4] == 1 and g[5] == 1 and g[8] == 1 and g[2] == H]
         reps = max(10, min(K, 50))
 
         def run_dom():
             for (_, M, N, Kd, ak, bk, of32, epi, _) in dom:
                 raf.raf_op_gemm(cfg["precision"], M, N, Kd, a_buf, Kd, 1, w_buf, Kd, 1, c_buf, N, epilogue=epi,
-                                bias=bias, aux=u_buf if epi == 2 else None, stream=stream)
+                                bias=bias, aux=u_buf if epi >= 2 else None, stream=stream)
         for _ in range(3):
             run_dom()
         stream.synchronize()
@@ -204,7 +211,7 @@ def main():
         "tokens_per_s_valid": valid_tokens / (ms_per_step * 1e-3),
         "step_gemm_tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
         "wall_ms_per_step": wall * 1e3 / K,
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_pipe_kernel<128,128,2x4 waves,K-major A,K-major B,2 stages> (forward weight GEMMs)",
+        "roofline": {"bound": "mfma", "kernel": DOMINANT_KERNEL_NAME.get(args.workload, "K-major bf16 MFMA GEMM, products with N = hidden"),
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "avg_launch_us": dom_ms * 1e3,
                      "flops_per_launch": dom_flops,
