@@ -227,7 +227,9 @@ raf_status raf_mlm_head_fwd_bwd(const raf_mlm_desc *desc, const raf_mlm_tensors 
  * a_kmajor=1: A element (i,k) at a[i*lda+k]; 0: at a[k*lda+i].
  * b_kmajor=1: B element (k,j) at b[j*ldb+k]; 0: at b[k*ldb+j].
  * epilogue: 0 none, 1 +bias[j], 2 +bias then GeLU (pre-activation stored to
- * aux, same shape/ld as C), 3 multiply by gelu'(aux[i,j]), 4 +residual aux[i,j].
+ * aux, same shape/ld as C), 3 multiply by gelu'(aux[i,j]), 4 +residual aux[i,j],
+ * 5 +bias then GeLU with gelu'(pre-activation) stored to aux, 6 multiply by aux[i,j]
+ * (5 and 6 are the forward / backward pair the bf16 layer uses).
  * out_f32=1 stores C as float regardless of precision. M,N,K multiples of 32. */
 raf_status raf_op_gemm(int32_t precision, int32_t M, int32_t N, int32_t K, const void *a, int32_t lda,
                        int32_t a_kmajor, const void *b, int32_t ldb, int32_t b_kmajor, void *c, int32_t ldc,

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libraf_mi355.so")
 RAF_F32, RAF_BF16_AMP = 0, 1
 RAF_OK, RAF_EINVAL, RAF_ENOTSUP, RAF_EWORKSPACE, RAF_EHIP = 0, -1, -2, -3, -4
 RAF_LOSS_PARTIALS = 1024
-EPI_NONE, EPI_BIAS, EPI_BIAS_GELU, EPI_MUL_GELU_GRAD, EPI_ADD_RES = range(5)
+EPI_NONE, EPI_BIAS, EPI_BIAS_GELU, EPI_MUL_GELU_GRAD, EPI_ADD_RES, EPI_BIAS_GELU_DERIV, EPI_MUL_AUX = range(7)
 
 PARAM_NAMES = ("w_qkv", "b_qkv", "w_o", "b_o", "ln1_g", "ln1_b",
                "w_1", "b_1", "w_2", "b_2", "ln2_g", "ln2_b")

@@ -188,6 +188,20 @@ __device__ __forceinline__ float gelu_grad_f(float u, int tanh_form) {
   return Phi + u * phi;
 }
 
+// GeLU and its derivative at once (they share the erf / tanh evaluation)
+__device__ __forceinline__ void gelu_and_grad_f(float u, int tanh_form, float& y, float& dy) {
+  if (tanh_form) {
+    const float k = 0.7978845608028654f;
+    const float t = tanhf(k * (u + 0.044715f * u * u * u));
+    y = 0.5f * u * (1.0f + t);
+    dy = 0.5f * (1.0f + t) + 0.5f * u * (1.0f - t * t) * k * (1.0f + 0.134145f * u * u);
+  } else {
+    const float Phi = 0.5f * (1.0f + erf_as(u * 0.7071067811865476f));
+    y = u * Phi;
+    dy = Phi + u * (0.3989422804014327f * __expf(-0.5f * u * u));
+  }
+}
+
 // ---------------------------------------------------------- row geometry --
 struct RowGeom {
   int lpr, nv;
@@ -221,7 +235,10 @@ inline RowGeom row_geom(int len) {
   } while (0)
 
 // --------------------------------------------------------- internal ops ---
-enum Epilogue { EPI_NONE = 0, EPI_BIAS = 1, EPI_BIAS_GELU = 2, EPI_MUL_GELU_GRAD = 3, EPI_ADD_RES = 4 };
+// EPI_BIAS_GELU_DERIV stores gelu'(pre-activation) in aux instead of the pre-activation, so that the matching
+// backward epilogue EPI_MUL_AUX is one multiply (the derivative shares the erf of the forward evaluation).
+enum Epilogue { EPI_NONE = 0, EPI_BIAS = 1, EPI_BIAS_GELU = 2, EPI_MUL_GELU_GRAD = 3, EPI_ADD_RES = 4,
+                EPI_BIAS_GELU_DERIV = 5, EPI_MUL_AUX = 6 };
 
 // One (optionally batched) GEMM problem.  Batch index z = zb*nz_inner + zi
 // moves each pointer by zb*stride_*[0] + zi*stride_*[1] elements.

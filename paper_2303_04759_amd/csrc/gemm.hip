@@ -162,22 +162,7 @@ __device__ __forceinline__ void staged_tile(const GemmDev& g, int m0, int n0, in
 
   // accumulator layout of the (transposed) 32x32 block: register r of lane l
   // holds output row (l & 31), column 8*(r/4) + 4*(l/32) + r%4.
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int row = m0 + wm + i * 32 + (lane & 31);
-    if (row < g.M) {
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int col = n0 + wn + j * 32 + 8 * q + 4 * (lane >> 5);
-          if (col < g.N) {
-            float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-            epilogue_store4<TC>(g, C, AUX, row, col, v);
-          }
-        }
-    }
-  }
+  epilogue_tile32<TC, TM, TN>(g, C, AUX, acc, m0 + wm, n0 + wn);
 }
 
 // Consecutive workgroup ids are dealt round-robin to the 8 XCDs (each with its
@@ -310,9 +295,9 @@ static raf_status check_gemm_args(const GemmArgs& g) {
   if ((g.M % 32) || (g.N % 32) || (g.K % 32)) return RAF_ENOTSUP;
   if (!g.a || !g.b || !g.c) return RAF_EINVAL;
   if (!aligned16(g.a) || !aligned16(g.b) || !aligned16(g.c)) return RAF_EINVAL;
-  if ((g.epilogue == EPI_BIAS || g.epilogue == EPI_BIAS_GELU) && !g.bias) return RAF_EINVAL;
+  if ((g.epilogue == EPI_BIAS || g.epilogue == EPI_BIAS_GELU || g.epilogue == EPI_BIAS_GELU_DERIV) && !g.bias) return RAF_EINVAL;
   if (g.epilogue >= EPI_BIAS_GELU && !g.aux) return RAF_EINVAL;
-  if (g.epilogue < 0 || g.epilogue > EPI_ADD_RES) return RAF_EINVAL;
+  if (g.epilogue < 0 || g.epilogue > EPI_MUL_AUX) return RAF_EINVAL;
   if ((g.lda % 8) || (g.ldb % 8) || (g.ldc % 8) || (g.aux && (g.ldaux % 8))) return RAF_EINVAL;
   if (g.batch > 65535) return RAF_ENOTSUP;
   return RAF_OK;

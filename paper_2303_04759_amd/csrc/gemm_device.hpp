@@ -40,6 +40,17 @@ __device__ __forceinline__ float epilogue_value(const GemmDev& g, TAUX* __restri
     case EPI_ADD_RES:
       v += (float)aux[(long)i * g.ldaux + j];
       break;
+    case EPI_BIAS_GELU_DERIV: {
+      v += g.bias[j];
+      float y, dy;
+      gelu_and_grad_f(v, g.gelu_tanh, y, dy);
+      aux[(long)i * g.ldaux + j] = (TAUX)dy;
+      v = y;
+      break;
+    }
+    case EPI_MUL_AUX:
+      v *= (float)aux[(long)i * g.ldaux + j];
+      break;
     default:
       break;
   }
@@ -69,32 +80,115 @@ __device__ __forceinline__ void store4(float* p, const float (&v)[4]) {
   *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
 }
 
-template <typename TC>
+// The epilogue kind is a template parameter here and the kernels switch on it once, outside their unrolled store
+// loops: with the run-time switch inside, every one of the 12-64 store groups of a wave carried all cases and the
+// epilogue of the plain-bias GEMMs slowed down by several microseconds when a case was added.
+template <typename TC, int EPI>
 __device__ __forceinline__ void epilogue_store4(const GemmDev& g, TC* __restrict__ c, bf16_t* __restrict__ aux, int i,
                                                 int j, float (&v)[4]) {
 #pragma unroll
   for (int e = 0; e < 4; ++e) v[e] *= g.alpha;
-  if (g.epilogue == EPI_BIAS || g.epilogue == EPI_BIAS_GELU) {
+  if constexpr (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU || EPI == EPI_BIAS_GELU_DERIV) {
     const float4 b = *reinterpret_cast<const float4*>(g.bias + j);
     v[0] += b.x; v[1] += b.y; v[2] += b.z; v[3] += b.w;
   }
-  if (g.epilogue == EPI_BIAS_GELU) {
+  if constexpr (EPI == EPI_BIAS_GELU) {
     store4(aux + (long)i * g.ldaux + j, v);
     // GeLU is evaluated on the value the backward pass will read back
 #pragma unroll
     for (int e = 0; e < 4; ++e) v[e] = gelu_f((float)(bf16_t)v[e], g.gelu_tanh);
-  } else if (g.epilogue == EPI_MUL_GELU_GRAD) {
+  } else if constexpr (EPI == EPI_MUL_GELU_GRAD) {
     float u[4];
     load4(aux + (long)i * g.ldaux + j, u);
 #pragma unroll
     for (int e = 0; e < 4; ++e) v[e] *= gelu_grad_f(u[e], g.gelu_tanh);
-  } else if (g.epilogue == EPI_ADD_RES) {
+  } else if constexpr (EPI == EPI_ADD_RES) {
     float r[4];
     load4(aux + (long)i * g.ldaux + j, r);
 #pragma unroll
     for (int e = 0; e < 4; ++e) v[e] += r[e];
+  } else if constexpr (EPI == EPI_BIAS_GELU_DERIV) {
+    float dy[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) gelu_and_grad_f(v[e], g.gelu_tanh, v[e], dy[e]);
+    store4(aux + (long)i * g.ldaux + j, dy);
+  } else if constexpr (EPI == EPI_MUL_AUX) {
+    float r[4];
+    load4(aux + (long)i * g.ldaux + j, r);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] *= r[e];
   }
   store4(c + (long)i * g.ldc + j, v);
+}
+
+template <int V>
+struct EpiTag {
+  static constexpr int value = V;
+};
+template <typename F>
+__device__ __forceinline__ void epilogue_dispatch(int epi, F&& f) {
+  switch (epi) {
+    case EPI_BIAS: f(EpiTag<EPI_BIAS>{}); break;
+    case EPI_BIAS_GELU: f(EpiTag<EPI_BIAS_GELU>{}); break;
+    case EPI_MUL_GELU_GRAD: f(EpiTag<EPI_MUL_GELU_GRAD>{}); break;
+    case EPI_ADD_RES: f(EpiTag<EPI_ADD_RES>{}); break;
+    case EPI_BIAS_GELU_DERIV: f(EpiTag<EPI_BIAS_GELU_DERIV>{}); break;
+    case EPI_MUL_AUX: f(EpiTag<EPI_MUL_AUX>{}); break;
+    default: f(EpiTag<EPI_NONE>{}); break;
+  }
+}
+
+// A wave's TM x TN blocks of the (transposed) 32x32 MFMA result: register r of lane l holds output row (l & 31),
+// column 8*(r/4) + 4*(l/32) + r%4 of its block.  row0 / col0: the wave tile's origin.
+template <typename TC, int TM, int TN>
+__device__ __forceinline__ void epilogue_tile32(const GemmDev& g, TC* __restrict__ C, bf16_t* __restrict__ AUX,
+                                                f32x16_t (&acc)[TM][TN], int row0, int col0) {
+  const int lane = threadIdx.x & 63;
+  epilogue_dispatch(g.epilogue, [&](auto tag) {
+    constexpr int EPI = decltype(tag)::value;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int row = row0 + i * 32 + (lane & 31);
+      if (row < g.M) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int col = col0 + j * 32 + 8 * q + 4 * (lane >> 5);
+            if (col < g.N) {
+              float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+              epilogue_store4<TC, EPI>(g, C, AUX, row, col, v);
+            }
+          }
+      }
+    }
+  });
+}
+
+// A wave's 4 x 3 blocks of the (transposed) 16x16 MFMA result: a lane holds output row (l & 15) and the 4
+// consecutive columns 4*(l>>4) + r of each block; only row blocks [i_begin, i_end) are written.
+template <typename TC>
+__device__ __forceinline__ void epilogue_tile16(const GemmDev& g, TC* __restrict__ C, bf16_t* __restrict__ AUX,
+                                                f32x4_t (&acc)[4][3], int row0, int col0, int i_begin, int i_end) {
+  const int lane = threadIdx.x & 63;
+  epilogue_dispatch(g.epilogue, [&](auto tag) {
+    constexpr int EPI = decltype(tag)::value;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (i < i_begin || i >= i_end) continue;
+      const int row = row0 + i * 16 + (lane & 15);
+      if (row < g.M) {
+#pragma unroll
+        for (int j = 0; j < 3; ++j) {
+          const int col = col0 + j * 16 + 4 * (lane >> 4);
+          if (col < g.N) {
+            float v[4] = {acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]};
+            epilogue_store4<TC, EPI>(g, C, AUX, row, col, v);
+          }
+        }
+      }
+    }
+  });
 }
 
 

@@ -208,22 +208,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_kernel(GemmDev 
   }
 
   // register r of lane l holds output row (l & 31), column 8*(r/4) + 4*(l/32) + r%4 of its 32x32 block
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int row = m0 + wm + i * 32 + (lane & 31);
-    if (row < g.M) {
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int col = n0 + wn + j * 32 + 8 * q + 4 * (lane >> 5);
-          if (col < g.N) {
-            float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-            epilogue_store4<TC>(g, C, AUX, row, col, v);
-          }
-        }
-    }
-  }
+  epilogue_tile32<TC, TM, TN>(g, C, AUX, acc, m0 + wm, n0 + wn);
 }
 
 template <int BM, int BN, int WGM, int WGN, bool AK, bool BKM, typename TC, int NS>
@@ -275,13 +260,16 @@ __global__ __launch_bounds__(64 * (WGM * WGN + NP)) void gemm_bf16_spec_kernel(G
   const int per = (ntile + 7) >> 3;
   const int t = (int)(blockIdx.x & 7) * per + (int)(blockIdx.x >> 3);   // XCD x takes tiles [x*per, (x+1)*per)
   if (t >= ntile) return;
-  int pi = 0;
+  // the problem is selected with static indices (a run-time index would copy the descriptors to scratch memory)
+  GemmDev g = grp.p[0];
+  int lt = t, tn = grp.tiles_n[0];
 #pragma unroll
   for (int q = 1; q < GEMM_GROUP_MAX; ++q)
-    if (q < grp.count && t >= grp.tile_start[q]) pi = q;
-  const GemmDev& g = grp.p[pi];                        // selected with wave-uniform scalar loads
-  const int lt = t - grp.tile_start[pi];
-  const int tn = grp.tiles_n[pi];
+    if (q < grp.count && t >= grp.tile_start[q]) {
+      g = grp.p[q];
+      lt = t - grp.tile_start[q];
+      tn = grp.tiles_n[q];
+    }
   const int m0 = (lt / tn) * BM, n0 = (lt % tn) * BN;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int nk = g.K / PBK;
@@ -362,22 +350,7 @@ __global__ __launch_bounds__(64 * (WGM * WGN + NP)) void gemm_bf16_spec_kernel(G
   TC* __restrict__ C = (TC*)g.c;
   bf16_t* __restrict__ AUX = (bf16_t*)g.aux;
   // register r of lane l holds output row (l & 31), column 8*(r/4) + 4*(l/32) + r%4 of its 32x32 block
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int row = m0 + wm + i * 32 + (lane & 31);
-    if (row < g.M) {
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int col = n0 + wn + j * 32 + 8 * q + 4 * (lane >> 5);
-          if (col < g.N) {
-            float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-            epilogue_store4<TC>(g, C, AUX, row, col, v);
-          }
-        }
-    }
-  }
+  epilogue_tile32<TC, TM, TN>(g, C, AUX, acc, m0 + wm, n0 + wn);
 }
 
 bool launch_gemm_group_spec(const GemmDev* ds, int count, hipStream_t st) {
@@ -565,21 +538,7 @@ __global__ __launch_bounds__(64 * WGM * WGN * KS) void gemm_bf16_w48_kernel(Gemm
     i_end = i_begin + 2;
   }
 
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    if (i < i_begin || i >= i_end) continue;
-    const int row = m0 + wm + i * 16 + (lane & 15);
-    if (row < g.M) {
-#pragma unroll
-      for (int j = 0; j < 3; ++j) {
-        const int col = n0 + wn + j * 16 + 4 * (lane >> 4);
-        if (col < g.N) {
-          float v[4] = {acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]};
-          epilogue_store4<TC>(g, C, AUX, row, col, v);
-        }
-      }
-    }
-  }
+  epilogue_tile16<TC>(g, C, AUX, acc, m0 + wm, n0 + wn, i_begin, i_end);
 }
 
 // Same tiles with the waves specialised: NP producer waves only issue the direct-to-LDS loads (a wave is held for
@@ -731,21 +690,7 @@ __global__ __launch_bounds__(64 * (WGM * WGN * KS + NP)) void gemm_bf16_w48s_ker
     i_end = i_begin + 2;
   }
 
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    if (i < i_begin || i >= i_end) continue;
-    const int row = m0 + wm + i * 16 + (lane & 15);
-    if (row < g.M) {
-#pragma unroll
-      for (int j = 0; j < 3; ++j) {
-        const int col = n0 + wn + j * 16 + 4 * (lane >> 4);
-        if (col < g.N) {
-          float v[4] = {acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]};
-          epilogue_store4<TC>(g, C, AUX, row, col, v);
-        }
-      }
-    }
-  }
+  epilogue_tile16<TC>(g, C, AUX, acc, m0 + wm, n0 + wn, i_begin, i_end);
 }
 
 template <int WGM, int WGN, int NS, int KS, int NP, typename TC>

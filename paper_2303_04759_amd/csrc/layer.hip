@@ -242,9 +242,10 @@ extern "C" raf_status raf_layer_fwd(const raf_layer_desc* desc, const raf_layer_
   else
     RAF_TRY(launch_ln_fwd(d, 2, T, a, x, (const float*)w->ln1_g, (const float*)w->ln1_b, ffn_in, z1, mu1, rstd1, step,
                           st));
-  // F7: u = ffn_in . W1^T + b1 (saved); g = gelu(u)
-  RAF_TRY(gemm(prec, st, T, F, H, ffn_in, H, 1, w->w_1, H, 1, g, F, 0, EPI_BIAS_GELU, (const float*)w->b_1, u, F,
-               d.gelu_tanh));
+  // F7: u = ffn_in . W1^T + b1; g = gelu(u).  Saved for the backward pass: u (fp32 mode) or, in bf16 AMP,
+  // gelu'(u), which shares the erf of the forward evaluation and makes the backward epilogue one multiply
+  RAF_TRY(gemm(prec, st, T, F, H, ffn_in, H, 1, w->w_1, H, 1, g, F, 0,
+               prec == RAF_BF16_AMP ? EPI_BIAS_GELU_DERIV : EPI_BIAS_GELU, (const float*)w->b_1, u, F, d.gelu_tanh));
   // F8: a2 = g . W2^T + b2
   RAF_TRY(gemm(prec, st, T, H, F, g, F, 1, w->w_2, F, 1, a, H, 0, EPI_BIAS, (const float*)w->b_2));
   // F9: post-LN: z2 = ffn_in + drop3(a2), y = LN2(z2); pre-LN: y = z1 + drop3(a2)
@@ -326,8 +327,8 @@ extern "C" raf_status raf_layer_bwd(const raf_layer_desc* desc, const raf_layer_
   // The four weight gradients (dW = dY^T X) are deferred to one grouped launch
   // at the end: each alone has too few output tiles to fill 256 CUs.
   // B8: a2 = g W2^T + b2  ->  du = (da2 W2) * gelu'(u)      [dW2 = da2^T g deferred]
-  RAF_TRY(gemm(prec, st, T, F, H, da, H, 1, wt ? wt_2 : w->w_2, wt ? H : F, wt ? 1 : 0, du, F, 0, EPI_MUL_GELU_GRAD,
-               nullptr, u, F, d.gelu_tanh));
+  RAF_TRY(gemm(prec, st, T, F, H, da, H, 1, wt ? wt_2 : w->w_2, wt ? H : F, wt ? 1 : 0, du, F, 0,
+               prec == RAF_BF16_AMP ? EPI_MUL_AUX : EPI_MUL_GELU_GRAD, nullptr, u, F, d.gelu_tanh));
   // B7: u = ffn_in W1^T + b1  ->  db1 ; dffn = du W1          [dW1 = du^T ffn_in deferred]
   cj[0] = ColsumJob{prec, du, T, F, F, (float*)grads->b_1, (float*)at(scratch, p.partial_cs[0]), 0};
   RAF_TRY(gemm(prec, st, T, H, F, du, F, 1, wt ? wt_1 : w->w_1, wt ? F : H, wt ? 1 : 0, dffn, H));

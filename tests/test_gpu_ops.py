@@ -132,6 +132,14 @@ def test_gemm_epilogues_and_f32_out(precision):
         raf.raf_op_gemm(precision, M, N, K, a_dev, K, 1, w_dev, K, 1, c, N, epilogue=raf.EPI_MUL_GELU_GRAD, aux=u,
                         gelu_tanh=tanh_form)
         assert rel_fro(host(c), lin * L.gelu_grad(host(u), bool(tanh_form))) <= 2 * tol
+        # forward / backward pair that saves gelu'(pre-activation) instead of the pre-activation
+        dsave = torch.zeros(M, N, dtype=dt, device="cuda")
+        raf.raf_op_gemm(precision, M, N, K, a_dev, K, 1, w_dev, K, 1, c, N, epilogue=raf.EPI_BIAS_GELU_DERIV,
+                        bias=b_dev, aux=dsave, gelu_tanh=tanh_form)
+        assert rel_fro(host(c), L.gelu(lin + bias, bool(tanh_form))) <= 2 * tol
+        assert rel_fro(host(dsave), L.gelu_grad(lin + bias, bool(tanh_form))) <= 2 * tol
+        raf.raf_op_gemm(precision, M, N, K, a_dev, K, 1, w_dev, K, 1, c, N, epilogue=raf.EPI_MUL_AUX, aux=dsave)
+        assert rel_fro(host(c), lin * host(dsave)) <= 2 * tol
     # residual add
     R = rnd(rng, (M, N), precision)
     r_dev = to_dev(R, dt)
