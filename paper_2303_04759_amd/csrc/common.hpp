@@ -265,6 +265,8 @@ inline GemmArgs gemm_args_default() {
 }
 
 raf_status launch_gemm(int precision, const GemmArgs& g, hipStream_t st);
+// two batched problems with equal shapes, layouts and batch counts; one launch where a kernel supports it
+raf_status launch_gemm_pair(int precision, const GemmArgs& g1, const GemmArgs& g2, hipStream_t st);
 // up to 4 independent weight-gradient GEMMs (A, B MN-major, float out) in one launch
 raf_status launch_gemm_group_wgrad(int precision, const GemmArgs* gs, int count, hipStream_t st);
 // dst[c][r] = src[r][c] for up to 4 dense row-major bf16 matrices (rows, cols multiples of 8) in one launch

@@ -152,8 +152,8 @@ static GemmArgs wgrad_args(int M, int N, int K, const void* a, long lda, const v
 struct HeadView {
   const void* p; long ld; int kmajor; bool is_prob;   // is_prob: [B,heads,S,S] else [T, ld] with head offset 64*h
 };
-static raf_status gemm_heads(const Plan& p, int prec, hipStream_t st, int M, int N, int K, HeadView a, HeadView b,
-                             void* c, long ldc, bool c_is_prob, float alpha) {
+static GemmArgs heads_args(const Plan& p, int M, int N, int K, HeadView a, HeadView b, void* c, long ldc, bool c_is_prob,
+                           float alpha) {
   GemmArgs g = gemm_args_default();
   g.M = M; g.N = N; g.K = K;
   g.a = a.p; g.lda = a.ld; g.a_kmajor = a.kmajor;
@@ -164,7 +164,11 @@ static raf_status gemm_heads(const Plan& p, int prec, hipStream_t st, int M, int
   g.sa[0] = a.is_prob ? p.NH * p.S * p.S : p.S * a.ld; g.sa[1] = a.is_prob ? p.S * p.S : 64;
   g.sb[0] = b.is_prob ? p.NH * p.S * p.S : p.S * b.ld; g.sb[1] = b.is_prob ? p.S * p.S : 64;
   g.sc[0] = c_is_prob ? p.NH * p.S * p.S : p.S * ldc;  g.sc[1] = c_is_prob ? p.S * p.S : 64;
-  return launch_gemm(prec, g, st);
+  return g;
+}
+static raf_status gemm_heads(const Plan& p, int prec, hipStream_t st, int M, int N, int K, HeadView a, HeadView b,
+                             void* c, long ldc, bool c_is_prob, float alpha) {
+  return launch_gemm(prec, heads_args(p, M, N, K, a, b, c, ldc, c_is_prob, alpha), st);
 }
 
 }  // namespace raf
@@ -343,9 +347,9 @@ extern "C" raf_status raf_layer_bwd(const raf_layer_desc* desc, const raf_layer_
                           &rj[nr++]));
   // B5: a1 = c Wo^T + bo  ->  dc = da1 Wo                   [dWo = da1^T c deferred]
   RAF_TRY(gemm(prec, st, T, H, H, da1, H, 1, wt ? wt_o : w->w_o, H, wt ? 1 : 0, dc, H));
-  // B4: c = prob_d V  ->  dV = prob_d^T dc ; dprob_d = dc V^T
-  RAF_TRY(gemm_heads(p, prec, st, S, 64, S, HeadView{prob_d, S, 0, true}, HeadView{dc, H, 0, false},
-                     at(dqkv, (size_t)2 * H * e), 3 * H, false, 1.0f));
+  // B4: c = prob_d V  ->  dV = prob_d^T dc (launched below, together with dK) ; dprob_d = dc V^T
+  const GemmArgs dv_args = heads_args(p, S, 64, S, HeadView{prob_d, S, 0, true}, HeadView{dc, H, 0, false},
+                                      at(dqkv, (size_t)2 * H * e), 3 * H, false, 1.0f);
   if (prec == RAF_BF16_AMP) {
     // B4b+B3 fused: dprob_d stays in registers; dropout and softmax adjoints with the 1/8 folded in
     RAF_TRY(launch_attn_prob_bwd(d, dc, qkv, prob, prob_d, ds, st));
@@ -358,8 +362,10 @@ extern "C" raf_status raf_layer_bwd(const raf_layer_desc* desc, const raf_layer_
   // B2: s = Q K^T / 8  ->  dQ = ds K ; dK = ds^T Q
   RAF_TRY(gemm_heads(p, prec, st, S, 64, S, HeadView{ds, S, 1, true},
                      HeadView{at(qkv, (size_t)H * e), 3 * H, 0, false}, dqkv, 3 * H, false, 1.0f));
-  RAF_TRY(gemm_heads(p, prec, st, S, 64, S, HeadView{ds, S, 0, true}, HeadView{qkv, 3 * H, 0, false},
-                     at(dqkv, (size_t)H * e), 3 * H, false, 1.0f));
+  // dK and dV have the same shape and layout (A^T B over the query index): one launch
+  RAF_TRY(launch_gemm_pair(prec, heads_args(p, S, 64, S, HeadView{ds, S, 0, true}, HeadView{qkv, 3 * H, 0, false},
+                                            at(dqkv, (size_t)H * e), 3 * H, false, 1.0f),
+                           dv_args, st));
   // B1: qkv = attn_in Wqkv^T + bqkv
   cj[1] = ColsumJob{prec, dqkv, T, 3 * H, 3 * H, (float*)grads->b_qkv, (float*)at(scratch, p.partial_cs[1]), 0};
   if (d.pre_ln) {
