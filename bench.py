@@ -22,8 +22,8 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel on the bert_base workload, from the two rocprofv3 --pmc
 # runs summarised in profiles/bench_bert_base_hbm_traffic.txt (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00,
-# factors from a plain 256 MiB copy): 42.7 MB read + 6.3 MB written.
-DOMINANT_KERNEL_TRAFFIC_BYTES = {"bert_base": 49.0e6}
+# factors from a plain 256 MiB copy): 42.3 MB read + 6.3 MB written.
+DOMINANT_KERNEL_TRAFFIC_BYTES = {"bert_base": 48.6e6}
 DOMINANT_KERNEL_NAME = {"bert_base": "gemm_bf16_w48s_kernel<128x96 tiles, 8 consumer + 8 producer waves, 3 stages, K-major "
                                      "operands> (the five products with N = hidden: out/ffn2 forward, ffn1/out/qkv "
                                      "input gradients)"}
