@@ -165,11 +165,11 @@ __device__ __forceinline__ void epilogue_tile32(const GemmDev& g, TC* __restrict
   });
 }
 
-// A wave's 4 x 3 blocks of the (transposed) 16x16 MFMA result: a lane holds output row (l & 15) and the 4
+// A wave's 4 x NB blocks of the (transposed) 16x16 MFMA result: a lane holds output row (l & 15) and the 4
 // consecutive columns 4*(l>>4) + r of each block; only row blocks [i_begin, i_end) are written.
-template <typename TC>
+template <typename TC, int NB>
 __device__ __forceinline__ void epilogue_tile16(const GemmDev& g, TC* __restrict__ C, bf16_t* __restrict__ AUX,
-                                                f32x4_t (&acc)[4][3], int row0, int col0, int i_begin, int i_end) {
+                                                f32x4_t (&acc)[4][NB], int row0, int col0, int i_begin, int i_end) {
   const int lane = threadIdx.x & 63;
   epilogue_dispatch(g.epilogue, [&](auto tag) {
     constexpr int EPI = decltype(tag)::value;
@@ -179,7 +179,7 @@ __device__ __forceinline__ void epilogue_tile16(const GemmDev& g, TC* __restrict
       const int row = row0 + i * 16 + (lane & 15);
       if (row < g.M) {
 #pragma unroll
-        for (int j = 0; j < 3; ++j) {
+        for (int j = 0; j < NB; ++j) {
           const int col = col0 + j * 16 + 4 * (lane >> 4);
           if (col < g.N) {
             float v[4] = {acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]};

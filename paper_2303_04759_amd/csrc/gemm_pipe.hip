@@ -552,7 +552,7 @@ __global__ __launch_bounds__(64 * WGM * WGN * KS) void gemm_bf16_w48_kernel(Gemm
     i_end = i_begin + 2;
   }
 
-  epilogue_tile16<TC>(g, C, AUX, acc, m0 + wm, n0 + wn, i_begin, i_end);
+  epilogue_tile16<TC, 3>(g, C, AUX, acc, m0 + wm, n0 + wn, i_begin, i_end);
 }
 
 // Same tiles with the waves specialised: NP producer waves only issue the direct-to-LDS loads (a wave is held for
@@ -560,9 +560,9 @@ __global__ __launch_bounds__(64 * WGM * WGN * KS) void gemm_bf16_w48_kernel(Gemm
 // MFMAs), the WGM*WGN*KS consumer waves only read fragments and issue MFMAs.  One workgroup barrier per k-step keeps
 // both sides in step: after barrier `it` the consumers work on stage it while the producers refill the stage that was
 // freed and then wait until stage it+1 has landed.
-template <int WGM, int WGN, int NS, int KS, int NP, typename TC>
+template <int WGM, int WGN, int NB, int NS, int KS, int NP, typename TC>
 __global__ __launch_bounds__(64 * (WGM * WGN * KS + NP)) void gemm_bf16_w48s_kernel(GemmDev g, int tiles_m, int tiles_n) {
-  constexpr int NT = WGM * WGN, NC = NT * KS, BM = 64 * WGM, BN = 48 * WGN;
+  constexpr int NT = WGM * WGN, NC = NT * KS, BM = 64 * WGM, BN = 16 * NB * WGN;
   constexpr int ACH = BM / 8, BCH = BN / 8;           // KiB per operand tile
   constexpr int STAGE_BYTES = (ACH + BCH) * 1024;
   constexpr int BFIRST = ACH % NP;                    // producer that takes B chunk 0
@@ -650,12 +650,12 @@ __global__ __launch_bounds__(64 * (WGM * WGN * KS + NP)) void gemm_bf16_w48s_ker
   TC* __restrict__ C = (TC*)g.c;
   bf16_t* __restrict__ AUX = (bf16_t*)g.aux;
   const int wt = wave % NT, kg = wave / NT;           // output block of this wave, its half of each k-step
-  const int wm = (wt / WGN) * 64, wn = (wt % WGN) * 48;
-  f32x4_t acc[4][3];
+  const int wm = (wt / WGN) * 64, wn = (wt % WGN) * 16 * NB;
+  f32x4_t acc[4][NB];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 3; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < NB; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   int stage = 0;
   for (int it = 0; it < nk; ++it) {
     __builtin_amdgcn_s_barrier();   // stage `it` is complete
@@ -664,16 +664,16 @@ __global__ __launch_bounds__(64 * (WGM * WGN * KS + NP)) void gemm_bf16_w48s_ker
 #pragma unroll
     for (int kh = 0; kh < 2 / KS; ++kh) {
       const int kk = KS == 2 ? kg : kh;
-      bf16x8_t fa[4], fb[3];
+      bf16x8_t fa[4], fb[NB];
 #pragma unroll
       for (int i = 0; i < 4; ++i) fa[i] = w48_fragment(ta, wm + i * 16, kk);
 #pragma unroll
-      for (int j = 0; j < 3; ++j) fb[j] = w48_fragment(tb, wn + j * 16, kk);
+      for (int j = 0; j < NB; ++j) fb[j] = w48_fragment(tb, wn + j * 16, kk);
       // operands swapped: a lane ends with output row (l & 15) and 4 consecutive columns 4*(l>>4) + r
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 3; ++j)
+        for (int j = 0; j < NB; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
     }
     stage = stage + 1 == NS ? 0 : stage + 1;
@@ -683,19 +683,19 @@ __global__ __launch_bounds__(64 * (WGM * WGN * KS + NP)) void gemm_bf16_w48s_ker
   if (KS == 2) {
     // exchange: the wave with kg = 0 finishes row blocks 0-1, its partner row blocks 2-3; each sends the other half
     __builtin_amdgcn_s_barrier();   // every wave is done with the ring
-    f32x4_t* xch = reinterpret_cast<f32x4_t*>(lds) + (wt * 2 + (kg ^ 1)) * 6 * 64;   // slot read by the partner
+    f32x4_t* xch = reinterpret_cast<f32x4_t*>(lds) + (wt * 2 + (kg ^ 1)) * 2 * NB * 64;   // slot read by the partner
 #pragma unroll
     for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
-      for (int j = 0; j < 3; ++j) xch[(ii * 3 + j) * 64 + lane] = kg ? acc[ii][j] : acc[2 + ii][j];   // static indices: no scratch
+      for (int j = 0; j < NB; ++j) xch[(ii * NB + j) * 64 + lane] = kg ? acc[ii][j] : acc[2 + ii][j];   // static indices: no scratch
     __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): the writes above have reached LDS
     __builtin_amdgcn_s_barrier();
-    const f32x4_t* got = reinterpret_cast<const f32x4_t*>(lds) + (wt * 2 + kg) * 6 * 64;
+    const f32x4_t* got = reinterpret_cast<const f32x4_t*>(lds) + (wt * 2 + kg) * 2 * NB * 64;
 #pragma unroll
     for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
-      for (int j = 0; j < 3; ++j) {
-        const f32x4_t o = got[(ii * 3 + j) * 64 + lane];
+      for (int j = 0; j < NB; ++j) {
+        const f32x4_t o = got[(ii * NB + j) * 64 + lane];
         // fixed order: first k-half plus second k-half
         if (kg == 0) acc[ii][j] = acc[ii][j] + o;
         else acc[2 + ii][j] = o + acc[2 + ii][j];
@@ -704,19 +704,19 @@ __global__ __launch_bounds__(64 * (WGM * WGN * KS + NP)) void gemm_bf16_w48s_ker
     i_end = i_begin + 2;
   }
 
-  epilogue_tile16<TC>(g, C, AUX, acc, m0 + wm, n0 + wn, i_begin, i_end);
+  epilogue_tile16<TC, NB>(g, C, AUX, acc, m0 + wm, n0 + wn, i_begin, i_end);
 }
 
-template <int WGM, int WGN, int NS, int KS, int NP, typename TC>
+template <int WGM, int WGN, int NB, int NS, int KS, int NP, typename TC>
 static bool launch_w48s_inst(const GemmDev& d, hipStream_t st) {
-  constexpr int BM = 64 * WGM, BN = 48 * WGN;
+  constexpr int BM = 64 * WGM, BN = 16 * NB * WGN;
   constexpr int RING_BYTES = NS * (BM / 8 + BN / 8) * 1024;
-  constexpr int XCH_BYTES = KS == 2 ? WGM * WGN * 2 * 6 * 64 * 16 : 0;   // accumulator exchange of the wave pairs
+  constexpr int XCH_BYTES = KS == 2 ? WGM * WGN * 2 * 2 * NB * 64 * 16 : 0;   // accumulator exchange of the wave pairs
   constexpr int LDS_BYTES = RING_BYTES > XCH_BYTES ? RING_BYTES : XCH_BYTES;
   static_assert(LDS_BYTES <= 160 * 1024, "ring exceeds the LDS of a CU");
   static_assert((NS - 2) * ((BM / 8 + BN / 8 + NP - 1) / NP) <= 24, "in-flight loads exceed wait_vmcnt_dyn");
   static_assert(64 * (WGM * WGN * KS + NP) <= 1024, "workgroup too large");
-  auto kern = gemm_bf16_w48s_kernel<WGM, WGN, NS, KS, NP, TC>;
+  auto kern = gemm_bf16_w48s_kernel<WGM, WGN, NB, NS, KS, NP, TC>;
   static bool attr_done = false;   // per instantiation
   if (!attr_done) {
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess) {
@@ -815,14 +815,15 @@ bool launch_gemm_pipe(const GemmDev& d, int a_kmajor, int b_kmajor, int out_f32,
     switch (best) {
       // one 128x96 tile per CU: 8 consumer + 8 producer waves, three stages (measured 24 us against 33 us for the
       // 4096x768x3072 product)
-      case 1: return launch_w48s_inst<2, 2, 3, 2, 8, bf16_t>(d, st);
+      case 1: return launch_w48s_inst<2, 2, 3, 3, 2, 8, bf16_t>(d, st);
       case 2: return launch_w48_inst<2, 3, 2, 2, bf16_t>(d, st);
       case 3: return launch_w48_inst<2, 4, 2, 1, bf16_t>(d, st);
       case 4: return launch_w48_inst<4, 3, 2, 1, bf16_t>(d, st);
       case 5: return launch_w48_inst<4, 4, 2, 1, bf16_t>(d, st);
       default: break;
     }
-    return launch_pipe_layout<true, true, bf16_t>(d, batch, st);
+    // 128x128: the same producer/consumer kernel with 64x64 wave tiles
+    return launch_w48s_inst<2, 2, 4, 3, 2, 8, bf16_t>(d, st);
   }
   // with a transposed B operand the ring only wins when there are enough tiles
   // for two workgroups per CU; below that the register-staged kernel is faster
