@@ -224,7 +224,11 @@ extern "C" raf_status raf_layer_fwd(const raf_layer_desc* desc, const raf_layer_
   }
   // F1: qkv = attn_in . Wqkv^T + bqkv
   RAF_TRY(gemm(prec, st, T, 3 * H, H, attn_in, H, 1, w->w_qkv, H, 1, qkv, 3 * H, 0, EPI_BIAS, (const float*)w->b_qkv));
-  if (prec == RAF_BF16_AMP) {
+  const bool attn_fused = attn_fused_supported(d);   // S <= 128: F4 is taken inside the probability kernel
+  if (attn_fused) {
+    // F2+F3+F4 fused: scores, mask, softmax, dropout site 1, context
+    RAF_TRY(launch_attn_fwd_fused(d, qkv, seq_lens, prob, prob_d, c, step, st));
+  } else if (prec == RAF_BF16_AMP) {
     // F2+F3 fused: scores, mask, softmax, dropout site 1; the score tensor stays in registers
     RAF_TRY(launch_attn_prob_fwd(d, qkv, seq_lens, prob, prob_d, step, st));
   } else {
@@ -235,8 +239,9 @@ extern "C" raf_status raf_layer_fwd(const raf_layer_desc* desc, const raf_layer_
     RAF_TRY(launch_softmax_fwd(d, s, seq_lens, prob, prob_d, step, st));
   }
   // F4: c = prob_d . V, heads merged on store
-  RAF_TRY(gemm_heads(p, prec, st, S, 64, S, HeadView{prob_d, S, 1, true},
-                     HeadView{at(qkv, (size_t)2 * H * e), 3 * H, 0, false}, c, H, false, 1.0f));
+  if (!attn_fused)
+    RAF_TRY(gemm_heads(p, prec, st, S, 64, S, HeadView{prob_d, S, 1, true},
+                       HeadView{at(qkv, (size_t)2 * H * e), 3 * H, 0, false}, c, H, false, 1.0f));
   // F5: a1 = c . Wo^T + bo
   RAF_TRY(gemm(prec, st, T, H, H, c, H, 1, w->w_o, H, 1, a, H, 0, EPI_BIAS, (const float*)w->b_o));
   // F6: z1 = x + drop2(a1); ffn_in = LN(z1)   (LN1 in post-LN, LN2 in pre-LN)
@@ -350,7 +355,11 @@ extern "C" raf_status raf_layer_bwd(const raf_layer_desc* desc, const raf_layer_
   // B4: c = prob_d V  ->  dV = prob_d^T dc (launched below, together with dK) ; dprob_d = dc V^T
   const GemmArgs dv_args = heads_args(p, S, 64, S, HeadView{prob_d, S, 0, true}, HeadView{dc, H, 0, false},
                                       at(dqkv, (size_t)2 * H * e), 3 * H, false, 1.0f);
-  if (prec == RAF_BF16_AMP) {
+  const bool attn_fused = attn_fused_supported(d);   // S <= 128: dQ is taken inside the probability kernel
+  if (attn_fused) {
+    // B4b+B3 and the dQ half of B2 fused
+    RAF_TRY(launch_attn_bwd_fused(d, dc, qkv, prob, prob_d, ds, dqkv, st));
+  } else if (prec == RAF_BF16_AMP) {
     // B4b+B3 fused: dprob_d stays in registers; dropout and softmax adjoints with the 1/8 folded in
     RAF_TRY(launch_attn_prob_bwd(d, dc, qkv, prob, prob_d, ds, st));
   } else {
@@ -360,8 +369,9 @@ extern "C" raf_status raf_layer_bwd(const raf_layer_desc* desc, const raf_layer_
     RAF_TRY(launch_softmax_bwd(d, prob, prob_d, dprob_d, ds, alpha, st));
   }
   // B2: s = Q K^T / 8  ->  dQ = ds K ; dK = ds^T Q
-  RAF_TRY(gemm_heads(p, prec, st, S, 64, S, HeadView{ds, S, 1, true},
-                     HeadView{at(qkv, (size_t)H * e), 3 * H, 0, false}, dqkv, 3 * H, false, 1.0f));
+  if (!attn_fused)
+    RAF_TRY(gemm_heads(p, prec, st, S, 64, S, HeadView{ds, S, 1, true},
+                       HeadView{at(qkv, (size_t)H * e), 3 * H, 0, false}, dqkv, 3 * H, false, 1.0f));
   // dK and dV have the same shape and layout (A^T B over the query index): one launch
   RAF_TRY(launch_gemm_pair(prec, heads_args(p, S, 64, S, HeadView{ds, S, 0, true}, HeadView{qkv, 3 * H, 0, false},
                                             at(dqkv, (size_t)H * e), 3 * H, false, 1.0f),
