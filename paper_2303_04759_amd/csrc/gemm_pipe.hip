@@ -404,7 +404,7 @@ bool launch_gemm_group_spec(const GemmDev* ds, int count, hipStream_t st) {
 // whole rounds when 128-wide tiles would leave most of the last round idle
 // (N = 2304: 16 x 16 tiles of 256x144, one per CU, instead of 576 of 128x128),
 // and the tall variants halve the bytes fetched per flop, which is what bounds
-// these kernels (about 40 bytes/clock/CU arrive from L2).  Each of the
+// these kernels (direct loads deliver at most about 52 bytes/clock/CU).  Each of the
 // WGM x WGN wavefronts owns 64 x 48 outputs as 4 x 3 blocks of
 // v_mfma_f32_16x16x32_bf16.  Same direct-to-LDS ring and swizzle as above, NS
 // stages deep; the KiB chunks of a stage are dealt round-robin to the waves, so
@@ -756,9 +756,9 @@ static bool launch_w48_inst(const GemmDev& d, hipStream_t st) {
   return true;
 }
 
-// 128x128 tiles, 8 wavefronts (2 x 4), two 32 KiB stages: two workgroups share a
-// CU (16 waves).  Measured on MI355X against 4-wave workgroups, deeper rings and
-// 256-wide tiles, this is the fastest variant for every shape of the layer.
+// 128x128 tiles, 8 wavefronts (2 x 4), two 32 KiB stages, two workgroups per CU (16 waves): the variant for a
+// K-major A with an MN-major B (products against an untransposed row-major weight, e.g. the tied decoder of the
+// MLM head) when there are enough tiles for two workgroups per CU.
 template <bool AK, bool BKM, typename TC>
 static bool launch_pipe_layout(const GemmDev& d, int batch, hipStream_t st) {
   return launch_pipe_inst<128, 128, 2, 4, AK, BKM, TC, 2>(d, batch, st);
