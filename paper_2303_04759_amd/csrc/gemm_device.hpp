@@ -192,6 +192,127 @@ __device__ __forceinline__ void epilogue_tile16(const GemmDev& g, TC* __restrict
 }
 
 
+// Bytes of LDS one wave needs for epilogue_tile16_staged.
+template <int NB>
+constexpr int epilogue_stage_bytes() {
+  return 2 * 16 * (32 * NB + 16);
+}
+
+// True when the output (and aux) rows of a problem can be written 16 bytes at a time.
+__device__ __forceinline__ bool epilogue_can_stage(const GemmDev& g) {
+  const unsigned long long p = (unsigned long long)g.c | (unsigned long long)g.aux;
+  return ((g.ldc | g.ldaux | (long)g.N) & 7) == 0 && (p & 15) == 0;
+}
+
+// Same result as epilogue_tile16 for bf16 outputs, written through a wave-private LDS buffer: the accumulator
+// layout gives a lane 4 columns of one row, so a direct store instruction touches 16 rows with 32 bytes each, and
+// such stores cost several times the time of full-row ones (5.5 us against 0.7 us for the 19-MB output of a
+// 4096 x 2304 product).  The blocks are therefore finished in registers, laid out row-major in LDS and written
+// (aux operands: read) as 16-byte pieces that run along the rows of the wave tile: two 16-row blocks per trip, an
+// aux operand being replaced in place by the result; one block per trip with two buffers for the epilogues that
+// write a second output.  LDS operations of one wave execute in order, so no barrier is needed; `stg` must not be
+// touched by any other wave.
+template <int NB>
+__device__ __forceinline__ void epilogue_tile16_staged(const GemmDev& g, bf16_t* __restrict__ C,
+                                                       bf16_t* __restrict__ AUX, f32x4_t (&acc)[4][NB], int row0,
+                                                       int col0, int i_begin, int i_end, char* stg) {
+  constexpr int P = 32 * NB + 16;         // row pitch in LDS, bytes
+  constexpr int CPR = 2 * NB;             // 16-byte pieces per row
+  const int lane = threadIdx.x & 63;
+  const int lr = lane & 15, lg = lane >> 4;
+  epilogue_dispatch(g.epilogue, [&](auto tag) {
+    constexpr int EPI = decltype(tag)::value;
+    constexpr bool AUX_IN = EPI == EPI_MUL_GELU_GRAD || EPI == EPI_ADD_RES || EPI == EPI_MUL_AUX;
+    constexpr bool AUX_OUT = EPI == EPI_BIAS_GELU || EPI == EPI_BIAS_GELU_DERIV;
+    constexpr bool BIAS = EPI == EPI_BIAS || EPI == EPI_BIAS_GELU || EPI == EPI_BIAS_GELU_DERIV;
+    constexpr int BLK = AUX_OUT ? 1 : 2;  // row blocks per trip through LDS
+    constexpr int ROWS = 16 * BLK, NCH = ROWS * CPR, IT = (NCH + 63) / 64;
+    char* s_out = stg;
+    char* s_aux = AUX_OUT ? stg + 16 * P : stg;
+    // piece `it` of this lane: row and 16-byte column within a trip
+    int pr[IT], pc[IT];
+#pragma unroll
+    for (int it = 0; it < IT; ++it) {
+      const int q = it * 64 + lane;
+      pr[it] = q / CPR;
+      pc[it] = q - pr[it] * CPR;
+    }
+    // aux pieces of one trip; the next trip's are requested as soon as these have gone to LDS
+    uint4 ain[IT];
+    auto load_aux = [&](int t) {
+#pragma unroll
+      for (int it = 0; it < IT; ++it) {
+        const int row = row0 + t * ROWS + pr[it], col = col0 + pc[it] * 8;
+        ain[it] = make_uint4(0u, 0u, 0u, 0u);
+        if (pr[it] < ROWS && row < g.M && col < g.N)
+          ain[it] = *reinterpret_cast<const uint4*>(AUX + (long)row * g.ldaux + col);
+      }
+    };
+    if constexpr (AUX_IN) load_aux(i_begin / BLK);
+    float4 bias[BIAS ? NB : 1];
+    if constexpr (BIAS) {
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+        const int col = col0 + j * 16 + 4 * lg;
+        bias[j] = col < g.N ? *reinterpret_cast<const float4*>(g.bias + col) : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < 4 / BLK; ++t) {
+      if (t * BLK < i_begin || t * BLK >= i_end) continue;
+      if constexpr (AUX_IN) {
+#pragma unroll
+        for (int it = 0; it < IT; ++it)
+          if (pr[it] < ROWS) *reinterpret_cast<uint4*>(s_aux + pr[it] * P + pc[it] * 16) = ain[it];
+        if ((t + 1) * BLK < i_end) load_aux(t + 1);
+      }
+#pragma unroll
+      for (int b = 0; b < BLK; ++b)
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+          const int i = t * BLK + b;
+          const int off = (b * 16 + lr) * P + j * 32 + lg * 8;
+          float v[4] = {acc[i][j][0] * g.alpha, acc[i][j][1] * g.alpha, acc[i][j][2] * g.alpha, acc[i][j][3] * g.alpha};
+          if constexpr (BIAS) {
+            v[0] += bias[j].x; v[1] += bias[j].y; v[2] += bias[j].z; v[3] += bias[j].w;
+          }
+          if constexpr (EPI == EPI_BIAS_GELU) {
+            store4(reinterpret_cast<bf16_t*>(s_aux + off), v);
+            // GeLU is evaluated on the value the backward pass will read back
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = gelu_f((float)(bf16_t)v[e], g.gelu_tanh);
+          } else if constexpr (EPI == EPI_BIAS_GELU_DERIV) {
+            float dy[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) gelu_and_grad_f(v[e], g.gelu_tanh, v[e], dy[e]);
+            store4(reinterpret_cast<bf16_t*>(s_aux + off), dy);
+          } else if constexpr (AUX_IN) {
+            float u[4];
+            load4(reinterpret_cast<const bf16_t*>(s_aux + off), u);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              if constexpr (EPI == EPI_MUL_GELU_GRAD) v[e] *= gelu_grad_f(u[e], g.gelu_tanh);
+              else if constexpr (EPI == EPI_ADD_RES) v[e] += u[e];
+              else v[e] *= u[e];
+            }
+          }
+          store4(reinterpret_cast<bf16_t*>(s_out + off), v);
+        }
+#pragma unroll
+      for (int it = 0; it < IT; ++it) {
+        const int row = row0 + t * ROWS + pr[it], col = col0 + pc[it] * 8;
+        if (pr[it] < ROWS && row < g.M && col < g.N) {
+          *reinterpret_cast<uint4*>(C + (long)row * g.ldc + col) =
+              *reinterpret_cast<const uint4*>(s_out + pr[it] * P + pc[it] * 16);
+          if constexpr (AUX_OUT)
+            *reinterpret_cast<uint4*>(AUX + (long)row * g.ldaux + col) =
+                *reinterpret_cast<const uint4*>(s_aux + pr[it] * P + pc[it] * 16);
+        }
+      }
+    }
+  });
+}
+
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x8_t __attribute__((ext_vector_type(8)));
 

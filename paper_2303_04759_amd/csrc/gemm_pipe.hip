@@ -529,6 +529,12 @@ __global__ __launch_bounds__(64 * WGM * WGN * KS) void gemm_bf16_w48_kernel(Gemm
   }
 
   int i_begin = 0, i_end = 4;
+  // wave-private LDS for the staged epilogue: with one wave per block a slice of the ring stage that nobody reads
+  // any more (every wave has passed the last barrier, so all reads of the stage before the last one are done and no
+  // load is in flight), with wave pairs the slot this wave received its partner's accumulators in
+  static_assert(KS == 2 || NW * epilogue_stage_bytes<3>() <= STAGE_BYTES, "staging exceeds a ring stage");
+  static_assert(epilogue_stage_bytes<3>() <= 6 * 64 * 16, "staging exceeds an exchange slot");
+  char* stg = lds + stage * STAGE_BYTES + wave * epilogue_stage_bytes<3>();
   if (KS == 2) {
     // exchange: the wave with kg = 0 finishes row blocks 0-1, its partner row blocks 2-3; each sends the other half
     __builtin_amdgcn_s_barrier();   // every wave is done with the ring
@@ -539,6 +545,7 @@ __global__ __launch_bounds__(64 * WGM * WGN * KS) void gemm_bf16_w48_kernel(Gemm
       for (int j = 0; j < 3; ++j) xch[(ii * 3 + j) * 64 + lane] = kg ? acc[ii][j] : acc[2 + ii][j];   // static indices: no scratch
     __syncthreads();
     const f32x4_t* got = reinterpret_cast<const f32x4_t*>(lds) + (wt * 2 + kg) * 6 * 64;
+    stg = lds + (wt * 2 + kg) * 6 * 64 * 16;
 #pragma unroll
     for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
@@ -552,6 +559,12 @@ __global__ __launch_bounds__(64 * WGM * WGN * KS) void gemm_bf16_w48_kernel(Gemm
     i_end = i_begin + 2;
   }
 
+  if constexpr (sizeof(TC) == 2) {
+    if (epilogue_can_stage(g)) {
+      epilogue_tile16_staged<3>(g, C, AUX, acc, m0 + wm, n0 + wn, i_begin, i_end, stg);
+      return;
+    }
+  }
   epilogue_tile16<TC, 3>(g, C, AUX, acc, m0 + wm, n0 + wn, i_begin, i_end);
 }
 
@@ -680,6 +693,13 @@ __global__ __launch_bounds__(64 * (WGM * WGN * KS + NP)) void gemm_bf16_w48s_ker
   }
 
   int i_begin = 0, i_end = 4;
+  // wave-private LDS for the staged epilogue: with one wave per block a slice of the ring stage that nobody reads
+  // any more (every consumer has passed the last barrier, so all reads of the stage before the last one are done,
+  // and the producers have no load in flight), with wave pairs the slot this wave received its partner's
+  // accumulators in
+  static_assert(KS == 2 || NC * epilogue_stage_bytes<NB>() <= STAGE_BYTES, "staging exceeds a ring stage");
+  static_assert(epilogue_stage_bytes<NB>() <= 2 * NB * 64 * 16, "staging exceeds an exchange slot");
+  char* stg = KS == 2 ? lds + (wt * 2 + kg) * 2 * NB * 64 * 16 : lds + stage * STAGE_BYTES + wave * epilogue_stage_bytes<NB>();
   if (KS == 2) {
     // exchange: the wave with kg = 0 finishes row blocks 0-1, its partner row blocks 2-3; each sends the other half
     __builtin_amdgcn_s_barrier();   // every wave is done with the ring
@@ -704,6 +724,12 @@ __global__ __launch_bounds__(64 * (WGM * WGN * KS + NP)) void gemm_bf16_w48s_ker
     i_end = i_begin + 2;
   }
 
+  if constexpr (sizeof(TC) == 2) {
+    if (epilogue_can_stage(g)) {
+      epilogue_tile16_staged<NB>(g, C, AUX, acc, m0 + wm, n0 + wn, i_begin, i_end, stg);
+      return;
+    }
+  }
   epilogue_tile16<TC, NB>(g, C, AUX, acc, m0 + wm, n0 + wn, i_begin, i_end);
 }
 
