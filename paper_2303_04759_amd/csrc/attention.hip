@@ -309,34 +309,74 @@ __global__ __launch_bounds__(256) void attn_prob_bwd_kernel(const bf16_t* __rest
 
 // ------------------------------------------- fused kernels for S <= 128 --
 // With the whole key range in one chunk the probabilities of a wave are already in registers in the layout of an
-// MFMA operand (a lane holds 8 consecutive keys of its query row per 32-key group), so the product that follows
-// them is taken in the same kernel: context = P~ . V in the forward pass, dQ = ds . K in the backward pass.  The
-// other operand ([S keys][64] of this head) is staged once per workgroup in LDS and read with the transposing
-// ds_read_b64_tr_b16; two batched GEMM launches (and their reads of P~ and ds) disappear.
+// MFMA operand (a lane holds 8 consecutive keys of its query row per 32-key group), so the products that follow
+// them are taken in the same kernel and no S x S tensor reaches memory at all:
+//   forward : context = P~ . V; the probabilities are not stored
+//   backward: P and the dropout mask are recomputed from Q, K and the counter-based generator, ds is formed in
+//             registers, and dQ = ds . K, dV = P~^T . dC and dK = ds^T . Q follow, the last two through LDS copies
+//             of P~ and ds (their contraction runs over the query index, which is spread over the waves).
+// One workgroup of 8 waves per (batch, head); wave w owns query rows 16w .. 16w+15.  The [S][64] operands of the
+// head (K, V, dC, Q) are brought into LDS once per workgroup by direct-to-LDS loads: loads into registers sustain
+// only about 16 bytes/clock/CU, and with every wave fetching its own K and V fragments from global memory that rate,
+// not the arithmetic, set the time of these kernels.  Fragments whose contraction index is the row index of the
+// tile are read with the transposing ds_read_b64_tr_b16.
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x8_t __attribute__((ext_vector_type(8)));
-constexpr int HT_PITCH = 160;   // bytes per key row of a staged tile: 128 data + 32 pad; rows with bit 3 set swap
-                                // their 64-byte halves, so the 8 key rows x 16 bytes one half-wave reads are conflict-free
+typedef __attribute__((address_space(3))) void* att_lds_ptr;
+typedef s16x4_t __attribute__((address_space(3))) * att_lds_v4_ptr;
 
-__device__ __forceinline__ void stage_head_tile(const bf16_t* __restrict__ src, long ld, int S, char* tile) {
-  for (int idx = threadIdx.x; idx < S * 8; idx += 256) {
-    const int r = idx >> 3, c = idx & 7;
-    const uint4 v = *reinterpret_cast<const uint4*>(src + (long)r * ld + c * 8);
-    *reinterpret_cast<uint4*>(tile + r * HT_PITCH + ((c * 16) ^ (((r >> 3) & 1) << 6))) = v;
-  }
+// [rows][64] bf16 tile, 128 bytes per row (the direct loads fill whole KiB of 8 rows); the 16-byte chunk c of row r
+// sits at chunk position c ^ hd_swz(r).  The swizzle makes both access patterns conflict-free: the 16 key rows
+// {0-3, 8-11, 16-19, 24-27} + 4v that one 16-lane group reads at a common chunk, and the 8 rows {0-3, 8-11} x 32
+// bytes that a half-wave reads transposed.
+constexpr int HD_TILE = ATT_KC * 128;
+__device__ __forceinline__ int hd_swz(int r) {
+  return (((r >> 1) & 1) << 1) | (((r >> 3) & 1) << 2) | (((r >> 2) ^ (r >> 4)) & 1);
 }
 
-// X^T fragment of the staged tile X [keys][64]: lane l gets row d = 16*nb + (l & 15), keys 32*u + 8*(l >> 4) .. +7
-__device__ __forceinline__ bf16x8_t head_tile_frag_t(const char* tile, int u, int nb) {
+// rows [0, S) of a head ([S][64] at row stride ld) -> tile, issued by all waves of the workgroup; complete for the
+// workgroup after hd_tile_wait() and a barrier
+__device__ __forceinline__ void hd_tile_load(const bf16_t* __restrict__ src, long ld, int S, char* tile) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
+  for (int q = wave; q < S / 8; q += nw) {
+    const int r = q * 8 + (lane >> 3);
+    const bf16_t* g = src + (long)r * ld + (((lane & 7) ^ hd_swz(r)) << 3);
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g, (att_lds_ptr)(tile + q * 1024), 16,
+                                     0, 0);
+  }
+}
+__device__ __forceinline__ void hd_tile_wait() { __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8)); }   // vmcnt(0)
+
+// operand fragment of a tile row: elements 32*kk + 8*(l >> 4) .. +7 of row `row`
+__device__ __forceinline__ bf16x8_t hd_frag(const char* tile, int row, int kk) {
+  const int c = 4 * kk + ((threadIdx.x & 63) >> 4);
+  return *reinterpret_cast<const bf16x8_t*>(tile + row * 128 + ((c ^ hd_swz(row)) << 4));
+}
+
+// X^T fragment of a tile X [rows][64]: lane l gets d = 16*nb + (l & 15), rows 32*u + 8*(l >> 4) .. +7
+__device__ __forceinline__ bf16x8_t hd_frag_t(const char* tile, int u, int nb) {
   const int lane = threadIdx.x & 63, g = lane >> 4, s = lane & 15;
-  const int r = 32 * u + 8 * g + (s >> 2);                    // key row of the first four values; +4 for the rest
-  const int boff = (32 * nb + 8 * (s & 3)) ^ ((g & 1) << 6);  // (r >> 3) & 1 == g & 1 for both rows
-  typedef s16x4_t __attribute__((address_space(3))) * lds_v4_ptr;
-  const char* p = tile + r * HT_PITCH + boff;
-  const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4_ptr)(p));
-  const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4_ptr)(p + 4 * HT_PITCH));
+  const int r = 32 * u + 8 * g + (s >> 2);                    // row of the first four values; +4 for the rest
+  const int c = 2 * nb + ((s & 3) >> 1), half = (s & 1) << 3;
+  const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((att_lds_v4_ptr)(tile + r * 128 + ((c ^ hd_swz(r)) << 4) + half));
+  const s16x4_t hi =
+      __builtin_amdgcn_ds_read_tr16_b64_v4i16((att_lds_v4_ptr)(tile + (r + 4) * 128 + ((c ^ hd_swz(r + 4)) << 4) + half));
   const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   return __builtin_bit_cast(bf16x8_t, both);
+}
+
+// chunk_products with the key-side operand (K or V) in an LDS tile
+__device__ __forceinline__ void tile_products(const char* tile, const bf16x8_t (&qf)[2], f32x4_t (&acc)[ATT_TILES],
+                                              int npairs) {
+  const int m = threadIdx.x & 15;
+#pragma unroll
+  for (int t = 0; t < ATT_TILES; ++t) {
+    const int u = t >> 1, v = t & 1;
+    const int row = (u < npairs ? 32 * u : 0) + 8 * (m >> 2) + 4 * v + (m & 3);
+    const f32x4_t zero = {0.f, 0.f, 0.f, 0.f};
+    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hd_frag(tile, row, 0), qf[0], zero, 0, 0, 0);
+    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hd_frag(tile, row, 1), qf[1], acc[t], 0, 0, 0);
+  }
 }
 
 __device__ __forceinline__ uint4 pack8_bf16(const float (&v)[8]) {
@@ -346,22 +386,9 @@ __device__ __forceinline__ uint4 pack8_bf16(const float (&v)[8]) {
   return r;
 }
 
-// out[query][64*h + d] = sum_keys frag[u] (this lane's 8 keys per group) x tile[key][d]; 8-byte stores
-__device__ __forceinline__ void head_product_store(const char* tile, const uint4 (&frag)[ATT_PAIRS], int npairs,
-                                                   bf16_t* __restrict__ out_row) {
+__device__ __forceinline__ void store_head_row(bf16_t* __restrict__ out_row, const f32x4_t (&acc)[4]) {
+  // the lane holds its row and d = 16*nb + 4*(l >> 4) + r
   const int lane = threadIdx.x & 63;
-  f32x4_t acc[4];
-#pragma unroll
-  for (int nb = 0; nb < 4; ++nb) acc[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-  for (int u = 0; u < ATT_PAIRS; ++u)
-    if (u < npairs) {
-      const bf16x8_t pf = __builtin_bit_cast(bf16x8_t, frag[u]);
-#pragma unroll
-      for (int nb = 0; nb < 4; ++nb)
-        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(head_tile_frag_t(tile, u, nb), pf, acc[nb], 0, 0, 0);
-    }
-  // the lane ends with its query row and d = 16*nb + 4*(l >> 4) + r
 #pragma unroll
   for (int nb = 0; nb < 4; ++nb) {
     uint2 r;
@@ -371,123 +398,211 @@ __device__ __forceinline__ void head_product_store(const char* tile, const uint4
   }
 }
 
-__global__ __launch_bounds__(256) void attn_fwd_fused_kernel(const bf16_t* __restrict__ qkv, const int32_t* __restrict__ lens,
-                                                             bf16_t* __restrict__ prob, bf16_t* __restrict__ prob_d,
+// out[query][64*h + d] = sum_keys frag[u] (this lane's 8 keys per group) x tile[key][d]
+__device__ __forceinline__ void head_product_store(const char* tile, const uint4 (&frag)[ATT_PAIRS], int npairs,
+                                                   bf16_t* __restrict__ out_row) {
+  f32x4_t acc[4];
+#pragma unroll
+  for (int nb = 0; nb < 4; ++nb) acc[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int u = 0; u < ATT_PAIRS; ++u)
+    if (u < npairs) {
+      const bf16x8_t pf = __builtin_bit_cast(bf16x8_t, frag[u]);
+#pragma unroll
+      for (int nb = 0; nb < 4; ++nb)
+        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hd_frag_t(tile, u, nb), pf, acc[nb], 0, 0, 0);
+    }
+  store_head_row(out_row, acc);
+}
+
+// scores -> mask -> softmax of this lane's query row: acc holds P (not yet divided by the sum) on return, the
+// reciprocal of the row sum is returned (0 for a row without admissible keys)
+__device__ __forceinline__ float row_softmax(f32x4_t (&acc)[ATT_TILES], int npairs, int limit, float alpha2) {
+  const int jl = 8 * ((threadIdx.x & 63) >> 4);
+  float mx = -INFINITY;
+#pragma unroll
+  for (int t = 0; t < ATT_TILES; ++t)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int j = 32 * (t >> 1) + jl + 4 * (t & 1) + r;
+      const float sc = ((t >> 1) < npairs && j < limit) ? acc[t][r] * alpha2 : -INFINITY;
+      acc[t][r] = sc;
+      mx = fmaxf(mx, sc);
+    }
+  mx = xgroup_max(mx);
+  const float ref = mx == -INFINITY ? 0.f : mx;         // row without admissible keys: every term is 2^-inf = 0
+  float sum = 0.f;
+#pragma unroll
+  for (int t = 0; t < ATT_TILES; ++t)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      acc[t][r] = exp2_hw(acc[t][r] - ref);
+      sum += acc[t][r];
+    }
+  sum = xgroup_sum(sum);
+  return sum > 0.f ? 1.0f / sum : 0.f;
+}
+
+__global__ __launch_bounds__(512) void attn_fwd_fused_kernel(const bf16_t* __restrict__ qkv, const int32_t* __restrict__ lens,
                                                              bf16_t* __restrict__ ctx, int S, int H, int heads, int causal,
                                                              float alpha2, DropSite drop) {
-  __shared__ __attribute__((aligned(16))) char vt[ATT_KC * HT_PITCH];
+  __shared__ __attribute__((aligned(1024))) char kt[HD_TILE];
+  __shared__ __attribute__((aligned(1024))) char vt[HD_TILE];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int bh = blockIdx.y, b = bh / heads, h = bh % heads;
+  const int bh = blockIdx.x, b = bh / heads, h = bh % heads;
   const long ld = 3L * H;
   const bf16_t* Q = qkv + ((long)b * S) * ld + h * 64;
-  const bf16_t* K = Q + H;
-  stage_head_tile(Q + 2 * H, ld, S, vt);                // V of this head; read after the barrier below
-  const int i0 = (blockIdx.x * 4 + wave) * ATT_ROWS;    // first query row of this wave
+  hd_tile_load(Q + H, ld, S, kt);
+  hd_tile_load(Q + 2 * H, ld, S, vt);
+  const int i0 = wave * ATT_ROWS;                        // first query row of this wave
   const bool active = i0 < S;                            // S is a multiple of 32: a wave is all in or all out
   const int npairs = S / 32;
-  uint4 pdf[ATT_PAIRS];
   const int i = i0 + (lane & 15);                        // this lane's query row
+  bf16x8_t qf[2];
+  if (active) load_frags(Q, i, ld, qf);
+  hd_tile_wait();
+  __syncthreads();                                        // K and V tiles complete
+  if (!active) return;
+  const int jl = 8 * (lane >> 4);                        // this lane's first key within a 32-key group
+  int len = lens ? lens[b] : S;
+  len = len < 0 ? 0 : (len > S ? S : len);
+  const int limit = causal ? (len < i + 1 ? len : i + 1) : len;      // keys >= limit are masked
+  const long row_off = ((long)bh * S + i) * S;
+  f32x4_t acc[ATT_TILES];
+  tile_products(kt, qf, acc, npairs);
+  const float inv = row_softmax(acc, npairs, limit, alpha2);
+  uint4 pdf[ATT_PAIRS];
+#pragma unroll
+  for (int u = 0; u < ATT_PAIRS; ++u) {
+    pdf[u] = make_uint4(0, 0, 0, 0);
+    if (u < npairs) {
+      float p[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) p[e] = acc[2 * u + (e >> 2)][e & 3] * inv;
+      if (drop.enabled) {
+        float mult[8];
+        drop_mult8(drop, (uint64_t)(row_off + 32 * u + jl), mult);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) p[e] *= mult[e];
+      }
+      pdf[u] = pack8_bf16(p);
+    }
+  }
+  head_product_store(vt, pdf, npairs, ctx + ((long)b * S + i) * H + h * 64);
+}
+
+// [S][S] tile of P~ or ds in LDS, row = query: 256 data bytes per row at a pitch of 288, rows with bit 3 set have
+// their 128-byte halves swapped, so that the 8 rows x 32 bytes one half-wave reads transposed are conflict-free.
+constexpr int SQ_PITCH = 288;
+// K | dC, later Q | V, later P~ and ds (the last tile is longer than V and extends beyond it)
+constexpr int ATT_BWD_LDS = 2 * HD_TILE + ATT_KC * SQ_PITCH;
+
+// this lane's 8 values of each 32-key group of query row `row` (0 .. S-1 within the head)
+__device__ __forceinline__ void sq_tile_write(char* tile, int row, const uint4 (&frag)[ATT_PAIRS], int npairs) {
+  const int g = (threadIdx.x & 63) >> 4;
+  char* p = tile + row * SQ_PITCH;
+  const int swap = ((row >> 3) & 1) << 7;
+#pragma unroll
+  for (int u = 0; u < ATT_PAIRS; ++u)
+    if (u < npairs) *reinterpret_cast<uint4*>(p + ((64 * u + 16 * g) ^ swap)) = frag[u];
+}
+
+// X^T fragment of such a tile: lane l gets row key = 16*kb + (l & 15), queries 32*u + 8*(l >> 4) .. +7
+__device__ __forceinline__ bf16x8_t sq_tile_frag_t(const char* tile, int u, int kb) {
+  const int lane = threadIdx.x & 63, g = lane >> 4, s = lane & 15;
+  const int r = 32 * u + 8 * g + (s >> 2);                    // query row of the first four values; +4 for the rest
+  const int boff = (32 * kb + 8 * (s & 3)) ^ ((g & 1) << 7);  // (r >> 3) & 1 == g & 1 for both rows
+  const char* p = tile + r * SQ_PITCH + boff;
+  const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((att_lds_v4_ptr)(p));
+  const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((att_lds_v4_ptr)(p + 4 * SQ_PITCH));
+  const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8_t, both);
+}
+
+// out[key][64*h + d] = sum_queries sq[query][key] x xt[query][d] for the 16 keys of block kb
+__device__ __forceinline__ void key_product_store(const char* sq, const char* xt, int npairs, int kb,
+                                                  bf16_t* __restrict__ out_row) {
+  f32x4_t acc[4];
+#pragma unroll
+  for (int nb = 0; nb < 4; ++nb) acc[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int u = 0; u < ATT_PAIRS; ++u)
+    if (u < npairs) {
+      const bf16x8_t yf = sq_tile_frag_t(sq, u, kb);
+#pragma unroll
+      for (int nb = 0; nb < 4; ++nb)
+        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hd_frag_t(xt, u, nb), yf, acc[nb], 0, 0, 0);
+    }
+  store_head_row(out_row, acc);
+}
+
+// Wave w owns query rows 16w .. 16w+15 until ds is formed and key rows 16w .. 16w+15 of dV and dK afterwards.
+// alpha2 = log2(e)/8 as in the forward pass, alpha = 1/8.
+__global__ __launch_bounds__(512) void attn_bwd_full_kernel(const bf16_t* __restrict__ dc, const bf16_t* __restrict__ qkv,
+                                                            const int32_t* __restrict__ lens, bf16_t* __restrict__ dqkv,
+                                                            int S, int H, int heads, int causal, float alpha2,
+                                                            float alpha, DropSite drop) {
+  extern __shared__ __attribute__((aligned(1024))) char att_lds[];
+  char* kt = att_lds;                          // K of this head
+  char* xt = kt + HD_TILE;                     // dC, later Q
+  char* vt = xt + HD_TILE;                     // V
+  char* sq = vt;                               // P~, later ds: written only after every wave is done with V
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int bh = blockIdx.x, b = bh / heads, h = bh % heads;
+  const long ld = 3L * H;
+  const bf16_t* Q = qkv + ((long)b * S) * ld + h * 64;
+  const bf16_t* DC = dc + ((long)b * S) * H + h * 64;
+  hd_tile_load(Q + H, ld, S, kt);
+  hd_tile_load(Q + 2 * H, ld, S, vt);
+  hd_tile_load(DC, H, S, xt);
+  const int i0 = wave * ATT_ROWS;
+  const bool active = i0 < S;                            // S is a multiple of 32: a wave is all in or all out
+  const int npairs = S / 32;
+  const int i = i0 + (lane & 15);                        // this lane's query row, later its key row
+  bf16_t* out_row = dqkv + ((long)b * S + i) * ld + h * 64;
+  bf16x8_t qf[2], gf[2];
+  if (active) {
+    load_frags(Q, i, ld, qf);
+    load_frags(DC, i, H, gf);
+  }
+  hd_tile_wait();
+  __syncthreads();                                        // K, V and dC tiles complete
+  uint4 pdf[ATT_PAIRS], dsf[ATT_PAIRS];
   if (active) {
     const int jl = 8 * (lane >> 4);                      // this lane's first key within a 32-key group
     int len = lens ? lens[b] : S;
     len = len < 0 ? 0 : (len > S ? S : len);
     const int limit = causal ? (len < i + 1 ? len : i + 1) : len;      // keys >= limit are masked
     const long row_off = ((long)bh * S + i) * S;
-    bf16x8_t qf[2];
-    load_frags(Q, i, ld, qf);
+    // P as in the forward pass
     f32x4_t acc[ATT_TILES];
-    chunk_products(K, ld, 0, qf, acc, npairs);
-    float mx = -INFINITY;
-#pragma unroll
-    for (int t = 0; t < ATT_TILES; ++t)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int j = 32 * (t >> 1) + jl + 4 * (t & 1) + r;
-        const float sc = ((t >> 1) < npairs && j < limit) ? acc[t][r] * alpha2 : -INFINITY;
-        acc[t][r] = sc;
-        mx = fmaxf(mx, sc);
-      }
-    mx = xgroup_max(mx);
-    const float ref = mx == -INFINITY ? 0.f : mx;         // row without admissible keys: every term is 2^-inf = 0
-    float sum = 0.f;
-#pragma unroll
-    for (int t = 0; t < ATT_TILES; ++t)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        acc[t][r] = exp2_hw(acc[t][r] - ref);
-        sum += acc[t][r];
-      }
-    sum = xgroup_sum(sum);
-    const float inv = sum > 0.f ? 1.0f / sum : 0.f;
+    tile_products(kt, qf, acc, npairs);
+    const float inv = row_softmax(acc, npairs, limit, alpha2);
+    // dP~ = dC V^T
+    f32x4_t dacc[ATT_TILES];
+    tile_products(vt, gf, dacc, npairs);
+    float dot = 0.f;
 #pragma unroll
     for (int u = 0; u < ATT_PAIRS; ++u) {
       pdf[u] = make_uint4(0, 0, 0, 0);
       if (u < npairs) {
-        float p[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) p[e] = acc[2 * u + (e >> 2)][e & 3] * inv;
-        const int j = 32 * u + jl;
-        store8_bf16(prob + row_off + j, p);
+        float mult[8], pd[8];
         if (drop.enabled) {
-          float mult[8];
-          drop_mult8(drop, (uint64_t)(row_off + j), mult);
+          drop_mult8(drop, (uint64_t)(row_off + 32 * u + jl), mult);
+        } else {
 #pragma unroll
-          for (int e = 0; e < 8; ++e) p[e] *= mult[e];
+          for (int e = 0; e < 8; ++e) mult[e] = 1.f;
         }
-        pdf[u] = pack8_bf16(p);
-        *reinterpret_cast<uint4*>(prob_d + row_off + j) = pdf[u];
-      }
-    }
-  }
-  __syncthreads();                                        // V tile complete
-  if (active) head_product_store(vt, pdf, npairs, ctx + ((long)b * S + i) * H + h * 64);
-}
-
-__global__ __launch_bounds__(256) void attn_bwd_fused_kernel(const bf16_t* __restrict__ dc, const bf16_t* __restrict__ qkv,
-                                                             const bf16_t* __restrict__ prob,
-                                                             const bf16_t* __restrict__ prob_d, bf16_t* __restrict__ ds,
-                                                             bf16_t* __restrict__ dq, int S, int H, int heads,
-                                                             float drop_scale, float alpha) {
-  __shared__ __attribute__((aligned(16))) char kt[ATT_KC * HT_PITCH];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int bh = blockIdx.y, b = bh / heads, h = bh % heads;
-  const long ldv = 3L * H;
-  const bf16_t* Kp = qkv + ((long)b * S) * ldv + H + h * 64;
-  stage_head_tile(Kp, ldv, S, kt);                       // K of this head; read after the barrier below
-  const int i0 = (blockIdx.x * 4 + wave) * ATT_ROWS;
-  const bool active = i0 < S;
-  const int npairs = S / 32;
-  const int i = i0 + (lane & 15);
-  uint4 dsf[ATT_PAIRS];
-  if (active) {
-    const bf16_t* DC = dc + ((long)b * S) * H + h * 64;
-    const bf16_t* V = qkv + ((long)b * S) * ldv + 2 * H + h * 64;
-    const int jl = 8 * (lane >> 4);
-    const long row_off = ((long)bh * S + i) * S;
-    bf16x8_t gf[2];
-    load_frags(DC, i, H, gf);
-    uint4 pr[ATT_PAIRS], pdr[ATT_PAIRS];
 #pragma unroll
-    for (int u = 0; u < ATT_PAIRS; ++u) {
-      const long o = row_off + (u < npairs ? 32 * u : 0) + jl;
-      pr[u] = load8_raw(prob + o);
-      pdr[u] = load8_raw(prob_d + o);
-    }
-    f32x4_t acc[ATT_TILES];
-    chunk_products(V, ldv, 0, gf, acc, npairs);
-    float dot = 0.f;
-#pragma unroll
-    for (int u = 0; u < ATT_PAIRS; ++u) {
-      float p[8], pd[8];
-      unpack8_bf16(pr[u], p);
-      unpack8_bf16(pdr[u], pd);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        // dropout adjoint of dP~: an element was dropped iff P != 0 but P~ == 0
-        const float dp = ((pd[e] != 0.f) || (p[e] == 0.f)) ? acc[2 * u + (e >> 2)][e & 3] * drop_scale : 0.f;
-        const float a = u < npairs ? p[e] * dp : 0.f;
-        acc[2 * u + (e >> 2)][e & 3] = a;
-        dot += a;
+        for (int e = 0; e < 8; ++e) {
+          const float pe = acc[2 * u + (e >> 2)][e & 3] * inv;
+          acc[2 * u + (e >> 2)][e & 3] = pe;
+          pd[e] = pe * mult[e];
+          const float a = pe * (dacc[2 * u + (e >> 2)][e & 3] * mult[e]);   // P (.) dP, dropout adjoint applied
+          dacc[2 * u + (e >> 2)][e & 3] = a;
+          dot += a;
+        }
+        pdf[u] = pack8_bf16(pd);
       }
     }
     dot = xgroup_sum(dot);
@@ -495,17 +610,26 @@ __global__ __launch_bounds__(256) void attn_bwd_fused_kernel(const bf16_t* __res
     for (int u = 0; u < ATT_PAIRS; ++u) {
       dsf[u] = make_uint4(0, 0, 0, 0);
       if (u < npairs) {
-        float p[8], o[8];
-        unpack8_bf16(pr[u], p);
+        float o[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = alpha * (acc[2 * u + (e >> 2)][e & 3] - p[e] * dot);
+        for (int e = 0; e < 8; ++e) o[e] = alpha * (dacc[2 * u + (e >> 2)][e & 3] - acc[2 * u + (e >> 2)][e & 3] * dot);
         dsf[u] = pack8_bf16(o);
-        *reinterpret_cast<uint4*>(ds + row_off + 32 * u + jl) = dsf[u];
       }
     }
   }
-  __syncthreads();                                        // K tile complete
-  if (active) head_product_store(kt, dsf, npairs, dq + ((long)b * S + i) * ldv + h * 64);
+  __syncthreads();                                        // every wave is done with the V tile
+  if (active) sq_tile_write(sq, i, pdf, npairs);
+  __syncthreads();                                        // P~ tile complete
+  if (active) {
+    head_product_store(kt, dsf, npairs, out_row);                     // dQ = ds . K
+    key_product_store(sq, xt, npairs, wave, out_row + 2 * H);         // dV = P~^T . dC
+  }
+  __syncthreads();                                        // every wave is done with the P~ and dC tiles
+  if (active) sq_tile_write(sq, i, dsf, npairs);
+  hd_tile_load(Q, ld, S, xt);
+  hd_tile_wait();
+  __syncthreads();                                        // ds and Q tiles complete
+  if (active) key_product_store(sq, xt, npairs, wave, out_row + H);   // dK = ds^T . Q
 }
 
 // ----------------------------------------------------------------- launch --
@@ -535,26 +659,31 @@ bool attn_fused_supported(const raf_layer_desc& d) {
   return d.precision == RAF_BF16_AMP && d.hidden / d.heads == 64 && d.seq % 32 == 0 && d.seq <= ATT_KC;
 }
 
-raf_status launch_attn_fwd_fused(const raf_layer_desc& d, const void* qkv, const int32_t* lens, void* prob, void* prob_d,
-                                 void* ctx, uint64_t step, hipStream_t st) {
-  if (!qkv || !prob || !prob_d || !ctx) return RAF_EINVAL;
+raf_status launch_attn_fwd_fused(const raf_layer_desc& d, const void* qkv, const int32_t* lens, void* ctx, uint64_t step,
+                                 hipStream_t st) {
+  if (!qkv || !ctx) return RAF_EINVAL;
   if (!attn_fused_supported(d)) return RAF_ENOTSUP;
   const DropSite drop = make_drop_site(d, 1, step);
-  dim3 grid((d.seq + 4 * ATT_ROWS - 1) / (4 * ATT_ROWS), d.batch * d.heads);
-  hipLaunchKernelGGL(attn_fwd_fused_kernel, grid, dim3(256), 0, st, (const bf16_t*)qkv, lens, (bf16_t*)prob,
-                     (bf16_t*)prob_d, (bf16_t*)ctx, d.seq, d.hidden, d.heads, d.causal, 0.125f * 1.44269504088896341f,
-                     drop);
+  hipLaunchKernelGGL(attn_fwd_fused_kernel, dim3(d.batch * d.heads), dim3(512), 0, st, (const bf16_t*)qkv, lens,
+                     (bf16_t*)ctx, d.seq, d.hidden, d.heads, d.causal, 0.125f * 1.44269504088896341f, drop);
   return check_launch();
 }
 
-raf_status launch_attn_bwd_fused(const raf_layer_desc& d, const void* dc, const void* qkv, const void* prob,
-                                 const void* prob_d, void* ds, void* dqkv, hipStream_t st) {
-  if (!dc || !qkv || !prob || !prob_d || !ds || !dqkv) return RAF_EINVAL;
+raf_status launch_attn_bwd_full(const raf_layer_desc& d, const void* dc, const void* qkv, const int32_t* lens, void* dqkv,
+                                uint64_t step, hipStream_t st) {
+  if (!dc || !qkv || !dqkv) return RAF_EINVAL;
   if (!attn_fused_supported(d)) return RAF_ENOTSUP;
-  dim3 grid((d.seq + 4 * ATT_ROWS - 1) / (4 * ATT_ROWS), d.batch * d.heads);
-  hipLaunchKernelGGL(attn_bwd_fused_kernel, grid, dim3(256), 0, st, (const bf16_t*)dc, (const bf16_t*)qkv,
-                     (const bf16_t*)prob, (const bf16_t*)prob_d, (bf16_t*)ds, (bf16_t*)dqkv, d.seq, d.hidden, d.heads,
-                     (float)(1.0 / (1.0 - d.dropout_p)), 0.125f);
+  static bool attr_done = false;
+  if (!attr_done) {
+    if (hipFuncSetAttribute((const void*)attn_bwd_full_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            ATT_BWD_LDS) != hipSuccess)
+      return check_launch();
+    attr_done = true;
+  }
+  const DropSite drop = make_drop_site(d, 1, step);
+  hipLaunchKernelGGL(attn_bwd_full_kernel, dim3(d.batch * d.heads), dim3(512), ATT_BWD_LDS, st, (const bf16_t*)dc,
+                     (const bf16_t*)qkv, lens, (bf16_t*)dqkv, d.seq, d.hidden, d.heads, d.causal,
+                     0.125f * 1.44269504088896341f, 0.125f, drop);
   return check_launch();
 }
 

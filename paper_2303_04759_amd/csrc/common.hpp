@@ -286,13 +286,14 @@ raf_status launch_attn_prob_fwd(const raf_layer_desc& d, const void* qkv, const 
                                 uint64_t step, hipStream_t st);
 raf_status launch_attn_prob_bwd(const raf_layer_desc& d, const void* dc, const void* qkv, const void* prob,
                                 const void* prob_d, void* ds, hipStream_t st);
-// S <= 128 in bf16 AMP: the same two kernels with the product that follows the probabilities taken in-kernel
-// (forward: ctx = P~ . V written to [T,H]; backward: dQ = ds . K written to the Q columns of dqkv [T,3H])
+// S <= 128 in bf16 AMP: no S x S tensor reaches memory.  Forward: ctx = P~ . V written to [T,H], the probabilities
+// are not stored.  Backward: P and the dropout mask are recomputed from qkv, the same lens and the same step; dQ, dK
+// and dV are written to dqkv [T,3H].
 bool attn_fused_supported(const raf_layer_desc& d);
-raf_status launch_attn_fwd_fused(const raf_layer_desc& d, const void* qkv, const int32_t* lens, void* prob, void* prob_d,
-                                 void* ctx, uint64_t step, hipStream_t st);
-raf_status launch_attn_bwd_fused(const raf_layer_desc& d, const void* dc, const void* qkv, const void* prob,
-                                 const void* prob_d, void* ds, void* dqkv, hipStream_t st);
+raf_status launch_attn_fwd_fused(const raf_layer_desc& d, const void* qkv, const int32_t* lens, void* ctx, uint64_t step,
+                                 hipStream_t st);
+raf_status launch_attn_bwd_full(const raf_layer_desc& d, const void* dc, const void* qkv, const int32_t* lens, void* dqkv,
+                                uint64_t step, hipStream_t st);
 raf_status launch_ln_fwd(const raf_layer_desc& d, int site, int64_t rows, const void* a, const void* res,
                          const float* gamma, const float* beta, void* out, void* z_out, float* mu, float* rstd,
                          uint64_t step, hipStream_t st);

@@ -239,7 +239,7 @@ __global__ __launch_bounds__(LN_BWD_THREADS) void ln_bwd_kernel(const T* __restr
   }
 
   for (long row = group; row < nrows; row += ngroups) {
-    float g[NV][8], xh[NV][8];
+    float g[NV][8], xh[NV][8], res[NV][8];   // res: requested with the other operands, used after the row sums
     float s1 = 0.f, s2 = 0.f;
     float mean = 0.f, rs = 0.f;
     if (HAS_LN) {
@@ -252,6 +252,7 @@ __global__ __launch_bounds__(LN_BWD_THREADS) void ln_bwd_kernel(const T* __restr
       if (vec < nvec) {
         const long off = row * H + vec * 8;
         Vec8<T>::load(dout + off, g[t]);
+        if (dres) Vec8<T>::load(dres + off, res[t]);
         if (dout2) {
           float g2[8];
           Vec8<T>::load(dout2 + off, g2);
@@ -295,10 +296,8 @@ __global__ __launch_bounds__(LN_BWD_THREADS) void ln_bwd_kernel(const T* __restr
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[e] = HAS_LN ? rs * (g[t][e] - s1 - xh[t][e] * s2) : g[t][e];
         if (dres) {
-          float r[8];
-          Vec8<T>::load(dres + off, r);
 #pragma unroll
-          for (int e = 0; e < 8; ++e) o[e] += r[e];
+          for (int e = 0; e < 8; ++e) o[e] += res[t][e];
         }
         if (dz) Vec8<T>::store(dz + off, o);
         if (da) {

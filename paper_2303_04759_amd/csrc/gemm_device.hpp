@@ -313,6 +313,39 @@ __device__ __forceinline__ void epilogue_tile16_staged(const GemmDev& g, bf16_t*
   });
 }
 
+// Float outputs of the 32x32 layout without elementwise epilogue (weight gradients), one 32x32 block per trip
+// through a wave-private LDS buffer of epilogue_stage32_bytes: a direct store instruction writes 32-byte pieces of
+// 32 rows, the staged one whole 128-byte rows.
+constexpr int epilogue_stage32_bytes = 32 * (128 + 16);
+__device__ __forceinline__ bool epilogue_can_stage32(const GemmDev& g) {
+  return g.epilogue == EPI_NONE && ((g.ldc | (long)g.N) & 3) == 0 && ((unsigned long long)g.c & 15) == 0;
+}
+template <int TM, int TN>
+__device__ __forceinline__ void epilogue_tile32_staged(const GemmDev& g, float* __restrict__ C,
+                                                       f32x16_t (&acc)[TM][TN], int row0, int col0, char* stg) {
+  constexpr int P = 128 + 16;
+  const int lane = threadIdx.x & 63;
+  const int wr = lane & 31, wh = lane >> 5;     // accumulator layout: row, which 4 of every 8 columns
+  const int rr = lane >> 3, rc = lane & 7;      // copy-out: row within 8, 16-byte piece of the row
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        *reinterpret_cast<float4*>(stg + wr * P + q * 32 + wh * 16) =
+            make_float4(acc[i][j][4 * q] * g.alpha, acc[i][j][4 * q + 1] * g.alpha, acc[i][j][4 * q + 2] * g.alpha,
+                        acc[i][j][4 * q + 3] * g.alpha);
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const int r = it * 8 + rr;
+        const int row = row0 + i * 32 + r, col = col0 + j * 32 + rc * 4;
+        if (row < g.M && col < g.N)
+          *reinterpret_cast<float4*>(C + (long)row * g.ldc + col) = *reinterpret_cast<const float4*>(stg + r * P + rc * 16);
+      }
+    }
+}
+
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x8_t __attribute__((ext_vector_type(8)));
 

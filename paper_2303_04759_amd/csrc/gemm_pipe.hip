@@ -364,6 +364,15 @@ __global__ __launch_bounds__(64 * (WGM * WGN + NP)) void gemm_bf16_spec_kernel(G
   TC* __restrict__ C = (TC*)g.c;
   bf16_t* __restrict__ AUX = (bf16_t*)g.aux;
   // register r of lane l holds output row (l & 31), column 8*(r/4) + 4*(l/32) + r%4 of its 32x32 block
+  if constexpr (sizeof(TC) == 4) {
+    // every consumer has passed the last barrier, so the stage after the last one is read by nobody and no load
+    // is in flight to it: each wave stages its blocks in a slice of it
+    static_assert(NC * epilogue_stage32_bytes <= STAGE_BYTES, "staging exceeds a ring stage");
+    if (epilogue_can_stage32(g)) {
+      epilogue_tile32_staged<TM, TN>(g, C, acc, m0 + wm, n0 + wn, lds + stage * STAGE_BYTES + wave * epilogue_stage32_bytes);
+      return;
+    }
+  }
   epilogue_tile32<TC, TM, TN>(g, C, AUX, acc, m0 + wm, n0 + wn);
 }
 

@@ -226,8 +226,9 @@ extern "C" raf_status raf_layer_fwd(const raf_layer_desc* desc, const raf_layer_
   RAF_TRY(gemm(prec, st, T, 3 * H, H, attn_in, H, 1, w->w_qkv, H, 1, qkv, 3 * H, 0, EPI_BIAS, (const float*)w->b_qkv));
   const bool attn_fused = attn_fused_supported(d);   // S <= 128: F4 is taken inside the probability kernel
   if (attn_fused) {
-    // F2+F3+F4 fused: scores, mask, softmax, dropout site 1, context
-    RAF_TRY(launch_attn_fwd_fused(d, qkv, seq_lens, prob, prob_d, c, step, st));
+    // F2+F3+F4 fused: scores, mask, softmax, dropout site 1, context; the backward pass recomputes the
+    // probabilities, so they are not stored
+    RAF_TRY(launch_attn_fwd_fused(d, qkv, seq_lens, c, step, st));
   } else if (prec == RAF_BF16_AMP) {
     // F2+F3 fused: scores, mask, softmax, dropout site 1; the score tensor stays in registers
     RAF_TRY(launch_attn_prob_fwd(d, qkv, seq_lens, prob, prob_d, step, st));
@@ -272,7 +273,6 @@ extern "C" raf_status raf_layer_bwd(const raf_layer_desc* desc, const raf_layer_
   RAF_TRY(validate_desc(desc));
   if (!tensors_ok(w) || !tensors_ok(grads) || !x || !dy || !dx || !saved || !scratch) return RAF_EINVAL;
   if (!aligned16(x) || !aligned16(dy) || !aligned16(dx) || !aligned16(saved) || !aligned16(scratch)) return RAF_EINVAL;
-  (void)seq_lens;   // masked probabilities are exactly zero in `saved`; no mask is needed again
   const raf_layer_desc& d = *desc;
   const Plan p = make_plan(d);
   hipStream_t st = (hipStream_t)hip_stream;
@@ -355,10 +355,10 @@ extern "C" raf_status raf_layer_bwd(const raf_layer_desc* desc, const raf_layer_
   // B4: c = prob_d V  ->  dV = prob_d^T dc (launched below, together with dK) ; dprob_d = dc V^T
   const GemmArgs dv_args = heads_args(p, S, 64, S, HeadView{prob_d, S, 0, true}, HeadView{dc, H, 0, false},
                                       at(dqkv, (size_t)2 * H * e), 3 * H, false, 1.0f);
-  const bool attn_fused = attn_fused_supported(d);   // S <= 128: dQ is taken inside the probability kernel
+  const bool attn_fused = attn_fused_supported(d);   // S <= 128: B4, B3 and B2 in one kernel
   if (attn_fused) {
-    // B4b+B3 and the dQ half of B2 fused
-    RAF_TRY(launch_attn_bwd_fused(d, dc, qkv, prob, prob_d, ds, dqkv, st));
+    // probabilities and dropout mask recomputed from qkv, seq_lens and the step counter; dQ, dK, dV written to dqkv
+    RAF_TRY(launch_attn_bwd_full(d, dc, qkv, seq_lens, dqkv, step, st));
   } else if (prec == RAF_BF16_AMP) {
     // B4b+B3 fused: dprob_d stays in registers; dropout and softmax adjoints with the 1/8 folded in
     RAF_TRY(launch_attn_prob_bwd(d, dc, qkv, prob, prob_d, ds, st));
@@ -373,7 +373,8 @@ extern "C" raf_status raf_layer_bwd(const raf_layer_desc* desc, const raf_layer_
     RAF_TRY(gemm_heads(p, prec, st, S, 64, S, HeadView{ds, S, 1, true},
                        HeadView{at(qkv, (size_t)H * e), 3 * H, 0, false}, dqkv, 3 * H, false, 1.0f));
   // dK and dV have the same shape and layout (A^T B over the query index): one launch
-  RAF_TRY(launch_gemm_pair(prec, heads_args(p, S, 64, S, HeadView{ds, S, 0, true}, HeadView{qkv, 3 * H, 0, false},
+  if (!attn_fused)
+    RAF_TRY(launch_gemm_pair(prec, heads_args(p, S, 64, S, HeadView{ds, S, 0, true}, HeadView{qkv, 3 * H, 0, false},
                                             at(dqkv, (size_t)H * e), 3 * H, false, 1.0f),
                            dv_args, st));
   // B1: qkv = attn_in Wqkv^T + bqkv
