@@ -59,9 +59,10 @@ typedef enum { RAF_F32 = 0, RAF_BF16_AMP = 1 } raf_precision;
  *   pre-LN  (pre_ln=1):  h  = x + drop2(attn(LN1(x)));  y = h + drop3(ffn(LN2(h)))
  * attn = out_proj(merge_heads(drop1(softmax(mask(Q K^T / 8))) V)), ffn = W2 gelu(W1 . + b1) + b2.
  * Dropout sites: 1 = attention probabilities [B,heads,S,S], 2 = attention
- * output [T,H], 3 = ffn output [T,H]; element idx of a site is kept iff word
- * (idx & 3) of Philox4x32-10(counter = (idx>>2, step>>32, site | layer_id<<8,
- * step & 0xffffffff), key = (seed lo, seed hi)) is >= floor(dropout_p * 2^32);
+ * output [T,H], 3 = ffn output [T,H]; element idx of a site is kept iff the
+ * 16-bit half (idx & 1: 0 = low, 1 = high) of word ((idx>>1) & 3) of
+ * Philox4x32-10(counter = (idx>>3, step>>32, site | layer_id<<8,
+ * step & 0xffffffff), key = (seed lo, seed hi)) is >= floor(dropout_p * 2^16);
  * kept values are scaled by 1/(1-dropout_p). */
 typedef struct {
   int32_t batch, seq, hidden, heads, ffn;
@@ -70,7 +71,7 @@ typedef struct {
   int32_t gelu_tanh; /* 0 = erf GeLU, 1 = tanh approximation                             */
   int32_t precision; /* raf_precision                                                     */
   float ln_eps;      /* added to the biased variance                                      */
-  double dropout_p;  /* [0,1); the keep threshold is floor(dropout_p * 2^32) in double    */
+  double dropout_p;  /* [0,1); the keep threshold is floor(dropout_p * 2^16) in double    */
   uint64_t seed;     /* dropout key                                                       */
   uint32_t layer_id; /* folded into the dropout counter (24 bits used)                    */
   uint32_t reserved; /* must be 0                                                         */

@@ -72,29 +72,32 @@ def philox4x32_10(c0, c1, c2, c3, k0, k1):
 
 
 def dropout_threshold(p):
-    """u32 threshold: element is KEPT iff its 32 random bits are >= threshold,
-    so P(drop) = floor(p * 2**32) / 2**32."""
+    """16-bit threshold: element is KEPT iff its 16 random bits are >= threshold,
+    so P(drop) = floor(p * 2**16) / 2**16."""
     if not (0.0 <= p < 1.0):
         raise ValueError("dropout p must be in [0, 1)")
-    return int(np.floor(float(p) * 4294967296.0))
+    return int(np.floor(float(p) * 65536.0))
 
 
 def dropout_keep(seed, layer_id, site, step, n, p):
     """Boolean keep-mask for n elements (flat index 0..n-1) of one dropout site.
 
-    Element idx uses block counter (idx>>2, step>>32, site | layer_id<<8, step&0xffffffff)
-    under key (seed&0xffffffff, seed>>32) and takes output word idx&3.
+    Element idx uses block counter (idx>>3, step>>32, site | layer_id<<8, step&0xffffffff)
+    under key (seed&0xffffffff, seed>>32) and takes 16 bits of the block: output word
+    (idx>>1)&3, its low half for even idx, its high half for odd idx.  (The generator's
+    cost is per block, so every output bit that the decision can use is used.)
     """
     if p == 0.0:
         return np.ones(n, dtype=bool)
-    if (n + 3) // 4 > 0xFFFFFFFF:
+    if (n + 7) // 8 > 0xFFFFFFFF:
         raise ValueError("site too large for a 32-bit block counter")
     thr = dropout_threshold(p)
-    nblk = (n + 3) // 4
+    nblk = (n + 7) // 8
     blk = np.arange(nblk, dtype=np.uint64)
     r = philox4x32_10(blk, (int(step) >> 32) & 0xFFFFFFFF,
                       (int(site) & 0xFF) | ((int(layer_id) & 0xFFFFFF) << 8),
                       int(step) & 0xFFFFFFFF,
                       int(seed) & 0xFFFFFFFF, (int(seed) >> 32) & 0xFFFFFFFF)
-    words = np.stack(r, axis=1).reshape(-1)[:n]
-    return words >= np.uint32(thr)
+    words = np.stack(r, axis=1)                               # [block][word]
+    halves = np.stack([words & np.uint32(0xFFFF), words >> np.uint32(16)], axis=2)   # [block][word][low, high]
+    return halves.reshape(-1)[:n] >= np.uint32(thr)

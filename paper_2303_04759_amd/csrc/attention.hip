@@ -315,7 +315,7 @@ __global__ __launch_bounds__(256) void attn_prob_bwd_kernel(const bf16_t* __rest
 //   backward: P and the dropout mask are recomputed from Q, K and the counter-based generator, ds is formed in
 //             registers, and dQ = ds . K, dV = P~^T . dC and dK = ds^T . Q follow, the last two through LDS copies
 //             of P~ and ds (their contraction runs over the query index, which is spread over the waves).
-// One workgroup of 8 waves per (batch, head); wave w owns query rows 16w .. 16w+15.  The [S][64] operands of the
+// A wave owns 16 query rows; the backward pass runs one workgroup of 8 waves per (batch, head).  The [S][64] operands of the
 // head (K, V, dC, Q) are brought into LDS once per workgroup by direct-to-LDS loads: loads into registers sustain
 // only about 16 bytes/clock/CU, and with every wave fetching its own K and V fragments from global memory that rate,
 // not the arithmetic, set the time of these kernels.  Fragments whose contraction index is the row index of the
@@ -443,7 +443,9 @@ __device__ __forceinline__ float row_softmax(f32x4_t (&acc)[ATT_TILES], int npai
   return sum > 0.f ? 1.0f / sum : 0.f;
 }
 
-__global__ __launch_bounds__(512) void attn_fwd_fused_kernel(const bf16_t* __restrict__ qkv, const int32_t* __restrict__ lens,
+// Forward: a workgroup of 4 waves takes 64 query rows of one head (two workgroups per head at S = 128, so that the
+// 256 CUs get three workgroups each instead of one and a half); each stages K and V for itself.
+__global__ __launch_bounds__(256) void attn_fwd_fused_kernel(const bf16_t* __restrict__ qkv, const int32_t* __restrict__ lens,
                                                              bf16_t* __restrict__ ctx, int S, int H, int heads, int causal,
                                                              float alpha2, DropSite drop) {
   __shared__ __attribute__((aligned(1024))) char kt[HD_TILE];
@@ -454,7 +456,7 @@ __global__ __launch_bounds__(512) void attn_fwd_fused_kernel(const bf16_t* __res
   const bf16_t* Q = qkv + ((long)b * S) * ld + h * 64;
   hd_tile_load(Q + H, ld, S, kt);
   hd_tile_load(Q + 2 * H, ld, S, vt);
-  const int i0 = wave * ATT_ROWS;                        // first query row of this wave
+  const int i0 = ((int)blockIdx.y * 4 + wave) * ATT_ROWS;   // first query row of this wave
   const bool active = i0 < S;                            // S is a multiple of 32: a wave is all in or all out
   const int npairs = S / 32;
   const int i = i0 + (lane & 15);                        // this lane's query row
@@ -664,7 +666,7 @@ raf_status launch_attn_fwd_fused(const raf_layer_desc& d, const void* qkv, const
   if (!qkv || !ctx) return RAF_EINVAL;
   if (!attn_fused_supported(d)) return RAF_ENOTSUP;
   const DropSite drop = make_drop_site(d, 1, step);
-  hipLaunchKernelGGL(attn_fwd_fused_kernel, dim3(d.batch * d.heads), dim3(512), 0, st, (const bf16_t*)qkv, lens,
+  hipLaunchKernelGGL(attn_fwd_fused_kernel, dim3(d.batch * d.heads, (d.seq + 63) / 64), dim3(256), 0, st, (const bf16_t*)qkv, lens,
                      (bf16_t*)ctx, d.seq, d.hidden, d.heads, d.causal, 0.125f * 1.44269504088896341f, drop);
   return check_launch();
 }

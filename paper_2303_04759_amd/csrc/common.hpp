@@ -107,7 +107,7 @@ __device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint3
 struct DropSite {
   uint32_t k0, k1;      // seed lo, hi
   uint32_t c1, c2, c3;  // step hi, site | layer<<8, step lo
-  uint32_t thr;         // keep iff word >= thr
+  uint32_t thr;         // keep iff the element's 16 random bits are >= thr
   float scale;          // 1/(1-p)
   int enabled;          // 0: p == 0 or no dropout at this call
 };
@@ -119,7 +119,7 @@ inline DropSite make_drop_site(const raf_layer_desc& d, int site, uint64_t step)
   s.c1 = (uint32_t)(step >> 32);
   s.c2 = ((uint32_t)site & 0xffu) | ((d.layer_id & 0xffffffu) << 8);
   s.c3 = (uint32_t)(step & 0xffffffffu);
-  const double t = d.dropout_p * 4294967296.0;
+  const double t = d.dropout_p * 65536.0;
   s.thr = (uint32_t)t;  // floor for t >= 0
   s.scale = (float)(1.0 / (1.0 - d.dropout_p));
   s.enabled = (site != 0 && d.dropout_p > 0.0) ? 1 : 0;
@@ -127,15 +127,15 @@ inline DropSite make_drop_site(const raf_layer_desc& d, int site, uint64_t step)
 }
 
 // keep-multipliers (0 or scale) for 8 consecutive elements starting at flat
-// index idx8 (a multiple of 8): two Philox blocks.
+// index idx8 (a multiple of 8): one Philox block, 16 bits per element (the
+// 32x32 multiplies of the generator are the main arithmetic cost of every
+// kernel with a dropout site, so no output bit is thrown away beyond that).
 __device__ __forceinline__ void drop_mult8(const DropSite& s, uint64_t idx8, float (&mult)[8]) {
-  const uint32_t blk = (uint32_t)(idx8 >> 2);
-  const Philox4 a = philox4x32_10(blk, s.c1, s.c2, s.c3, s.k0, s.k1);
-  const Philox4 b = philox4x32_10(blk + 1, s.c1, s.c2, s.c3, s.k0, s.k1);
-  mult[0] = a.x >= s.thr ? s.scale : 0.f; mult[1] = a.y >= s.thr ? s.scale : 0.f;
-  mult[2] = a.z >= s.thr ? s.scale : 0.f; mult[3] = a.w >= s.thr ? s.scale : 0.f;
-  mult[4] = b.x >= s.thr ? s.scale : 0.f; mult[5] = b.y >= s.thr ? s.scale : 0.f;
-  mult[6] = b.z >= s.thr ? s.scale : 0.f; mult[7] = b.w >= s.thr ? s.scale : 0.f;
+  const Philox4 a = philox4x32_10((uint32_t)(idx8 >> 3), s.c1, s.c2, s.c3, s.k0, s.k1);
+  mult[0] = (a.x & 0xffffu) >= s.thr ? s.scale : 0.f; mult[1] = (a.x >> 16) >= s.thr ? s.scale : 0.f;
+  mult[2] = (a.y & 0xffffu) >= s.thr ? s.scale : 0.f; mult[3] = (a.y >> 16) >= s.thr ? s.scale : 0.f;
+  mult[4] = (a.z & 0xffffu) >= s.thr ? s.scale : 0.f; mult[5] = (a.z >> 16) >= s.thr ? s.scale : 0.f;
+  mult[6] = (a.w & 0xffffu) >= s.thr ? s.scale : 0.f; mult[7] = (a.w >> 16) >= s.thr ? s.scale : 0.f;
 }
 
 // ------------------------------------------------------------- reductions --

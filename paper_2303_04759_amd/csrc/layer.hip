@@ -61,7 +61,9 @@ static Plan make_plan(const raf_layer_desc& d) {
   p.B = d.batch; p.S = d.seq; p.H = d.hidden; p.F = d.ffn; p.NH = d.heads;
   p.T = p.B * p.S;
   p.PS = p.B * p.NH * p.S * p.S;
-  const size_t TH = (size_t)p.T * p.H * p.e, TF = (size_t)p.T * p.F * p.e, PSb = (size_t)p.PS * p.e;
+  // the fused attention path (S <= 128, bf16) keeps every S x S tensor on chip: no room is reserved for them
+  const size_t TH = (size_t)p.T * p.H * p.e, TF = (size_t)p.T * p.F * p.e,
+               PSb = attn_fused_supported(d) ? 0 : (size_t)p.PS * p.e;
   size_t o = 0;
   p.qkv = bump(o, 3 * TH);
   p.prob = bump(o, PSb);

@@ -50,23 +50,36 @@ def test_vectorised_4x32_matches_generic():
 
 
 def test_keep_mask_indexing_matches_definition():
-    # element idx uses block idx>>2, word idx&3, with (step_hi, site|layer<<8, step_lo) in the counter
+    # element idx uses block idx>>3, word (idx>>1)&3, half idx&1 (0 = low 16 bits), with
+    # (step_hi, site|layer<<8, step_lo) in the counter
     seed, layer, site, step, p = 0x123456789ABCDEF, 5, 2, (3 << 32) | 17, 0.3
-    n = 23
+    n = 43
     keep = ph.dropout_keep(seed, layer, site, step, n, p)
-    thr = int(np.floor(0.3 * 2**32))
-    for idx in (0, 1, 2, 3, 4, 7, 21, 22):
-        r = ph.philox_generic((idx >> 2, 3, site | (layer << 8), 17),
+    thr = int(np.floor(0.3 * 2**16))
+    for idx in (0, 1, 2, 3, 4, 7, 8, 9, 21, 22, 39, 40, 42):
+        r = ph.philox_generic((idx >> 3, 3, site | (layer << 8), 17),
                               (seed & 0xFFFFFFFF, seed >> 32), 32, ph.PHILOX_M4x32, ph.PHILOX_W32, 10)
-        assert bool(keep[idx]) == (r[idx & 3] >= thr)
+        word = r[(idx >> 1) & 3]
+        bits = (word >> 16) if (idx & 1) else (word & 0xFFFF)
+        assert bool(keep[idx]) == (bits >= thr)
 
 
 def test_threshold_and_p_zero():
-    assert ph.dropout_threshold(0.1) == 429496729
+    assert ph.dropout_threshold(0.1) == 6553
+    assert ph.dropout_threshold(0.5) == 32768
     assert ph.dropout_threshold(0.0) == 0
     assert ph.dropout_keep(1, 0, 1, 0, 1000, 0.0).all()
     with pytest.raises(ValueError):
         ph.dropout_threshold(1.0)
+
+
+def test_halves_of_a_word_are_used_independently():
+    # low and high halves of the same output word decide neighbouring elements: their agreement
+    # rate is that of independent draws
+    n, p = 1 << 20, 0.3
+    a = ph.dropout_keep(7, 0, 3, 5, n, p)
+    indep = (1 - p) ** 2 + p ** 2
+    assert abs((a[0::2] == a[1::2]).mean() - indep) < 5 * np.sqrt(indep * (1 - indep) / (n // 2))
 
 
 def test_keep_fraction_and_decorrelation():
