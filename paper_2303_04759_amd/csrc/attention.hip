@@ -634,6 +634,296 @@ __global__ __launch_bounds__(512) void attn_bwd_full_kernel(const bf16_t* __rest
   if (active) key_product_store(sq, xt, npairs, wave, out_row + H);   // dK = ds^T . Q
 }
 
+// --------------------------------------------- longer rows (S > 128) --
+// The same three products per 128-key block with a running maximum and sum (the rescaling form of the softmax), so
+// that rows of any length keep their probabilities on chip as well.  The forward pass leaves one number per query
+// row, lse = max + log2(sum) in the base-2 units of the scores, from which the backward kernels recompute
+// P = 2^(s - lse) block by block.  The backward pass is two kernels with opposite ownership, each deterministic:
+//   attn_flash_dq_kernel   waves own query rows and walk the key blocks   (dQ; also D = rowsum(dC (.) ctx))
+//   attn_flash_dkv_kernel  waves own key rows and walk the query blocks   (dK, dV)
+// In the second one the score block is formed transposed (own key row, 8 consecutive queries per lane and 32-query
+// group), which is already the operand layout of dV = P~^T dC and dK = ds^T Q: no exchange between waves is needed.
+// Dropout blocks cover 8 consecutive keys of one query, so there each lane generates the block of one (query,
+// key octet) of its 16 x 32 sub-block and the keep bits are exchanged with lane permutes.
+constexpr int FL_QB = 128;   // query rows per workgroup (8 waves x 16)
+
+// keep bits (bit e = element idx8 + e is kept) of one Philox block
+__device__ __forceinline__ uint32_t drop_keep8(const DropSite& s, uint64_t idx8) {
+  const Philox4 a = philox4x32_10((uint32_t)(idx8 >> 3), s.c1, s.c2, s.c3, s.k0, s.k1);
+  uint32_t bits = 0;
+  bits |= ((a.x & 0xffffu) >= s.thr ? 1u : 0u) | ((a.x >> 16) >= s.thr ? 2u : 0u);
+  bits |= ((a.y & 0xffffu) >= s.thr ? 4u : 0u) | ((a.y >> 16) >= s.thr ? 8u : 0u);
+  bits |= ((a.z & 0xffffu) >= s.thr ? 16u : 0u) | ((a.z >> 16) >= s.thr ? 32u : 0u);
+  bits |= ((a.w & 0xffffu) >= s.thr ? 64u : 0u) | ((a.w >> 16) >= s.thr ? 128u : 0u);
+  return bits;
+}
+
+__device__ __forceinline__ float frag_dot(const bf16x8_t (&a)[2], const bf16x8_t (&b)[2]) {
+  float d = 0.f;
+#pragma unroll
+  for (int k = 0; k < 2; ++k)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) d += (float)a[k][e] * (float)b[k][e];
+  return d;
+}
+
+__global__ __launch_bounds__(512) void attn_flash_fwd_kernel(const bf16_t* __restrict__ qkv, const int32_t* __restrict__ lens,
+                                                             bf16_t* __restrict__ ctx, float* __restrict__ lse, int S,
+                                                             int H, int heads, int causal, float alpha2, DropSite drop) {
+  __shared__ __attribute__((aligned(1024))) char kt[HD_TILE];
+  __shared__ __attribute__((aligned(1024))) char vt[HD_TILE];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int bh = blockIdx.y, b = bh / heads, h = bh % heads;
+  const long ld = 3L * H;
+  const bf16_t* Q = qkv + ((long)b * S) * ld + h * 64;
+  const int q0 = (int)blockIdx.x * FL_QB;
+  const int i0 = q0 + wave * ATT_ROWS;
+  const bool active = i0 < S;                            // S is a multiple of 32: a wave is all in or all out
+  const int i = i0 + (lane & 15);                        // this lane's query row
+  const int jl = 8 * (lane >> 4);                        // this lane's first key within a 32-key group
+  int len = lens ? lens[b] : S;
+  len = len < 0 ? 0 : (len > S ? S : len);
+  const int limit = causal ? (len < i + 1 ? len : i + 1) : len;      // keys >= limit are masked
+  const int q_end = q0 + FL_QB < S ? q0 + FL_QB : S;
+  const int kmax = causal ? (len < q_end ? len : q_end) : len;       // no row of the workgroup sees keys beyond
+  const int nkb = (kmax + ATT_KC - 1) / ATT_KC;
+  const long row_off = ((long)bh * S + i) * S;
+  bf16x8_t qf[2];
+  if (active) load_frags(Q, i, ld, qf);
+  float mx = -INFINITY, sum = 0.f;
+  f32x4_t o[4];
+#pragma unroll
+  for (int nb = 0; nb < 4; ++nb) o[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  for (int jb = 0; jb < nkb; ++jb) {
+    const int key0 = jb * ATT_KC;
+    const int rows = S - key0 < ATT_KC ? S - key0 : ATT_KC;
+    const int npairs = rows / 32;
+    hd_tile_load(Q + H + (long)key0 * ld, ld, rows, kt);
+    hd_tile_load(Q + 2 * H + (long)key0 * ld, ld, rows, vt);
+    hd_tile_wait();
+    __syncthreads();                                      // K and V blocks complete
+    if (active) {
+      f32x4_t acc[ATT_TILES];
+      tile_products(kt, qf, acc, npairs);
+      float bm = -INFINITY;
+#pragma unroll
+      for (int t = 0; t < ATT_TILES; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int j = key0 + 32 * (t >> 1) + jl + 4 * (t & 1) + r;
+          const float sc = ((t >> 1) < npairs && j < limit) ? acc[t][r] * alpha2 : -INFINITY;
+          acc[t][r] = sc;
+          bm = fmaxf(bm, sc);
+        }
+      bm = xgroup_max(bm);
+      const float nm = fmaxf(mx, bm);
+      const float ref = nm == -INFINITY ? 0.f : nm;       // nothing admissible so far: every term is 2^-inf = 0
+      const float corr = exp2_hw(mx - ref);
+      float bs = 0.f;
+#pragma unroll
+      for (int t = 0; t < ATT_TILES; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          acc[t][r] = exp2_hw(acc[t][r] - ref);
+          bs += acc[t][r];
+        }
+      bs = xgroup_sum(bs);
+      sum = sum * corr + bs;
+      mx = nm;
+#pragma unroll
+      for (int nb = 0; nb < 4; ++nb) o[nb] = o[nb] * corr;
+#pragma unroll
+      for (int u = 0; u < ATT_PAIRS; ++u)
+        if (u < npairs) {
+          float p[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) p[e] = acc[2 * u + (e >> 2)][e & 3];
+          if (drop.enabled) {
+            float mult[8];
+            drop_mult8(drop, (uint64_t)(row_off + key0 + 32 * u + jl), mult);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) p[e] *= mult[e];
+          }
+          const bf16x8_t pf = __builtin_bit_cast(bf16x8_t, pack8_bf16(p));
+#pragma unroll
+          for (int nb = 0; nb < 4; ++nb)
+            o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hd_frag_t(vt, u, nb), pf, o[nb], 0, 0, 0);
+        }
+    }
+    __syncthreads();                                      // every wave is done with the blocks
+  }
+  if (!active) return;
+  const float inv = sum > 0.f ? 1.0f / sum : 0.f;         // a row without admissible keys gives zeros
+#pragma unroll
+  for (int nb = 0; nb < 4; ++nb) o[nb] = o[nb] * inv;
+  store_head_row(ctx + ((long)b * S + i) * H + h * 64, o);
+  if (lane < 16) lse[(long)bh * S + i] = sum > 0.f ? mx + __log2f(sum) : INFINITY;
+}
+
+// dQ = ds . K over all key blocks; also writes D = rowsum(dC (.) ctx) for the dK/dV kernel
+__global__ __launch_bounds__(512) void attn_flash_dq_kernel(const bf16_t* __restrict__ dc, const bf16_t* __restrict__ qkv,
+                                                            const bf16_t* __restrict__ ctx, const float* __restrict__ lse,
+                                                            const int32_t* __restrict__ lens, bf16_t* __restrict__ dqkv,
+                                                            float* __restrict__ dvec, int S, int H, int heads, int causal,
+                                                            float alpha2, float alpha, DropSite drop) {
+  __shared__ __attribute__((aligned(1024))) char kt[HD_TILE];
+  __shared__ __attribute__((aligned(1024))) char vt[HD_TILE];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int bh = blockIdx.y, b = bh / heads, h = bh % heads;
+  const long ld = 3L * H;
+  const bf16_t* Q = qkv + ((long)b * S) * ld + h * 64;
+  const int q0 = (int)blockIdx.x * FL_QB;
+  const int i0 = q0 + wave * ATT_ROWS;
+  const bool active = i0 < S;
+  const int i = i0 + (lane & 15);
+  const int jl = 8 * (lane >> 4);
+  int len = lens ? lens[b] : S;
+  len = len < 0 ? 0 : (len > S ? S : len);
+  const int limit = causal ? (len < i + 1 ? len : i + 1) : len;
+  const int q_end = q0 + FL_QB < S ? q0 + FL_QB : S;
+  const int kmax = causal ? (len < q_end ? len : q_end) : len;
+  const int nkb = (kmax + ATT_KC - 1) / ATT_KC;
+  const long row_off = ((long)bh * S + i) * S;
+  bf16x8_t qf[2], gf[2];
+  float L = INFINITY, D = 0.f;
+  if (active) {
+    bf16x8_t of[2];
+    load_frags(Q, i, ld, qf);
+    load_frags(dc + ((long)b * S) * H + h * 64, i, H, gf);
+    load_frags(ctx + ((long)b * S) * H + h * 64, i, H, of);
+    L = lse[(long)bh * S + i];
+    D = xgroup_sum(frag_dot(gf, of));
+    if (lane < 16) dvec[(long)bh * S + i] = D;
+  }
+  f32x4_t dq[4];
+#pragma unroll
+  for (int nb = 0; nb < 4; ++nb) dq[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  for (int jb = 0; jb < nkb; ++jb) {
+    const int key0 = jb * ATT_KC;
+    const int rows = S - key0 < ATT_KC ? S - key0 : ATT_KC;
+    const int npairs = rows / 32;
+    hd_tile_load(Q + H + (long)key0 * ld, ld, rows, kt);
+    hd_tile_load(Q + 2 * H + (long)key0 * ld, ld, rows, vt);
+    hd_tile_wait();
+    __syncthreads();
+    if (active) {
+      f32x4_t acc[ATT_TILES], dacc[ATT_TILES];
+      tile_products(kt, qf, acc, npairs);
+      tile_products(vt, gf, dacc, npairs);
+#pragma unroll
+      for (int u = 0; u < ATT_PAIRS; ++u)
+        if (u < npairs) {
+          float mult[8], dsv[8];
+          if (drop.enabled) {
+            drop_mult8(drop, (uint64_t)(row_off + key0 + 32 * u + jl), mult);
+          } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) mult[e] = 1.f;
+          }
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const int j = key0 + 32 * u + jl + e;
+            const float pe = j < limit ? exp2_hw(acc[2 * u + (e >> 2)][e & 3] * alpha2 - L) : 0.f;
+            dsv[e] = alpha * pe * (dacc[2 * u + (e >> 2)][e & 3] * mult[e] - D);
+          }
+          const bf16x8_t df = __builtin_bit_cast(bf16x8_t, pack8_bf16(dsv));
+#pragma unroll
+          for (int nb = 0; nb < 4; ++nb)
+            dq[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hd_frag_t(kt, u, nb), df, dq[nb], 0, 0, 0);
+        }
+    }
+    __syncthreads();
+  }
+  if (active) store_head_row(dqkv + ((long)b * S + i) * ld + h * 64, dq);
+}
+
+// dV = P~^T dC and dK = ds^T Q for the 128 keys of one block, over all query blocks
+__global__ __launch_bounds__(512) void attn_flash_dkv_kernel(const bf16_t* __restrict__ dc, const bf16_t* __restrict__ qkv,
+                                                             const float* __restrict__ lse, const float* __restrict__ dvec,
+                                                             const int32_t* __restrict__ lens, bf16_t* __restrict__ dqkv,
+                                                             int S, int H, int heads, int causal, float alpha2,
+                                                             float alpha, DropSite drop) {
+  __shared__ __attribute__((aligned(1024))) char qt[HD_TILE];
+  __shared__ __attribute__((aligned(1024))) char ct[HD_TILE];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int bh = blockIdx.y, b = bh / heads, h = bh % heads;
+  const long ld = 3L * H;
+  const bf16_t* Q = qkv + ((long)b * S) * ld + h * 64;
+  const bf16_t* DC = dc + ((long)b * S) * H + h * 64;
+  const int jb = blockIdx.x;
+  const int kbase = jb * ATT_KC + wave * ATT_ROWS;       // first key row of this wave
+  const bool active = kbase < S;
+  const int m = lane & 15, g = lane >> 4;
+  const int k = kbase + m;                               // this lane's key row
+  int len = lens ? lens[b] : S;
+  len = len < 0 ? 0 : (len > S ? S : len);
+  bf16x8_t kf[2], vf[2];
+  if (active) {
+    load_frags(Q + H, k, ld, kf);
+    load_frags(Q + 2 * H, k, ld, vf);
+  }
+  f32x4_t dv[4], dk[4];
+#pragma unroll
+  for (int nb = 0; nb < 4; ++nb) dv[nb] = dk[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  const int nqb = (S + FL_QB - 1) / FL_QB;
+  // causal: query blocks before this key block see none of its keys; keys beyond every length contribute nothing
+  const int ib0 = causal ? jb : 0;
+  const int ib1 = jb * ATT_KC < len ? nqb : ib0;
+  for (int ib = ib0; ib < ib1; ++ib) {
+    const int q0 = ib * FL_QB;
+    const int rows = S - q0 < FL_QB ? S - q0 : FL_QB;
+    const int npairs = rows / 32;
+    hd_tile_load(Q + (long)q0 * ld, ld, rows, qt);
+    hd_tile_load(DC + (long)q0 * H, H, rows, ct);
+    hd_tile_wait();
+    __syncthreads();                                      // Q and dC blocks complete
+    if (active) {
+      f32x4_t acc[ATT_TILES], dacc[ATT_TILES];
+      tile_products(qt, kf, acc, npairs);                 // own key row x 8 consecutive queries per 32-query group
+      tile_products(ct, vf, dacc, npairs);
+#pragma unroll
+      for (int u = 0; u < ATT_PAIRS; ++u)
+        if (u < npairs) {
+          const int qg = q0 + 32 * u + 8 * g;             // first of this lane's 8 queries in the group
+          float Lv[8], Dv[8];
+          *reinterpret_cast<float4*>(&Lv[0]) = *reinterpret_cast<const float4*>(lse + (long)bh * S + qg);
+          *reinterpret_cast<float4*>(&Lv[4]) = *reinterpret_cast<const float4*>(lse + (long)bh * S + qg + 4);
+          *reinterpret_cast<float4*>(&Dv[0]) = *reinterpret_cast<const float4*>(dvec + (long)bh * S + qg);
+          *reinterpret_cast<float4*>(&Dv[4]) = *reinterpret_cast<const float4*>(dvec + (long)bh * S + qg + 4);
+          // this lane's Philox block: query qg + (m & 7), keys kbase + 8*(m >> 3) .. +7; the lane that needs the bit
+          // of (query qg + e, key k) fetches the block of lane (g, e + 8*(m >> 3)) and takes bit m & 7
+          uint32_t mine = 0xffu;
+          if (drop.enabled)
+            mine = drop_keep8(drop, (uint64_t)(((long)bh * S + qg + (m & 7)) * S + kbase + 8 * (m >> 3)));
+          float pd[8], dsv[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const uint32_t theirs = (uint32_t)__shfl((int)mine, (g << 4) | (e + 8 * (m >> 3)), WAVE);
+            const float mult = drop.enabled ? (((theirs >> (m & 7)) & 1u) ? drop.scale : 0.f) : 1.f;
+            const int q = qg + e;
+            const bool admissible = k < len && (!causal || k <= q);
+            const float pe = admissible ? exp2_hw(acc[2 * u + (e >> 2)][e & 3] * alpha2 - Lv[e]) : 0.f;
+            pd[e] = pe * mult;
+            dsv[e] = alpha * pe * (dacc[2 * u + (e >> 2)][e & 3] * mult - Dv[e]);
+          }
+          const bf16x8_t pf = __builtin_bit_cast(bf16x8_t, pack8_bf16(pd));
+          const bf16x8_t df = __builtin_bit_cast(bf16x8_t, pack8_bf16(dsv));
+#pragma unroll
+          for (int nb = 0; nb < 4; ++nb) {
+            dv[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hd_frag_t(ct, u, nb), pf, dv[nb], 0, 0, 0);
+            dk[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hd_frag_t(qt, u, nb), df, dk[nb], 0, 0, 0);
+          }
+        }
+    }
+    __syncthreads();                                      // every wave is done with the blocks
+  }
+  if (active) {
+    bf16_t* out_row = dqkv + ((long)b * S + k) * ld + h * 64;
+    store_head_row(out_row + H, dk);
+    store_head_row(out_row + 2 * H, dv);
+  }
+}
+
 // ----------------------------------------------------------------- launch --
 raf_status launch_attn_prob_fwd(const raf_layer_desc& d, const void* qkv, const int32_t* lens, void* prob, void* prob_d,
                                 uint64_t step, hipStream_t st) {
@@ -686,6 +976,39 @@ raf_status launch_attn_bwd_full(const raf_layer_desc& d, const void* dc, const v
   hipLaunchKernelGGL(attn_bwd_full_kernel, dim3(d.batch * d.heads), dim3(512), ATT_BWD_LDS, st, (const bf16_t*)dc,
                      (const bf16_t*)qkv, lens, (bf16_t*)dqkv, d.seq, d.hidden, d.heads, d.causal,
                      0.125f * 1.44269504088896341f, 0.125f, drop);
+  return check_launch();
+}
+
+bool attn_flash_supported(const raf_layer_desc& d) {
+  return d.precision == RAF_BF16_AMP && d.hidden / d.heads == 64 && d.seq % 32 == 0 && d.seq > ATT_KC;
+}
+
+raf_status launch_attn_flash_fwd(const raf_layer_desc& d, const void* qkv, const int32_t* lens, void* ctx, float* lse,
+                                 uint64_t step, hipStream_t st) {
+  if (!qkv || !ctx || !lse) return RAF_EINVAL;
+  if (!attn_flash_supported(d)) return RAF_ENOTSUP;
+  const DropSite drop = make_drop_site(d, 1, step);
+  dim3 grid((d.seq + FL_QB - 1) / FL_QB, d.batch * d.heads);
+  hipLaunchKernelGGL(attn_flash_fwd_kernel, grid, dim3(512), 0, st, (const bf16_t*)qkv, lens, (bf16_t*)ctx, lse, d.seq,
+                     d.hidden, d.heads, d.causal, 0.125f * 1.44269504088896341f, drop);
+  return check_launch();
+}
+
+raf_status launch_attn_flash_bwd(const raf_layer_desc& d, const void* dc, const void* qkv, const void* ctx,
+                                 const float* lse, const int32_t* lens, void* dqkv, float* dvec, uint64_t step,
+                                 hipStream_t st) {
+  if (!dc || !qkv || !ctx || !lse || !dqkv || !dvec) return RAF_EINVAL;
+  if (!attn_flash_supported(d)) return RAF_ENOTSUP;
+  const DropSite drop = make_drop_site(d, 1, step);
+  const float alpha2 = 0.125f * 1.44269504088896341f;
+  dim3 grid((d.seq + FL_QB - 1) / FL_QB, d.batch * d.heads);
+  hipLaunchKernelGGL(attn_flash_dq_kernel, grid, dim3(512), 0, st, (const bf16_t*)dc, (const bf16_t*)qkv,
+                     (const bf16_t*)ctx, lse, lens, (bf16_t*)dqkv, dvec, d.seq, d.hidden, d.heads, d.causal, alpha2,
+                     0.125f, drop);
+  const raf_status rc = check_launch();
+  if (rc != RAF_OK) return rc;
+  hipLaunchKernelGGL(attn_flash_dkv_kernel, grid, dim3(512), 0, st, (const bf16_t*)dc, (const bf16_t*)qkv, lse,
+                     (const float*)dvec, lens, (bf16_t*)dqkv, d.seq, d.hidden, d.heads, d.causal, alpha2, 0.125f, drop);
   return check_launch();
 }
 

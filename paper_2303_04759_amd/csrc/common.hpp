@@ -292,6 +292,14 @@ raf_status launch_attn_prob_bwd(const raf_layer_desc& d, const void* dc, const v
 bool attn_fused_supported(const raf_layer_desc& d);
 raf_status launch_attn_fwd_fused(const raf_layer_desc& d, const void* qkv, const int32_t* lens, void* ctx, uint64_t step,
                                  hipStream_t st);
+// S > 128 in bf16 AMP: blockwise with running softmax statistics; lse [B*heads*S] floats goes from forward to
+// backward, dvec [B*heads*S] floats is backward scratch
+bool attn_flash_supported(const raf_layer_desc& d);
+raf_status launch_attn_flash_fwd(const raf_layer_desc& d, const void* qkv, const int32_t* lens, void* ctx, float* lse,
+                                 uint64_t step, hipStream_t st);
+raf_status launch_attn_flash_bwd(const raf_layer_desc& d, const void* dc, const void* qkv, const void* ctx,
+                                 const float* lse, const int32_t* lens, void* dqkv, float* dvec, uint64_t step,
+                                 hipStream_t st);
 raf_status launch_attn_bwd_full(const raf_layer_desc& d, const void* dc, const void* qkv, const int32_t* lens, void* dqkv,
                                 uint64_t step, hipStream_t st);
 raf_status launch_ln_fwd(const raf_layer_desc& d, int site, int64_t rows, const void* a, const void* res,

@@ -41,11 +41,11 @@ struct Plan {
   size_t e;   // element size of the compute dtype
   long T, H, F, S, NH, B, PS;   // PS = B*heads*S*S
   // saved
-  size_t qkv, prob, prob_d, c, z1, ffn_in, u, g, z2, n1, mu1, rstd1, mu2, rstd2, saved_bytes;
+  size_t qkv, prob, prob_d, c, z1, ffn_in, u, g, z2, n1, mu1, rstd1, mu2, rstd2, lse, saved_bytes;
   // scratch, forward
   size_t s, a;
   // scratch, backward
-  size_t dz2, da, da1, du, dffn, dz1, dc, dprob_d, ds, dqkv, dattn, partial_ln[3], partial_cs[2], wt_qkv, wt_o, wt_1, wt_2;
+  size_t dz2, da, da1, du, dffn, dz1, dc, dprob_d, ds, dqkv, dattn, dvec, partial_ln[3], partial_cs[2], wt_qkv, wt_o, wt_1, wt_2;
   size_t scratch_bytes;
 };
 
@@ -61,9 +61,10 @@ static Plan make_plan(const raf_layer_desc& d) {
   p.B = d.batch; p.S = d.seq; p.H = d.hidden; p.F = d.ffn; p.NH = d.heads;
   p.T = p.B * p.S;
   p.PS = p.B * p.NH * p.S * p.S;
-  // the fused attention path (S <= 128, bf16) keeps every S x S tensor on chip: no room is reserved for them
-  const size_t TH = (size_t)p.T * p.H * p.e, TF = (size_t)p.T * p.F * p.e,
-               PSb = attn_fused_supported(d) ? 0 : (size_t)p.PS * p.e;
+  // the bf16 attention kernels keep every S x S tensor on chip: no room is reserved for them
+  const bool onchip = attn_fused_supported(d) || attn_flash_supported(d);
+  const size_t TH = (size_t)p.T * p.H * p.e, TF = (size_t)p.T * p.F * p.e, PSb = onchip ? 0 : (size_t)p.PS * p.e;
+  const size_t rowstat = attn_flash_supported(d) ? (size_t)p.B * p.NH * p.S * 4 : 0;   // one float per query row and head
   size_t o = 0;
   p.qkv = bump(o, 3 * TH);
   p.prob = bump(o, PSb);
@@ -79,6 +80,7 @@ static Plan make_plan(const raf_layer_desc& d) {
   p.rstd1 = bump(o, p.T * 4);
   p.mu2 = bump(o, p.T * 4);
   p.rstd2 = bump(o, p.T * 4);
+  p.lse = bump(o, rowstat);
   p.saved_bytes = o;
   size_t f = 0;
   p.s = bump(f, PSb);
@@ -95,6 +97,7 @@ static Plan make_plan(const raf_layer_desc& d) {
   p.ds = bump(b, PSb);
   p.dqkv = bump(b, 3 * TH);
   p.dattn = bump(b, TH);
+  p.dvec = bump(b, rowstat);
   // one partial-sum buffer per producer: their second stages run together at the end of the backward pass
   for (int i = 0; i < 3; ++i) p.partial_ln[i] = bump(b, ln_bwd_partial_floats((int)p.H, p.T) * 4);
   p.partial_cs[0] = bump(b, colsum_partial_floats((int)p.F, p.T) * 4);
@@ -226,11 +229,14 @@ extern "C" raf_status raf_layer_fwd(const raf_layer_desc* desc, const raf_layer_
   }
   // F1: qkv = attn_in . Wqkv^T + bqkv
   RAF_TRY(gemm(prec, st, T, 3 * H, H, attn_in, H, 1, w->w_qkv, H, 1, qkv, 3 * H, 0, EPI_BIAS, (const float*)w->b_qkv));
-  const bool attn_fused = attn_fused_supported(d);   // S <= 128: F4 is taken inside the probability kernel
-  if (attn_fused) {
+  const bool attn_fused = attn_fused_supported(d) || attn_flash_supported(d);   // F4 is taken inside the attention kernel
+  if (attn_fused_supported(d)) {
     // F2+F3+F4 fused: scores, mask, softmax, dropout site 1, context; the backward pass recomputes the
     // probabilities, so they are not stored
     RAF_TRY(launch_attn_fwd_fused(d, qkv, seq_lens, c, step, st));
+  } else if (attn_flash_supported(d)) {
+    // the same for longer rows, 128 keys at a time; leaves one softmax statistic per query row for the backward pass
+    RAF_TRY(launch_attn_flash_fwd(d, qkv, seq_lens, c, (float*)at(saved, p.lse), step, st));
   } else if (prec == RAF_BF16_AMP) {
     // F2+F3 fused: scores, mask, softmax, dropout site 1; the score tensor stays in registers
     RAF_TRY(launch_attn_prob_fwd(d, qkv, seq_lens, prob, prob_d, step, st));
@@ -357,10 +363,14 @@ extern "C" raf_status raf_layer_bwd(const raf_layer_desc* desc, const raf_layer_
   // B4: c = prob_d V  ->  dV = prob_d^T dc (launched below, together with dK) ; dprob_d = dc V^T
   const GemmArgs dv_args = heads_args(p, S, 64, S, HeadView{prob_d, S, 0, true}, HeadView{dc, H, 0, false},
                                       at(dqkv, (size_t)2 * H * e), 3 * H, false, 1.0f);
-  const bool attn_fused = attn_fused_supported(d);   // S <= 128: B4, B3 and B2 in one kernel
-  if (attn_fused) {
-    // probabilities and dropout mask recomputed from qkv, seq_lens and the step counter; dQ, dK, dV written to dqkv
+  // bf16: B4, B3 and B2 in the attention kernels; probabilities and dropout mask are recomputed from qkv, seq_lens
+  // and the step counter; dQ, dK, dV are written to dqkv
+  const bool attn_fused = attn_fused_supported(d) || attn_flash_supported(d);
+  if (attn_fused_supported(d)) {
     RAF_TRY(launch_attn_bwd_full(d, dc, qkv, seq_lens, dqkv, step, st));
+  } else if (attn_flash_supported(d)) {
+    RAF_TRY(launch_attn_flash_bwd(d, dc, qkv, c, (const float*)at(saved, p.lse), seq_lens, dqkv,
+                                  (float*)at(scratch, p.dvec), step, st));
   } else if (prec == RAF_BF16_AMP) {
     // B4b+B3 fused: dprob_d stays in registers; dropout and softmax adjoints with the 1/8 folded in
     RAF_TRY(launch_attn_prob_bwd(d, dc, qkv, prob, prob_d, ds, st));
