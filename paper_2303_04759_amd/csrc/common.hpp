@@ -267,8 +267,6 @@ inline GemmArgs gemm_args_default() {
 }
 
 raf_status launch_gemm(int precision, const GemmArgs& g, hipStream_t st);
-// two batched problems with equal shapes, layouts and batch counts; one launch where a kernel supports it
-raf_status launch_gemm_pair(int precision, const GemmArgs& g1, const GemmArgs& g2, hipStream_t st);
 // up to 4 independent weight-gradient GEMMs (A, B MN-major, float out) in one launch
 raf_status launch_gemm_group_wgrad(int precision, const GemmArgs* gs, int count, hipStream_t st);
 // dst[c][r] = src[r][c] for up to 4 dense row-major bf16 matrices (rows, cols multiples of 8) in one launch
@@ -281,11 +279,6 @@ raf_status launch_softmax_fwd(const raf_layer_desc& d, const void* s, const int3
                               uint64_t step, hipStream_t st);
 raf_status launch_softmax_bwd(const raf_layer_desc& d, const void* prob, const void* prob_d, const void* dprob_d,
                               void* ds, float scale_out, hipStream_t st);
-// bf16 AMP only: scores + mask + softmax + dropout in one kernel (no S x S score tensor), and its adjoint
-raf_status launch_attn_prob_fwd(const raf_layer_desc& d, const void* qkv, const int32_t* lens, void* prob, void* prob_d,
-                                uint64_t step, hipStream_t st);
-raf_status launch_attn_prob_bwd(const raf_layer_desc& d, const void* dc, const void* qkv, const void* prob,
-                                const void* prob_d, void* ds, hipStream_t st);
 // S <= 128 in bf16 AMP: no S x S tensor reaches memory.  Forward: ctx = P~ . V written to [T,H], the probabilities
 // are not stored.  Backward: P and the dropout mask are recomputed from qkv, the same lens and the same step; dQ, dK
 // and dV are written to dqkv [T,3H].

@@ -423,20 +423,6 @@ raf_status launch_gemm_group_wgrad(int precision, const GemmArgs* gs, int count,
   return check_launch();
 }
 
-raf_status launch_gemm_pair(int precision, const GemmArgs& g1, const GemmArgs& g2, hipStream_t st) {
-  raf_status rc = check_gemm_args(g1);
-  if (rc != RAF_OK) return rc;
-  rc = check_gemm_args(g2);
-  if (rc != RAF_OK) return rc;
-  if (precision == RAF_BF16_AMP && g1.batch == g2.batch && g1.a_kmajor == g2.a_kmajor && g1.b_kmajor == g2.b_kmajor &&
-      !g1.out_f32 && !g2.out_f32 && g1.epilogue == EPI_NONE && g2.epilogue == EPI_NONE && g1.nz_inner == g2.nz_inner &&
-      launch_gemm_pipe_pair(to_dev(g1), to_dev(g2), g1.a_kmajor, g1.b_kmajor, g1.batch, st))
-    return check_launch();
-  rc = launch_gemm(precision, g1, st);
-  if (rc != RAF_OK) return rc;
-  return launch_gemm(precision, g2, st);
-}
-
 raf_status launch_gemm(int precision, const GemmArgs& g, hipStream_t st) {
   raf_status rc = check_gemm_args(g);
   if (rc != RAF_OK) return rc;

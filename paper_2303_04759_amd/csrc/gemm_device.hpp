@@ -368,7 +368,5 @@ bool launch_gemm_group_spec(const GemmDev* ds, int count, hipStream_t st);
 // the problem does not meet its requirements (K % 64, tile fit) and the
 // caller must use the staged kernel instead.
 bool launch_gemm_pipe(const GemmDev& d, int a_kmajor, int b_kmajor, int out_f32, int batch, hipStream_t st);
-// two batched problems of identical shape and layout in one launch; false when the shape does not fit
-bool launch_gemm_pipe_pair(const GemmDev& d1, const GemmDev& d2, int a_kmajor, int b_kmajor, int batch, hipStream_t st);
 
 }  // namespace raf

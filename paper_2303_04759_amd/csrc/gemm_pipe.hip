@@ -215,16 +215,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_kernel(GemmDev 
   pipe_body<BM, BN, WGM, WGN, A_KMAJOR, B_KMAJOR, TC, NS>(g, tiles_m, tiles_n, remap, (int)blockIdx.y);
 }
 
-// Two batched problems of one shape and layout in a single launch (the dK and dV products of the attention
-// backward pass): blockIdx.y < split works on g1, the rest on g2.
-template <int BM, int BN, int WGM, int WGN, bool A_KMAJOR, bool B_KMAJOR, typename TC, int NS>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_pipe_pair_kernel(GemmDev g1, GemmDev g2, int split,
-                                                                             int tiles_m, int tiles_n) {
-  const bool second = (int)blockIdx.y >= split;
-  const GemmDev g = second ? g2 : g1;   // static selection: the descriptors stay in scalar registers
-  pipe_body<BM, BN, WGM, WGN, A_KMAJOR, B_KMAJOR, TC, NS>(g, tiles_m, tiles_n, 0, (int)blockIdx.y - (second ? split : 0));
-}
-
 template <int BM, int BN, int WGM, int WGN, bool AK, bool BKM, typename TC, int NS>
 static bool launch_pipe_inst(const GemmDev& d, int batch, hipStream_t st) {
   constexpr int NW = WGM * WGN;
@@ -797,27 +787,6 @@ static bool launch_w48_inst(const GemmDev& d, hipStream_t st) {
 template <bool AK, bool BKM, typename TC>
 static bool launch_pipe_layout(const GemmDev& d, int batch, hipStream_t st) {
   return launch_pipe_inst<128, 128, 2, 4, AK, BKM, TC, 2>(d, batch, st);
-}
-
-bool launch_gemm_pipe_pair(const GemmDev& d1, const GemmDev& d2, int a_kmajor, int b_kmajor, int batch,
-                           hipStream_t st) {
-  // same conditions as the per-head path of launch_gemm_pipe, both operands MN-major
-  if (a_kmajor || b_kmajor || batch < 1 || 2 * batch > 65535) return false;
-  if (d1.M != d2.M || d1.N != d2.N || d1.K != d2.K) return false;
-  if (d1.N != 64 || d1.K > 2 * PBK || d1.K % PBK || d1.M < 128 || d1.M % 128) return false;
-  constexpr int LDS_BYTES = 3 * (PipeTile<128, false, 4>::BYTES + PipeTile<64, false, 4>::BYTES);
-  auto kern = gemm_bf16_pipe_pair_kernel<128, 64, 2, 2, false, false, bf16_t, 3>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess) {
-      (void)hipGetLastError();
-      return false;
-    }
-    attr_done = true;
-  }
-  const int tiles_m = d1.M / 128;
-  hipLaunchKernelGGL(kern, dim3(tiles_m, 2 * batch), dim3(256), LDS_BYTES, st, d1, d2, batch, tiles_m, 1);
-  return true;
 }
 
 bool launch_gemm_pipe(const GemmDev& d, int a_kmajor, int b_kmajor, int out_f32, int batch, hipStream_t st) {

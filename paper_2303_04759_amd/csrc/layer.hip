@@ -237,10 +237,7 @@ extern "C" raf_status raf_layer_fwd(const raf_layer_desc* desc, const raf_layer_
   } else if (attn_flash_supported(d)) {
     // the same for longer rows, 128 keys at a time; leaves one softmax statistic per query row for the backward pass
     RAF_TRY(launch_attn_flash_fwd(d, qkv, seq_lens, c, (float*)at(saved, p.lse), step, st));
-  } else if (prec == RAF_BF16_AMP) {
-    // F2+F3 fused: scores, mask, softmax, dropout site 1; the score tensor stays in registers
-    RAF_TRY(launch_attn_prob_fwd(d, qkv, seq_lens, prob, prob_d, step, st));
-  } else {
+  } else {   // fp32
     // F2: s = Q K^T / 8 per (batch, head)
     RAF_TRY(gemm_heads(p, prec, st, S, S, 64, HeadView{qkv, 3 * H, 1, false},
                        HeadView{at(qkv, (size_t)H * e), 3 * H, 1, false}, s, S, true, alpha));
@@ -360,35 +357,28 @@ extern "C" raf_status raf_layer_bwd(const raf_layer_desc* desc, const raf_layer_
                           &rj[nr++]));
   // B5: a1 = c Wo^T + bo  ->  dc = da1 Wo                   [dWo = da1^T c deferred]
   RAF_TRY(gemm(prec, st, T, H, H, da1, H, 1, wt ? wt_o : w->w_o, H, wt ? 1 : 0, dc, H));
-  // B4: c = prob_d V  ->  dV = prob_d^T dc (launched below, together with dK) ; dprob_d = dc V^T
-  const GemmArgs dv_args = heads_args(p, S, 64, S, HeadView{prob_d, S, 0, true}, HeadView{dc, H, 0, false},
-                                      at(dqkv, (size_t)2 * H * e), 3 * H, false, 1.0f);
-  // bf16: B4, B3 and B2 in the attention kernels; probabilities and dropout mask are recomputed from qkv, seq_lens
-  // and the step counter; dQ, dK, dV are written to dqkv
-  const bool attn_fused = attn_fused_supported(d) || attn_flash_supported(d);
+  // B4, B3, B2: adjoint of the attention core; dQ, dK, dV are written to dqkv
   if (attn_fused_supported(d)) {
+    // bf16, S <= 128: one kernel; probabilities and dropout mask recomputed from qkv, seq_lens and the step counter
     RAF_TRY(launch_attn_bwd_full(d, dc, qkv, seq_lens, dqkv, step, st));
   } else if (attn_flash_supported(d)) {
+    // bf16, longer rows: the same from the row statistics of the forward pass, 128 keys / queries at a time
     RAF_TRY(launch_attn_flash_bwd(d, dc, qkv, c, (const float*)at(saved, p.lse), seq_lens, dqkv,
                                   (float*)at(scratch, p.dvec), step, st));
-  } else if (prec == RAF_BF16_AMP) {
-    // B4b+B3 fused: dprob_d stays in registers; dropout and softmax adjoints with the 1/8 folded in
-    RAF_TRY(launch_attn_prob_bwd(d, dc, qkv, prob, prob_d, ds, st));
-  } else {
+  } else {   // fp32
+    // B4: c = prob_d V  ->  dV = prob_d^T dc ; dprob_d = dc V^T
     RAF_TRY(gemm_heads(p, prec, st, S, S, 64, HeadView{dc, H, 1, false},
                        HeadView{at(qkv, (size_t)2 * H * e), 3 * H, 1, false}, dprob_d, S, true, 1.0f));
+    RAF_TRY(gemm_heads(p, prec, st, S, 64, S, HeadView{prob_d, S, 0, true}, HeadView{dc, H, 0, false},
+                       at(dqkv, (size_t)2 * H * e), 3 * H, false, 1.0f));
     // B3: softmax + dropout adjoint, with the 1/8 of the score scaling folded in
     RAF_TRY(launch_softmax_bwd(d, prob, prob_d, dprob_d, ds, alpha, st));
-  }
-  // B2: s = Q K^T / 8  ->  dQ = ds K ; dK = ds^T Q
-  if (!attn_fused)
+    // B2: s = Q K^T / 8  ->  dQ = ds K ; dK = ds^T Q
     RAF_TRY(gemm_heads(p, prec, st, S, 64, S, HeadView{ds, S, 1, true},
                        HeadView{at(qkv, (size_t)H * e), 3 * H, 0, false}, dqkv, 3 * H, false, 1.0f));
-  // dK and dV have the same shape and layout (A^T B over the query index): one launch
-  if (!attn_fused)
-    RAF_TRY(launch_gemm_pair(prec, heads_args(p, S, 64, S, HeadView{ds, S, 0, true}, HeadView{qkv, 3 * H, 0, false},
-                                            at(dqkv, (size_t)H * e), 3 * H, false, 1.0f),
-                           dv_args, st));
+    RAF_TRY(gemm_heads(p, prec, st, S, 64, S, HeadView{ds, S, 0, true}, HeadView{qkv, 3 * H, 0, false},
+                       at(dqkv, (size_t)H * e), 3 * H, false, 1.0f));
+  }
   // B1: qkv = attn_in Wqkv^T + bqkv
   cj[1] = ColsumJob{prec, dqkv, T, 3 * H, 3 * H, (float*)grads->b_qkv, (float*)at(scratch, p.partial_cs[1]), 0};
   if (d.pre_ln) {
