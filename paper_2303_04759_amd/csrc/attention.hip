@@ -379,6 +379,8 @@ __global__ __launch_bounds__(512) void attn_bwd_full_kernel(const bf16_t* __rest
 // Dropout blocks cover 8 consecutive keys of one query, so there each lane generates the block of one (query,
 // key octet) of its 16 x 32 sub-block and the keep bits are exchanged with lane permutes.
 constexpr int FL_QB = 128;   // query rows per workgroup (8 waves x 16)
+constexpr int FL_STAGE = 2 * HD_TILE;                      // K and V (or Q and dC) block
+constexpr int FL_DKV_STAGE = 2 * HD_TILE + 2 * FL_QB * 4;  // plus lse and D of the query rows
 
 // keep bits (bit e = element idx8 + e is kept) of one Philox block
 __device__ __forceinline__ uint32_t drop_keep8(const DropSite& s, uint64_t idx8) {
@@ -403,8 +405,7 @@ __device__ __forceinline__ float frag_dot(const bf16x8_t (&a)[2], const bf16x8_t
 __global__ __launch_bounds__(512) void attn_flash_fwd_kernel(const bf16_t* __restrict__ qkv, const int32_t* __restrict__ lens,
                                                              bf16_t* __restrict__ ctx, float* __restrict__ lse, int S,
                                                              int H, int heads, int causal, float alpha2, DropSite drop) {
-  __shared__ __attribute__((aligned(1024))) char kt[HD_TILE];
-  __shared__ __attribute__((aligned(1024))) char vt[HD_TILE];
+  extern __shared__ __attribute__((aligned(1024))) char fl_lds[];   // two stages of (K block, V block)
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int bh = blockIdx.y, b = bh / heads, h = bh % heads;
   const long ld = 3L * H;
@@ -427,14 +428,23 @@ __global__ __launch_bounds__(512) void attn_flash_fwd_kernel(const bf16_t* __res
   f32x4_t o[4];
 #pragma unroll
   for (int nb = 0; nb < 4; ++nb) o[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  auto fetch = [&](int jb) {   // K and V rows of key block jb -> stage jb & 1
+    const int key0 = jb * ATT_KC;
+    const int rows = S - key0 < ATT_KC ? S - key0 : ATT_KC;
+    char* st = fl_lds + (jb & 1) * 2 * HD_TILE;
+    hd_tile_load(Q + H + (long)key0 * ld, ld, rows, st);
+    hd_tile_load(Q + 2 * H + (long)key0 * ld, ld, rows, st + HD_TILE);
+  };
+  if (nkb > 0) fetch(0);
   for (int jb = 0; jb < nkb; ++jb) {
     const int key0 = jb * ATT_KC;
     const int rows = S - key0 < ATT_KC ? S - key0 : ATT_KC;
     const int npairs = rows / 32;
-    hd_tile_load(Q + H + (long)key0 * ld, ld, rows, kt);
-    hd_tile_load(Q + 2 * H + (long)key0 * ld, ld, rows, vt);
+    const char* kt = fl_lds + (jb & 1) * 2 * HD_TILE;
+    const char* vt = kt + HD_TILE;
     hd_tile_wait();
-    __syncthreads();                                      // K and V blocks complete
+    __syncthreads();                                      // block jb has landed; every wave is done with block jb-1
+    if (jb + 1 < nkb) fetch(jb + 1);                      // overlaps the arithmetic below
     if (active) {
       f32x4_t acc[ATT_TILES];
       tile_products(kt, qf, acc, npairs);
@@ -483,7 +493,6 @@ __global__ __launch_bounds__(512) void attn_flash_fwd_kernel(const bf16_t* __res
             o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hd_frag_t(vt, u, nb), pf, o[nb], 0, 0, 0);
         }
     }
-    __syncthreads();                                      // every wave is done with the blocks
   }
   if (!active) return;
   const float inv = sum > 0.f ? 1.0f / sum : 0.f;         // a row without admissible keys gives zeros
@@ -499,8 +508,7 @@ __global__ __launch_bounds__(512) void attn_flash_dq_kernel(const bf16_t* __rest
                                                             const int32_t* __restrict__ lens, bf16_t* __restrict__ dqkv,
                                                             float* __restrict__ dvec, int S, int H, int heads, int causal,
                                                             float alpha2, float alpha, DropSite drop) {
-  __shared__ __attribute__((aligned(1024))) char kt[HD_TILE];
-  __shared__ __attribute__((aligned(1024))) char vt[HD_TILE];
+  extern __shared__ __attribute__((aligned(1024))) char fl_lds[];   // two stages of (K block, V block)
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int bh = blockIdx.y, b = bh / heads, h = bh % heads;
   const long ld = 3L * H;
@@ -531,14 +539,23 @@ __global__ __launch_bounds__(512) void attn_flash_dq_kernel(const bf16_t* __rest
   f32x4_t dq[4];
 #pragma unroll
   for (int nb = 0; nb < 4; ++nb) dq[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  auto fetch = [&](int jb) {   // K and V rows of key block jb -> stage jb & 1
+    const int key0 = jb * ATT_KC;
+    const int rows = S - key0 < ATT_KC ? S - key0 : ATT_KC;
+    char* st = fl_lds + (jb & 1) * 2 * HD_TILE;
+    hd_tile_load(Q + H + (long)key0 * ld, ld, rows, st);
+    hd_tile_load(Q + 2 * H + (long)key0 * ld, ld, rows, st + HD_TILE);
+  };
+  if (nkb > 0) fetch(0);
   for (int jb = 0; jb < nkb; ++jb) {
     const int key0 = jb * ATT_KC;
     const int rows = S - key0 < ATT_KC ? S - key0 : ATT_KC;
     const int npairs = rows / 32;
-    hd_tile_load(Q + H + (long)key0 * ld, ld, rows, kt);
-    hd_tile_load(Q + 2 * H + (long)key0 * ld, ld, rows, vt);
+    const char* kt = fl_lds + (jb & 1) * 2 * HD_TILE;
+    const char* vt = kt + HD_TILE;
     hd_tile_wait();
-    __syncthreads();
+    __syncthreads();                                      // block jb has landed; every wave is done with block jb-1
+    if (jb + 1 < nkb) fetch(jb + 1);
     if (active) {
       f32x4_t acc[ATT_TILES], dacc[ATT_TILES];
       tile_products(kt, qf, acc, npairs);
@@ -565,7 +582,6 @@ __global__ __launch_bounds__(512) void attn_flash_dq_kernel(const bf16_t* __rest
             dq[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hd_frag_t(kt, u, nb), df, dq[nb], 0, 0, 0);
         }
     }
-    __syncthreads();
   }
   if (active) store_head_row(dqkv + ((long)b * S + i) * ld + h * 64, dq);
 }
@@ -576,8 +592,7 @@ __global__ __launch_bounds__(512) void attn_flash_dkv_kernel(const bf16_t* __res
                                                              const int32_t* __restrict__ lens, bf16_t* __restrict__ dqkv,
                                                              int S, int H, int heads, int causal, float alpha2,
                                                              float alpha, DropSite drop) {
-  __shared__ __attribute__((aligned(1024))) char qt[HD_TILE];
-  __shared__ __attribute__((aligned(1024))) char ct[HD_TILE];
+  extern __shared__ __attribute__((aligned(1024))) char fl_lds[];   // two stages of (Q block, dC block, lse and D of its rows)
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int bh = blockIdx.y, b = bh / heads, h = bh % heads;
   const long ld = 3L * H;
@@ -602,14 +617,32 @@ __global__ __launch_bounds__(512) void attn_flash_dkv_kernel(const bf16_t* __res
   // causal: query blocks before this key block see none of its keys; keys beyond every length contribute nothing
   const int ib0 = causal ? jb : 0;
   const int ib1 = jb * ATT_KC < len ? nqb : ib0;
+  auto fetch = [&](int ib) {   // Q and dC rows of query block ib and their row statistics -> stage ib & 1
+    const int q0 = ib * FL_QB;
+    const int rows = S - q0 < FL_QB ? S - q0 : FL_QB;
+    char* st = fl_lds + (ib & 1) * FL_DKV_STAGE;
+    hd_tile_load(Q + (long)q0 * ld, ld, rows, st);
+    hd_tile_load(DC + (long)q0 * H, H, rows, st + HD_TILE);
+    if (wave < 4) {   // 4 bytes per lane: lse rows 0-63, 64-127, then D likewise (rows past the end re-read the last row)
+      int q = q0 + (wave & 1) * 64 + lane;
+      q = q < S ? q : S - 1;
+      const float* src = (wave < 2 ? lse : dvec) + (long)bh * S + q;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                       (att_lds_ptr)(st + 2 * HD_TILE + wave * 256), 4, 0, 0);
+    }
+  };
+  if (ib0 < ib1) fetch(ib0);
   for (int ib = ib0; ib < ib1; ++ib) {
     const int q0 = ib * FL_QB;
     const int rows = S - q0 < FL_QB ? S - q0 : FL_QB;
     const int npairs = rows / 32;
-    hd_tile_load(Q + (long)q0 * ld, ld, rows, qt);
-    hd_tile_load(DC + (long)q0 * H, H, rows, ct);
+    const char* qt = fl_lds + (ib & 1) * FL_DKV_STAGE;
+    const char* ct = qt + HD_TILE;
+    const float* lse_t = reinterpret_cast<const float*>(ct + HD_TILE);
+    const float* dvec_t = lse_t + FL_QB;
     hd_tile_wait();
-    __syncthreads();                                      // Q and dC blocks complete
+    __syncthreads();                                      // block ib has landed; every wave is done with block ib-1
+    if (ib + 1 < ib1) fetch(ib + 1);
     if (active) {
       f32x4_t acc[ATT_TILES], dacc[ATT_TILES];
       tile_products(qt, kf, acc, npairs);                 // own key row x 8 consecutive queries per 32-query group
@@ -619,10 +652,10 @@ __global__ __launch_bounds__(512) void attn_flash_dkv_kernel(const bf16_t* __res
         if (u < npairs) {
           const int qg = q0 + 32 * u + 8 * g;             // first of this lane's 8 queries in the group
           float Lv[8], Dv[8];
-          *reinterpret_cast<float4*>(&Lv[0]) = *reinterpret_cast<const float4*>(lse + (long)bh * S + qg);
-          *reinterpret_cast<float4*>(&Lv[4]) = *reinterpret_cast<const float4*>(lse + (long)bh * S + qg + 4);
-          *reinterpret_cast<float4*>(&Dv[0]) = *reinterpret_cast<const float4*>(dvec + (long)bh * S + qg);
-          *reinterpret_cast<float4*>(&Dv[4]) = *reinterpret_cast<const float4*>(dvec + (long)bh * S + qg + 4);
+          *reinterpret_cast<float4*>(&Lv[0]) = *reinterpret_cast<const float4*>(lse_t + 32 * u + 8 * g);
+          *reinterpret_cast<float4*>(&Lv[4]) = *reinterpret_cast<const float4*>(lse_t + 32 * u + 8 * g + 4);
+          *reinterpret_cast<float4*>(&Dv[0]) = *reinterpret_cast<const float4*>(dvec_t + 32 * u + 8 * g);
+          *reinterpret_cast<float4*>(&Dv[4]) = *reinterpret_cast<const float4*>(dvec_t + 32 * u + 8 * g + 4);
           // this lane's Philox block: query qg + (m & 7), keys kbase + 8*(m >> 3) .. +7; the lane that needs the bit
           // of (query qg + e, key k) fetches the block of lane (g, e + 8*(m >> 3)) and takes bit m & 7
           uint32_t mine = 0xffu;
@@ -648,7 +681,6 @@ __global__ __launch_bounds__(512) void attn_flash_dkv_kernel(const bf16_t* __res
           }
         }
     }
-    __syncthreads();                                      // every wave is done with the blocks
   }
   if (active) {
     bf16_t* out_row = dqkv + ((long)b * S + k) * ld + h * 64;
@@ -700,7 +732,14 @@ raf_status launch_attn_flash_fwd(const raf_layer_desc& d, const void* qkv, const
   if (!attn_flash_supported(d)) return RAF_ENOTSUP;
   const DropSite drop = make_drop_site(d, 1, step);
   dim3 grid((d.seq + FL_QB - 1) / FL_QB, d.batch * d.heads);
-  hipLaunchKernelGGL(attn_flash_fwd_kernel, grid, dim3(512), 0, st, (const bf16_t*)qkv, lens, (bf16_t*)ctx, lse, d.seq,
+  static bool attr_done = false;
+  if (!attr_done) {
+    if (hipFuncSetAttribute((const void*)attn_flash_fwd_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            2 * FL_STAGE) != hipSuccess)
+      return check_launch();
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(attn_flash_fwd_kernel, grid, dim3(512), 2 * FL_STAGE, st, (const bf16_t*)qkv, lens, (bf16_t*)ctx, lse, d.seq,
                      d.hidden, d.heads, d.causal, 0.125f * 1.44269504088896341f, drop);
   return check_launch();
 }
@@ -713,12 +752,21 @@ raf_status launch_attn_flash_bwd(const raf_layer_desc& d, const void* dc, const 
   const DropSite drop = make_drop_site(d, 1, step);
   const float alpha2 = 0.125f * 1.44269504088896341f;
   dim3 grid((d.seq + FL_QB - 1) / FL_QB, d.batch * d.heads);
-  hipLaunchKernelGGL(attn_flash_dq_kernel, grid, dim3(512), 0, st, (const bf16_t*)dc, (const bf16_t*)qkv,
+  static bool attr_done = false;
+  if (!attr_done) {
+    if (hipFuncSetAttribute((const void*)attn_flash_dq_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            2 * FL_STAGE) != hipSuccess ||
+        hipFuncSetAttribute((const void*)attn_flash_dkv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            2 * FL_DKV_STAGE) != hipSuccess)
+      return check_launch();
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(attn_flash_dq_kernel, grid, dim3(512), 2 * FL_STAGE, st, (const bf16_t*)dc, (const bf16_t*)qkv,
                      (const bf16_t*)ctx, lse, lens, (bf16_t*)dqkv, dvec, d.seq, d.hidden, d.heads, d.causal, alpha2,
                      0.125f, drop);
   const raf_status rc = check_launch();
   if (rc != RAF_OK) return rc;
-  hipLaunchKernelGGL(attn_flash_dkv_kernel, grid, dim3(512), 0, st, (const bf16_t*)dc, (const bf16_t*)qkv, lse,
+  hipLaunchKernelGGL(attn_flash_dkv_kernel, grid, dim3(512), 2 * FL_DKV_STAGE, st, (const bf16_t*)dc, (const bf16_t*)qkv, lse,
                      (const float*)dvec, lens, (bf16_t*)dqkv, d.seq, d.hidden, d.heads, d.causal, alpha2, 0.125f, drop);
   return check_launch();
 }
