@@ -246,6 +246,22 @@ raf_status raf_op_softmax_fwd(const raf_layer_desc *desc, const void *s, const i
 raf_status raf_op_softmax_bwd(const raf_layer_desc *desc, const void *prob, const void *prob_d,
                               const void *dprob_d, void *ds, float scale_out, void *hip_stream);
 
+/* Attention core of the bf16 AMP path (precision must be RAF_BF16_AMP), all S x S
+ * tensors kept on chip: ctx = merge_heads(dropout1(softmax(mask(Q K^T / 8))) V)
+ * from qkv [B*S,3H] (column blocks Q | K | V, head h = columns 64h .. 64h+63).
+ *   ctx [dev] [B*S,H] written; lse [dev] float[B*heads*S] written when
+ *   seq > 128 (row statistic max + log2(sum) in base-2 score units that the
+ *   backward call needs), ignored and may be NULL otherwise. */
+raf_status raf_op_attention_fwd(const raf_layer_desc *desc, const void *qkv, const int32_t *seq_lens, void *ctx,
+                                float *lse, uint64_t step, void *hip_stream);
+/* Adjoint: dqkv [B*S,3H] (dQ | dK | dV) from dctx [B*S,H]; probabilities and
+ * dropout mask are recomputed from qkv, seq_lens and step, which must be those of
+ * the forward call.  seq > 128 also needs ctx and lse of the forward call and
+ * dvec [dev] float[B*heads*S] scratch; they are ignored (may be NULL) otherwise. */
+raf_status raf_op_attention_bwd(const raf_layer_desc *desc, const void *dctx, const void *qkv, const void *ctx,
+                                const float *lse, const int32_t *seq_lens, void *dqkv, float *dvec, uint64_t step,
+                                void *hip_stream);
+
 /* z = res + dropout_site(a); out = LayerNorm(z) with float statistics.
  * a == NULL: z = res (plain LayerNorm).  gamma == NULL: no LayerNorm, out = z
  * (z_out, mu, rstd ignored).  site in {2,3}. rows*H elements, compute dtype. */

@@ -105,6 +105,49 @@ def _merge_heads(t, B, S, nh, dh):
     return t.transpose(0, 2, 1, 3).reshape(B * S, nh * dh)     # [T,H]
 
 
+# ---------------------------------------------------- attention core --
+def attention_core_forward(cfg, qkv, seq_lens=None, step=0):
+    """qkv [T,3H] (column blocks Q | K | V, head h = columns 64h..) -> (c [T,H], cache):
+    s = Q K^T / sqrt(dh), mask, softmax, dropout site 1, c = merge_heads(P~ V)."""
+    B, S, H, nh = (cfg[k] for k in ("batch", "seq", "hidden", "heads"))
+    dh = H // nh
+    p = float(cfg["dropout_p"])
+    alpha = 1.0 / np.sqrt(dh)
+    scale = 1.0 / (1.0 - p)
+    qkv = np.asarray(qkv, dtype=np.float64).reshape(B * S, 3 * H)
+    q = _split_heads(qkv[:, 0 * H:1 * H], B, S, nh, dh)
+    k = _split_heads(qkv[:, 1 * H:2 * H], B, S, nh, dh)
+    v = _split_heads(qkv[:, 2 * H:3 * H], B, S, nh, dh)
+    s = alpha * np.einsum("bhid,bhjd->bhij", q, k)
+    masked = attention_masked(B, S, seq_lens, bool(cfg["causal"]))
+    prob = masked_softmax(s, masked)
+    keep1 = _keep(cfg, 1, step, (B, nh, S, S))
+    prob_d = prob * keep1 * scale
+    c = _merge_heads(np.einsum("bhij,bhjd->bhid", prob_d, v), B, S, nh, dh)
+    return c, dict(q=q, k=k, v=v, prob=prob, keep1=keep1, prob_d=prob_d)
+
+
+def attention_core_backward(cfg, A, dc):
+    """Adjoint of attention_core_forward: dc [T,H] -> (dqkv [T,3H], ds [B,nh,S,S])."""
+    B, S, H, nh = (cfg[k] for k in ("batch", "seq", "hidden", "heads"))
+    dh = H // nh
+    p = float(cfg["dropout_p"])
+    alpha = 1.0 / np.sqrt(dh)
+    scale = 1.0 / (1.0 - p)
+    dc = _split_heads(np.asarray(dc, dtype=np.float64).reshape(B * S, H), B, S, nh, dh)   # [B,nh,S,dh]
+    # c = prob_d V
+    dprob_d = np.einsum("bhid,bhjd->bhij", dc, A["v"])
+    dv = np.einsum("bhij,bhid->bhjd", A["prob_d"], dc)
+    # prob_d = prob * keep1 * scale ; prob = softmax(s)
+    dprob = dprob_d * A["keep1"] * scale
+    ds = A["prob"] * (dprob - (dprob * A["prob"]).sum(axis=-1, keepdims=True))
+    # s = alpha q k^T
+    dq = alpha * np.einsum("bhij,bhjd->bhid", ds, A["k"])
+    dk = alpha * np.einsum("bhij,bhid->bhjd", ds, A["q"])
+    dqkv = np.concatenate([_merge_heads(t, B, S, nh, dh) for t in (dq, dk, dv)], axis=1)
+    return dqkv, ds
+
+
 # ---------------------------------------------------------------- forward --
 def layer_forward(cfg, params, x, seq_lens=None, step=0):
     """x: [B,S,H] (or [T,H]).  Returns (y [T,H], cache dict)."""
@@ -128,19 +171,12 @@ def layer_forward(cfg, params, x, seq_lens=None, step=0):
     C["attn_in"] = attn_in
 
     qkv = attn_in @ P64["w_qkv"].T + P64["b_qkv"]
-    q = _split_heads(qkv[:, 0 * H:1 * H], B, S, nh, dh)
-    k = _split_heads(qkv[:, 1 * H:2 * H], B, S, nh, dh)
-    v = _split_heads(qkv[:, 2 * H:3 * H], B, S, nh, dh)
-    s = alpha * np.einsum("bhid,bhjd->bhij", q, k)
-    masked = attention_masked(B, S, seq_lens, bool(cfg["causal"]))
-    prob = masked_softmax(s, masked)
-    keep1 = _keep(cfg, 1, step, (B, nh, S, S))
-    prob_d = prob * keep1 * scale
-    c = _merge_heads(np.einsum("bhij,bhjd->bhid", prob_d, v), B, S, nh, dh)
+    c, A = attention_core_forward(cfg, qkv, seq_lens, step)
     a1 = c @ P64["w_o"].T + P64["b_o"]
     keep2 = _keep(cfg, 2, step, (T, H))
     z1 = x + a1 * keep2 * scale
-    C.update(q=q, k=k, v=v, prob=prob, keep1=keep1, prob_d=prob_d, c=c, keep2=keep2, z1=z1)
+    C.update(A)
+    C.update(c=c, keep2=keep2, z1=z1)
 
     if pre_ln:
         ffn_in, C["xhat2"], C["rstd2"] = layernorm(z1, P64["ln2_g"], P64["ln2_b"], eps)
@@ -219,17 +255,7 @@ def layer_backward(cfg, cache, dy):
     dx = dz1.copy()
     gr["w_o"] = da1.T @ C["c"]
     gr["b_o"] = da1.sum(axis=0)
-    dc = _split_heads(da1 @ W["w_o"], B, S, nh, dh)              # [B,nh,S,dh]
-    # c = prob_d V
-    dprob_d = np.einsum("bhid,bhjd->bhij", dc, C["v"])
-    dv = np.einsum("bhij,bhid->bhjd", C["prob_d"], dc)
-    # prob_d = prob * keep1 * scale ; prob = softmax(s)
-    dprob = dprob_d * C["keep1"] * scale
-    ds = C["prob"] * (dprob - (dprob * C["prob"]).sum(axis=-1, keepdims=True))
-    # s = alpha q k^T
-    dq = alpha * np.einsum("bhij,bhjd->bhid", ds, C["k"])
-    dk = alpha * np.einsum("bhij,bhid->bhjd", ds, C["q"])
-    dqkv = np.concatenate([_merge_heads(t, B, S, nh, dh) for t in (dq, dk, dv)], axis=1)
+    dqkv, ds = attention_core_backward(cfg, C, da1 @ W["w_o"])
     gr["w_qkv"] = dqkv.T @ C["attn_in"]
     gr["b_qkv"] = dqkv.sum(axis=0)
     dattn_in = dqkv @ W["w_qkv"]

@@ -92,6 +92,9 @@ _SIGNATURES = {
                                      C.c_uint64, C.c_void_p]),
     "raf_op_softmax_bwd": (C.c_int, [C.POINTER(LayerDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_float, C.c_void_p]),
+    "raf_op_attention_fwd": (C.c_int, [C.POINTER(LayerDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                       C.c_uint64, C.c_void_p]),
+    "raf_op_attention_bwd": (C.c_int, [C.POINTER(LayerDesc)] + [C.c_void_p] * 7 + [C.c_uint64, C.c_void_p]),
     "raf_op_dropout_residual_ln_fwd": (C.c_int, [C.POINTER(LayerDesc), C.c_int32, C.c_int64, C.c_void_p, C.c_void_p,
                                                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                                  C.c_void_p, C.c_uint64, C.c_void_p]),
@@ -233,6 +236,17 @@ def raf_op_softmax_fwd(desc, s, seq_lens, prob, prob_d, step, stream=None):
 def raf_op_softmax_bwd(desc, prob, prob_d, dprob_d, ds, scale_out, stream=None):
     _check(load_library().raf_op_softmax_bwd(C.byref(desc), _ptr(prob), _ptr(prob_d), _ptr(dprob_d), _ptr(ds),
                                              float(scale_out), _stream(stream)), "raf_op_softmax_bwd")
+
+
+def raf_op_attention_fwd(desc, qkv, seq_lens, ctx, lse, step, stream=None):
+    _check(load_library().raf_op_attention_fwd(C.byref(desc), _ptr(qkv), _ptr(seq_lens), _ptr(ctx), _ptr(lse),
+                                               int(step), _stream(stream)), "raf_op_attention_fwd")
+
+
+def raf_op_attention_bwd(desc, dctx, qkv, ctx, lse, seq_lens, dqkv, dvec, step, stream=None):
+    _check(load_library().raf_op_attention_bwd(C.byref(desc), _ptr(dctx), _ptr(qkv), _ptr(ctx), _ptr(lse),
+                                               _ptr(seq_lens), _ptr(dqkv), _ptr(dvec), int(step), _stream(stream)),
+           "raf_op_attention_bwd")
 
 
 def raf_op_dropout_residual_ln_fwd(desc, site, rows, a, res, gamma, beta, out, z_out, mu, rstd, step, stream=None):

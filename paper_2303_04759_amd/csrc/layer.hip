@@ -425,6 +425,30 @@ extern "C" raf_status raf_op_softmax_fwd(const raf_layer_desc* desc, const void*
   return launch_softmax_fwd(*desc, s, seq_lens, prob, prob_d, step, (hipStream_t)hip_stream);
 }
 
+extern "C" raf_status raf_op_attention_fwd(const raf_layer_desc* desc, const void* qkv, const int32_t* seq_lens,
+                                           void* ctx, float* lse, uint64_t step, void* hip_stream) {
+  RAF_TRY(validate_desc(desc));
+  if (!qkv || !ctx || !aligned16(qkv) || !aligned16(ctx) || !aligned16(lse)) return RAF_EINVAL;
+  if (attn_fused_supported(*desc)) return launch_attn_fwd_fused(*desc, qkv, seq_lens, ctx, step, (hipStream_t)hip_stream);
+  if (attn_flash_supported(*desc))
+    return launch_attn_flash_fwd(*desc, qkv, seq_lens, ctx, lse, step, (hipStream_t)hip_stream);
+  return RAF_ENOTSUP;
+}
+
+extern "C" raf_status raf_op_attention_bwd(const raf_layer_desc* desc, const void* dctx, const void* qkv,
+                                           const void* ctx, const float* lse, const int32_t* seq_lens, void* dqkv,
+                                           float* dvec, uint64_t step, void* hip_stream) {
+  RAF_TRY(validate_desc(desc));
+  if (!dctx || !qkv || !dqkv || !aligned16(dctx) || !aligned16(qkv) || !aligned16(dqkv) || !aligned16(ctx) ||
+      !aligned16(lse) || !aligned16(dvec))
+    return RAF_EINVAL;
+  if (attn_fused_supported(*desc))
+    return launch_attn_bwd_full(*desc, dctx, qkv, seq_lens, dqkv, step, (hipStream_t)hip_stream);
+  if (attn_flash_supported(*desc))
+    return launch_attn_flash_bwd(*desc, dctx, qkv, ctx, lse, seq_lens, dqkv, dvec, step, (hipStream_t)hip_stream);
+  return RAF_ENOTSUP;
+}
+
 extern "C" raf_status raf_op_softmax_bwd(const raf_layer_desc* desc, const void* prob, const void* prob_d,
                                          const void* dprob_d, void* ds, float scale_out, void* hip_stream) {
   RAF_TRY(validate_desc(desc));

@@ -192,6 +192,48 @@ def test_softmax_fwd_bwd(precision, B, S, causal, p):
     assert (host(ds)[np.broadcast_to(masked, got.shape)] == 0).all()
 
 
+# -------------------------------------------------------------- attention --
+@pytest.mark.parametrize("B,S,nh,causal,p", [(2, 32, 1, 0, 0.0), (3, 64, 2, 1, 0.1), (3, 96, 3, 0, 0.1),
+                                             (3, 128, 2, 1, 0.2), (3, 160, 2, 0, 0.1), (3, 256, 2, 1, 0.1),
+                                             (2, 416, 1, 1, 0.1), (3, 512, 2, 0, 0.1), (1, 1024, 1, 1, 0.1)])
+def test_attention_core_fwd_bwd(B, S, nh, causal, p):
+    """The on-chip attention kernels (one block of keys for S <= 128, blockwise with running statistics beyond)
+    against the oracle's attention core: context, then dQ | dK | dV, with key padding (a full, a ragged and an
+    empty sequence), causal masks and dropout."""
+    announce("attention", B, S, nh, causal, p)
+    H = 64 * nh
+    cfg = cfg_for(B, S, H, 1, p=p, causal=causal)
+    desc = raf.make_desc(cfg)
+    rng = np.random.default_rng(1000 * S + nh + causal)
+    qkv = rnd(rng, (B * S, 3 * H), 1, 1.5)
+    dctx = rnd(rng, (B * S, H), 1)
+    lens = np.array([S, max(1, S // 3), 0][:B], dtype=np.int32)
+    step = 5
+    bf = torch.bfloat16
+    qkv_d, dctx_d, lens_d = to_dev(qkv, bf), to_dev(dctx, bf), torch.from_numpy(lens).cuda()
+    ctx = torch.full((B * S, H), 7.0, device="cuda", dtype=bf)
+    dqkv = torch.full((B * S, 3 * H), 7.0, device="cuda", dtype=bf)
+    lse = torch.zeros(B * nh * S, device="cuda", dtype=torch.float32)
+    dvec = torch.zeros(B * nh * S, device="cuda", dtype=torch.float32)
+    raf.raf_op_attention_fwd(desc, qkv_d, lens_d, ctx, lse, step)
+    raf.raf_op_attention_bwd(desc, dctx_d, qkv_d, ctx, lse, lens_d, dqkv, dvec, step)
+    torch.cuda.synchronize()
+    ref_c, A = L.attention_core_forward(cfg, qkv, lens, step)
+    ref_dqkv, _ = L.attention_core_backward(cfg, A, dctx)
+    assert rel_fro(host(ctx), ref_c) <= FWD_TOL[1]
+    got = host(dqkv)
+    for blk, name in enumerate(("dQ", "dK", "dV")):
+        g, r = got[:, blk * H:(blk + 1) * H], ref_dqkv[:, blk * H:(blk + 1) * H]
+        assert rel_fro(g, r) <= BWD_TOL[1], name
+    # the empty sequence: no admissible key, so context and every gradient of that sequence are exactly zero
+    if B == 3:
+        assert (host(ctx)[2 * S:] == 0).all() and (got[2 * S:] == 0).all()
+    # keys beyond a sequence's length receive no gradient
+    if B >= 2:
+        L1 = int(lens[1])
+        assert (got[S + L1:2 * S, H:] == 0).all()
+
+
 # -------------------------------------------------------------- layernorm --
 @pytest.mark.parametrize("precision", [0, 1])
 @pytest.mark.parametrize("rows,H,p", [(64, 128, 0.0), (100, 768, 0.1), (37, 1024, 0.1), (9, 2048, 0.3), (5, 4096, 0.1),
