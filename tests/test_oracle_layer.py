@@ -204,6 +204,48 @@ def test_pieces_against_library_routines():
     assert np.allclose(pr, torch.softmax(torch.from_numpy(s), -1).numpy(), rtol=1e-12)
 
 
+@pytest.mark.parametrize("causal,with_lens", [(0, False), (1, False), (0, True), (1, True)])
+def test_attention_core_against_library_attention(causal, with_lens):
+    """attention_core_forward / _backward against torch's scaled_dot_product_attention (library routine, its own
+    autograd) without dropout, and with dropout against autograd through an independently typed forward that takes
+    the same keep mask."""
+    B, S, nh, dh = 2, 12, 2, 64
+    H = nh * dh
+    cfg = micro_cfg(batch=B, seq=S, hidden=H, heads=nh, ffn=4 * H, causal=causal, dropout_p=0.0)
+    rng = np.random.default_rng(5 + causal)
+    qkv = rng.standard_normal((B * S, 3 * H))
+    dc = rng.standard_normal((B * S, H))
+    lens = np.array([S, 7], dtype=np.int32) if with_lens else None
+    c, A = L.attention_core_forward(cfg, qkv, lens, step=3)
+    dqkv, _ = L.attention_core_backward(cfg, A, dc)
+    t = torch.tensor(qkv, requires_grad=True)
+    q, k, v = [t[:, i * H:(i + 1) * H].reshape(B, S, nh, dh).permute(0, 2, 1, 3) for i in range(3)]
+    allowed = torch.ones(B, 1, S, S, dtype=torch.bool)
+    if with_lens:
+        allowed = allowed & (torch.arange(S)[None, None, None, :] < torch.from_numpy(lens.astype(np.int64))[:, None, None, None])
+    if causal:
+        allowed = allowed & torch.ones(S, S, dtype=torch.bool).tril()
+    o = torch.nn.functional.scaled_dot_product_attention(q, k, v, attn_mask=allowed)
+    tc = o.permute(0, 2, 1, 3).reshape(B * S, H)
+    (tc * torch.from_numpy(dc)).sum().backward()
+    assert np.allclose(c, tc.detach().numpy(), rtol=1e-10, atol=1e-12)
+    assert np.allclose(dqkv, t.grad.numpy(), rtol=1e-9, atol=1e-11)
+    # dropout at site 1: same keep mask fed to an independent forward
+    cfg_d = dict(cfg, dropout_p=0.25)
+    c2, A2 = L.attention_core_forward(cfg_d, qkv, lens, step=3)
+    dqkv2, _ = L.attention_core_backward(cfg_d, A2, dc)
+    keep = torch.from_numpy(dropout_keep(cfg_d["seed"], cfg_d["layer_id"], 1, 3, B * nh * S * S, 0.25)
+                            .reshape(B, nh, S, S).astype(np.float64))
+    t2 = torch.tensor(qkv, requires_grad=True)
+    q, k, v = [t2[:, i * H:(i + 1) * H].reshape(B, S, nh, dh).permute(0, 2, 1, 3) for i in range(3)]
+    sc = torch.matmul(q, k.transpose(-1, -2)) / dh ** 0.5
+    pr = torch.softmax(sc.masked_fill(~allowed, float("-inf")), dim=-1)
+    tc2 = torch.matmul(pr * keep / 0.75, v).permute(0, 2, 1, 3).reshape(B * S, H)
+    (tc2 * torch.from_numpy(dc)).sum().backward()
+    assert np.allclose(c2, tc2.detach().numpy(), rtol=1e-10, atol=1e-12)
+    assert np.allclose(dqkv2, t2.grad.numpy(), rtol=1e-9, atol=1e-11)
+
+
 def test_softmax_invariants_and_masking():
     cfg = micro_cfg(batch=3, seq=12, hidden=16, heads=2, causal=0)
     params, x, G = rand_problem(cfg, seed=2)
