@@ -200,7 +200,9 @@ def main():
     valid_tokens = int(np.sum(inp["seq_lens"])) if inp["seq_lens"] is not None else lay.T
     total_flops = sum(2.0 * M * N * Kd * b for (_, M, N, Kd, _a, _b, _f, _e, b) in gemm_launches(cfg))
     out = {
-        "metric": "train samples/sec, BERT-base layer fwd+bwd+Adam (bf16 AMP, 1 GPU)",
+        "metric": "train samples/sec, %s layer fwd+bwd+Adam (%s, 1 GPU)" %
+                  ({"bert_base": "BERT-base", "bert_large": "BERT-large", "gpt2_medium": "GPT-2-medium"}.get(
+                      args.workload, args.workload), "bf16 AMP" if cfg["precision"] == 1 else "fp32"),
         "value": samples_per_s, "unit": "samples/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg["precision"] == 1 else "f32", "data": "synthetic",
