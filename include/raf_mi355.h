@@ -148,6 +148,44 @@ typedef struct {
 raf_status raf_adam_step(const raf_adam_tensor *list, int32_t count, double lr, double beta1, double beta2,
                          double eps, double weight_decay, int64_t t, double inv_loss_scale, void *hip_stream);
 
+/* ---- Dynamic loss scaling with a non-finite skip (mixed precision applied by the
+ * system, Section 3.1.2; the paper's float16 AMP runs of Section 5.1 need it).
+ * The paper prints no rule; this is the standard one: the loss gradient is
+ * multiplied by the scale; if any gradient of the step is non-finite the optimizer
+ * step is skipped and the scale multiplied by backoff_factor, otherwise the step is
+ * taken on gradients divided by the scale and after growth_interval consecutive
+ * good steps the scale is multiplied by growth_factor.  Every decision is taken on
+ * the device from this state, so a captured step replays correctly:
+ *   raf_loss_seed_scaled -> raf_layer_bwd ... -> raf_grads_check ->
+ *   raf_adam_step_scaled -> raf_scaler_update.
+ * The state lives in device memory (16-byte aligned); read it back with a copy. */
+typedef struct {
+  float scale;          /* current loss scale                                   */
+  float inv_scale;      /* 1/scale                                              */
+  int32_t good_steps;   /* consecutive steps without a non-finite gradient      */
+  int32_t found_inf;    /* set by raf_grads_check, cleared by raf_scaler_update */
+  int64_t t;            /* optimizer steps taken so far (skipped ones excluded) */
+  float lr_over_bc1;    /* Adam constants of step t+1, written by               */
+  float inv_bc2;        /*   raf_adam_step_scaled                               */
+} raf_scaler_state;
+
+/* state [dev] written: scale = init_scale (> 0, finite), counters zero. */
+raf_status raf_scaler_init(raf_scaler_state *state, float init_scale, void *hip_stream);
+/* raf_loss_seed with loss_scale read from state->scale on the device. */
+raf_status raf_loss_seed_scaled(int32_t precision, const void *y, const void *G, int64_t n,
+                                const raf_scaler_state *state, float *loss_out, void *dy, float *partial,
+                                void *hip_stream);
+/* state->found_inf = 1 if any element of any list[i].grad is inf or nan (it is not cleared here). */
+raf_status raf_grads_check(const raf_adam_tensor *list, int32_t count, raf_scaler_state *state, void *hip_stream);
+/* raf_adam_step with t = state->t + 1 and inv_loss_scale = state->inv_scale, both read on the
+ * device; a no-op on every tensor when state->found_inf is set. */
+raf_status raf_adam_step_scaled(const raf_adam_tensor *list, int32_t count, double lr, double beta1, double beta2,
+                                double eps, double weight_decay, raf_scaler_state *state, void *hip_stream);
+/* The scale rule above; also advances state->t on a good step and clears found_inf.
+ * growth_factor >= 1, 0 < backoff_factor <= 1, growth_interval >= 1. */
+raf_status raf_scaler_update(raf_scaler_state *state, float growth_factor, float backoff_factor,
+                             int32_t growth_interval, void *hip_stream);
+
 /* Test hook: the keep-mask of one dropout site as bytes (1 = kept).
  *   mask_out [dev] uint8[n]; element order is the site's flat index. */
 raf_status raf_debug_dropout_mask(const raf_layer_desc *desc, int32_t site, uint64_t step, uint8_t *mask_out,

@@ -64,6 +64,12 @@ class AdamTensor(C.Structure):
                 ("lowp", C.c_void_p), ("n", C.c_int64)]
 
 
+class ScalerState(C.Structure):
+    """Device-resident state of the dynamic loss scaler (raf_scaler_state): 32 bytes."""
+    _fields_ = [("scale", C.c_float), ("inv_scale", C.c_float), ("good_steps", C.c_int32), ("found_inf", C.c_int32),
+                ("t", C.c_int64), ("lr_over_bc1", C.c_float), ("inv_bc2", C.c_float)]
+
+
 _lib = None
 
 _SIGNATURES = {
@@ -76,6 +82,13 @@ _SIGNATURES = {
                                 C.c_void_p, C.c_void_p]),
     "raf_adam_step": (C.c_int, [C.POINTER(AdamTensor), C.c_int32, C.c_double, C.c_double, C.c_double, C.c_double,
                                 C.c_double, C.c_int64, C.c_double, C.c_void_p]),
+    "raf_scaler_init": (C.c_int, [C.c_void_p, C.c_float, C.c_void_p]),
+    "raf_loss_seed_scaled": (C.c_int, [C.c_int32, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+                                       C.c_void_p, C.c_void_p, C.c_void_p]),
+    "raf_grads_check": (C.c_int, [C.POINTER(AdamTensor), C.c_int32, C.c_void_p, C.c_void_p]),
+    "raf_adam_step_scaled": (C.c_int, [C.POINTER(AdamTensor), C.c_int32, C.c_double, C.c_double, C.c_double,
+                                       C.c_double, C.c_double, C.c_void_p, C.c_void_p]),
+    "raf_scaler_update": (C.c_int, [C.c_void_p, C.c_float, C.c_float, C.c_int32, C.c_void_p]),
     "raf_debug_dropout_mask": (C.c_int, [C.POINTER(LayerDesc), C.c_int32, C.c_uint64, C.c_void_p, C.c_int64,
                                          C.c_void_p]),
     "raf_embed_workspace": (C.c_int, [C.POINTER(EmbedDesc), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]),
@@ -199,6 +212,38 @@ def raf_layer_bwd(desc, w, x, dy, seq_lens, saved, dx, grads, scratch, step, str
 def raf_loss_seed(precision, y, G, n, loss_scale, loss_out, dy, partial, stream=None):
     _check(load_library().raf_loss_seed(int(precision), _ptr(y), _ptr(G), int(n), float(loss_scale), _ptr(loss_out),
                                         _ptr(dy), _ptr(partial), _stream(stream)), "raf_loss_seed")
+
+
+def raf_scaler_init(state, init_scale, stream=None):
+    """state: a device buffer of at least ctypes.sizeof(ScalerState) bytes."""
+    _check(load_library().raf_scaler_init(_ptr(state), float(init_scale), _stream(stream)), "raf_scaler_init")
+
+
+def raf_loss_seed_scaled(precision, y, G, n, state, loss_out, dy, partial, stream=None):
+    _check(load_library().raf_loss_seed_scaled(int(precision), _ptr(y), _ptr(G), int(n), _ptr(state), _ptr(loss_out),
+                                               _ptr(dy), _ptr(partial), _stream(stream)), "raf_loss_seed_scaled")
+
+
+def raf_grads_check(adam_list, count, state, stream=None):
+    _check(load_library().raf_grads_check(adam_list, int(count), _ptr(state), _stream(stream)), "raf_grads_check")
+
+
+def raf_adam_step_scaled(adam_list, count, lr, beta1, beta2, eps, weight_decay, state, stream=None):
+    _check(load_library().raf_adam_step_scaled(adam_list, int(count), float(lr), float(beta1), float(beta2),
+                                               float(eps), float(weight_decay), _ptr(state), _stream(stream)),
+           "raf_adam_step_scaled")
+
+
+def raf_scaler_update(state, growth_factor, backoff_factor, growth_interval, stream=None):
+    _check(load_library().raf_scaler_update(_ptr(state), float(growth_factor), float(backoff_factor),
+                                            int(growth_interval), _stream(stream)), "raf_scaler_update")
+
+
+def read_scaler_state(state):
+    """Copies the device state to the host (synchronises) and returns it as a dict."""
+    raw = bytes(state[:C.sizeof(ScalerState)].cpu().numpy().tobytes())
+    st = ScalerState.from_buffer_copy(raw)
+    return dict(scale=st.scale, inv_scale=st.inv_scale, good_steps=st.good_steps, found_inf=st.found_inf, t=st.t)
 
 
 def make_adam_list(entries):

@@ -31,7 +31,15 @@ __device__ __forceinline__ void adam_update(float& w, float g, float& m, float& 
   w = w - h.lr_over_bc1 * m / (sqrtf(v * h.inv_bc2) + h.eps);
 }
 
-__global__ __launch_bounds__(256) void adam_kernel(AdamTable tab, AdamHyper h) {
+// dyn != nullptr: step count and loss scale come from the device-resident scaler state, and the whole launch is a
+// no-op when the step's gradients held a non-finite value
+__global__ __launch_bounds__(256) void adam_kernel(AdamTable tab, AdamHyper h, const raf_scaler_state* __restrict__ dyn) {
+  if (dyn) {
+    if (dyn->found_inf) return;
+    h.inv_scale = dyn->inv_scale;
+    h.lr_over_bc1 = dyn->lr_over_bc1;
+    h.inv_bc2 = dyn->inv_bc2;
+  }
   int ti = 0;
   while (ti + 1 < tab.count && (int)blockIdx.x >= tab.block_start[ti + 1]) ++ti;
   const long n = tab.n[ti];
@@ -78,9 +86,10 @@ __global__ __launch_bounds__(256) void adam_kernel(AdamTable tab, AdamHyper h) {
 // ------------------------------------------------------------- loss seed --
 template <typename T>
 __global__ __launch_bounds__(256) void loss_seed_kernel(const T* __restrict__ y, const T* __restrict__ G, long n,
-                                                        float loss_scale, T* __restrict__ dy,
-                                                        float* __restrict__ partial) {
+                                                        float loss_scale, const float* __restrict__ scale_ptr,
+                                                        T* __restrict__ dy, float* __restrict__ partial) {
   __shared__ float red[4];
+  if (scale_ptr) loss_scale = *scale_ptr;   // dynamic loss scale, device-resident
   float acc = 0.f;
   for (long i = ((long)blockIdx.x * 256 + threadIdx.x) * 8; i < n; i += (long)gridDim.x * 256 * 8) {
     float a[8], g[8];
@@ -119,6 +128,69 @@ raf_status launch_sum_partials(const float* partial, int nparts, float* out, hip
   return check_launch();
 }
 
+// -------------------------------------------------- dynamic loss scale ---
+__global__ void scaler_init_kernel(raf_scaler_state* st, float scale) {
+  st->scale = scale;
+  st->inv_scale = 1.0f / scale;
+  st->good_steps = 0;
+  st->found_inf = 0;
+  st->t = 0;
+  st->lr_over_bc1 = 0.f;
+  st->inv_bc2 = 0.f;
+}
+
+// one chunk of one gradient tensor per block (the Adam partition); any non-finite element raises the flag
+__global__ __launch_bounds__(256) void grads_check_kernel(AdamTable tab, raf_scaler_state* st) {
+  int ti = 0;
+  while (ti + 1 < tab.count && (int)blockIdx.x >= tab.block_start[ti + 1]) ++ti;
+  const long n = tab.n[ti];
+  const float* __restrict__ G = tab.grad[ti];
+  const long base = (long)(blockIdx.x - tab.block_start[ti]) * ADAM_CHUNK;
+  bool bad = false;
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const long i = base + ((long)it * 256 + threadIdx.x) * 4;
+    if (i + 3 < n) {
+      const float4 g = *reinterpret_cast<const float4*>(G + i);
+      // x - x is 0 for finite x and nan for inf and nan
+      bad |= !((g.x - g.x) + (g.y - g.y) + (g.z - g.z) + (g.w - g.w) == 0.f);
+    } else {
+      for (long j = i; j < n && j < i + 4; ++j) bad |= !(G[j] - G[j] == 0.f);
+    }
+  }
+  if (__any(bad) && (threadIdx.x & 63) == 0) st->found_inf = 1;   // every writer stores the same value
+}
+
+// Adam's step-dependent constants for step t + 1, formed in double like the host does for the static entry point
+__global__ void adam_prepare_kernel(raf_scaler_state* st, double lr, double beta1, double beta2) {
+  if (st->found_inf) return;
+  const double t = (double)(st->t + 1);
+  const double bc1 = 1.0 - pow(beta1, t);
+  const double bc2 = 1.0 - pow(beta2, t);
+  st->lr_over_bc1 = (float)(lr / bc1);
+  st->inv_bc2 = (float)(1.0 / bc2);
+}
+
+__global__ void scaler_update_kernel(raf_scaler_state* st, float growth, float backoff, int interval) {
+  float scale = st->scale;
+  if (st->found_inf) {
+    scale *= backoff;
+    st->good_steps = 0;
+  } else {
+    st->t += 1;
+    const int good = st->good_steps + 1;
+    if (good == interval) {
+      scale *= growth;
+      st->good_steps = 0;
+    } else {
+      st->good_steps = good;
+    }
+  }
+  st->scale = scale;
+  st->inv_scale = 1.0f / scale;
+  st->found_inf = 0;
+}
+
 // ------------------------------------------------------- mask test hook ---
 __global__ __launch_bounds__(256) void dropout_mask_kernel(uint8_t* __restrict__ out, long n, DropSite drop) {
   const long i8 = ((long)blockIdx.x * 256 + threadIdx.x) * 8;
@@ -137,11 +209,14 @@ __global__ __launch_bounds__(256) void dropout_mask_kernel(uint8_t* __restrict__
 
 using namespace raf;
 
-extern "C" raf_status raf_adam_step(const raf_adam_tensor* list, int32_t count, double lr, double beta1, double beta2,
-                                    double eps, double weight_decay, int64_t t, double inv_loss_scale,
-                                    void* hip_stream) {
+#define RAF_TRY(expr)                \
+  do {                               \
+    const raf_status _rc = (expr);   \
+    if (_rc != RAF_OK) return _rc;   \
+  } while (0)
+
+static raf_status check_adam_list(const raf_adam_tensor* list, int32_t count) {
   if (count < 0 || (count > 0 && !list)) return RAF_EINVAL;
-  if (t < 1 || !(beta1 >= 0.0 && beta1 < 1.0) || !(beta2 >= 0.0 && beta2 < 1.0)) return RAF_EINVAL;
   for (int i = 0; i < count; ++i) {
     const raf_adam_tensor& a = list[i];
     if (a.n < 0) return RAF_EINVAL;
@@ -150,19 +225,13 @@ extern "C" raf_status raf_adam_step(const raf_adam_tensor* list, int32_t count, 
     if (!aligned16(a.master) || !aligned16(a.grad) || !aligned16(a.m) || !aligned16(a.v) || !aligned16(a.lowp))
       return RAF_EINVAL;
   }
-  AdamHyper h;
-  const double bc1 = 1.0 - pow(beta1, (double)t);
-  const double bc2 = 1.0 - pow(beta2, (double)t);
-  h.lr_over_bc1 = (float)(lr / bc1);
-  h.inv_bc2 = (float)(1.0 / bc2);
-  h.beta1 = (float)beta1;
-  h.beta2 = (float)beta2;
-  h.one_minus_beta1 = (float)(1.0 - beta1);
-  h.one_minus_beta2 = (float)(1.0 - beta2);
-  h.eps = (float)eps;
-  h.weight_decay = (float)weight_decay;
-  h.inv_scale = (float)inv_loss_scale;
-  hipStream_t st = (hipStream_t)hip_stream;
+  return RAF_OK;
+}
+
+// Splits the list into kernel-argument tables of at most ADAM_MAX_TENSORS tensors, one chunk of one tensor per
+// block, and calls launch(table, blocks) for each.
+template <typename F>
+static raf_status for_each_adam_table(const raf_adam_tensor* list, int32_t count, F&& launch) {
   int i = 0;
   while (i < count) {
     AdamTable tab;
@@ -181,31 +250,111 @@ extern "C" raf_status raf_adam_step(const raf_adam_tensor* list, int32_t count, 
     }
     if (tab.count == 0) continue;
     tab.block_start[tab.count] = (int)blocks;
-    hipLaunchKernelGGL(adam_kernel, dim3((unsigned)blocks), dim3(256), 0, st, tab, h);
+    launch(tab, (unsigned)blocks);
     raf_status rc = check_launch();
     if (rc != RAF_OK) return rc;
   }
   return RAF_OK;
 }
 
-extern "C" raf_status raf_loss_seed(int32_t precision, const void* y, const void* G, int64_t n, float loss_scale,
-                                    float* loss_out, void* dy, float* partial, void* hip_stream) {
+static AdamHyper adam_constants(double beta1, double beta2, double eps, double weight_decay) {
+  AdamHyper h{};
+  h.beta1 = (float)beta1;
+  h.beta2 = (float)beta2;
+  h.one_minus_beta1 = (float)(1.0 - beta1);
+  h.one_minus_beta2 = (float)(1.0 - beta2);
+  h.eps = (float)eps;
+  h.weight_decay = (float)weight_decay;
+  return h;
+}
+
+extern "C" raf_status raf_adam_step(const raf_adam_tensor* list, int32_t count, double lr, double beta1, double beta2,
+                                    double eps, double weight_decay, int64_t t, double inv_loss_scale,
+                                    void* hip_stream) {
+  RAF_TRY(check_adam_list(list, count));
+  if (t < 1 || !(beta1 >= 0.0 && beta1 < 1.0) || !(beta2 >= 0.0 && beta2 < 1.0)) return RAF_EINVAL;
+  AdamHyper h = adam_constants(beta1, beta2, eps, weight_decay);
+  const double bc1 = 1.0 - pow(beta1, (double)t);
+  const double bc2 = 1.0 - pow(beta2, (double)t);
+  h.lr_over_bc1 = (float)(lr / bc1);
+  h.inv_bc2 = (float)(1.0 / bc2);
+  h.inv_scale = (float)inv_loss_scale;
+  hipStream_t st = (hipStream_t)hip_stream;
+  return for_each_adam_table(list, count, [&](const AdamTable& tab, unsigned blocks) {
+    hipLaunchKernelGGL(adam_kernel, dim3(blocks), dim3(256), 0, st, tab, h, (const raf_scaler_state*)nullptr);
+  });
+}
+
+extern "C" raf_status raf_scaler_init(raf_scaler_state* state, float init_scale, void* hip_stream) {
+  if (!state || !aligned16(state) || !(init_scale > 0.f) || !(init_scale <= 3.0e38f)) return RAF_EINVAL;
+  hipLaunchKernelGGL(scaler_init_kernel, dim3(1), dim3(1), 0, (hipStream_t)hip_stream, state, init_scale);
+  return check_launch();
+}
+
+extern "C" raf_status raf_grads_check(const raf_adam_tensor* list, int32_t count, raf_scaler_state* state,
+                                      void* hip_stream) {
+  RAF_TRY(check_adam_list(list, count));
+  if (!state || !aligned16(state)) return RAF_EINVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  return for_each_adam_table(list, count, [&](const AdamTable& tab, unsigned blocks) {
+    hipLaunchKernelGGL(grads_check_kernel, dim3(blocks), dim3(256), 0, st, tab, state);
+  });
+}
+
+extern "C" raf_status raf_adam_step_scaled(const raf_adam_tensor* list, int32_t count, double lr, double beta1,
+                                           double beta2, double eps, double weight_decay, raf_scaler_state* state,
+                                           void* hip_stream) {
+  RAF_TRY(check_adam_list(list, count));
+  if (!state || !aligned16(state)) return RAF_EINVAL;
+  if (!(beta1 >= 0.0 && beta1 < 1.0) || !(beta2 >= 0.0 && beta2 < 1.0)) return RAF_EINVAL;
+  const AdamHyper h = adam_constants(beta1, beta2, eps, weight_decay);
+  hipStream_t st = (hipStream_t)hip_stream;
+  hipLaunchKernelGGL(adam_prepare_kernel, dim3(1), dim3(1), 0, st, state, lr, beta1, beta2);
+  RAF_TRY(check_launch());
+  return for_each_adam_table(list, count, [&](const AdamTable& tab, unsigned blocks) {
+    hipLaunchKernelGGL(adam_kernel, dim3(blocks), dim3(256), 0, st, tab, h, (const raf_scaler_state*)state);
+  });
+}
+
+extern "C" raf_status raf_scaler_update(raf_scaler_state* state, float growth_factor, float backoff_factor,
+                                        int32_t growth_interval, void* hip_stream) {
+  if (!state || !aligned16(state)) return RAF_EINVAL;
+  if (!(growth_factor >= 1.f) || !(backoff_factor > 0.f && backoff_factor <= 1.f) || growth_interval < 1)
+    return RAF_EINVAL;
+  hipLaunchKernelGGL(scaler_update_kernel, dim3(1), dim3(1), 0, (hipStream_t)hip_stream, state, growth_factor,
+                     backoff_factor, growth_interval);
+  return check_launch();
+}
+
+static raf_status loss_seed_impl(int32_t precision, const void* y, const void* G, int64_t n, float loss_scale,
+                                 const float* scale_ptr, float* loss_out, void* dy, float* partial, hipStream_t st) {
   if (!y || !G || !loss_out || !dy || !partial || n <= 0 || (n % 8)) return RAF_EINVAL;
   if (!aligned16(y) || !aligned16(G) || !aligned16(dy)) return RAF_EINVAL;
   if (precision != RAF_F32 && precision != RAF_BF16_AMP) return RAF_EINVAL;
-  hipStream_t st = (hipStream_t)hip_stream;
   long nb = (n / 8 + 255) / 256;
   if (nb > RAF_LOSS_PARTIALS) nb = RAF_LOSS_PARTIALS;
   if (precision == RAF_F32)
     hipLaunchKernelGGL((loss_seed_kernel<float>), dim3(nb), dim3(256), 0, st, (const float*)y, (const float*)G,
-                       (long)n, loss_scale, (float*)dy, partial);
+                       (long)n, loss_scale, scale_ptr, (float*)dy, partial);
   else
     hipLaunchKernelGGL((loss_seed_kernel<bf16_t>), dim3(nb), dim3(256), 0, st, (const bf16_t*)y, (const bf16_t*)G,
-                       (long)n, loss_scale, (bf16_t*)dy, partial);
+                       (long)n, loss_scale, scale_ptr, (bf16_t*)dy, partial);
   raf_status rc = check_launch();
   if (rc != RAF_OK) return rc;
   hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(256), 0, st, partial, (int)nb, loss_out);
   return check_launch();
+}
+
+extern "C" raf_status raf_loss_seed(int32_t precision, const void* y, const void* G, int64_t n, float loss_scale,
+                                    float* loss_out, void* dy, float* partial, void* hip_stream) {
+  return loss_seed_impl(precision, y, G, n, loss_scale, nullptr, loss_out, dy, partial, (hipStream_t)hip_stream);
+}
+
+extern "C" raf_status raf_loss_seed_scaled(int32_t precision, const void* y, const void* G, int64_t n,
+                                           const raf_scaler_state* state, float* loss_out, void* dy, float* partial,
+                                           void* hip_stream) {
+  if (!state || !aligned16(state)) return RAF_EINVAL;
+  return loss_seed_impl(precision, y, G, n, 1.0f, &state->scale, loss_out, dy, partial, (hipStream_t)hip_stream);
 }
 
 extern "C" raf_status raf_debug_dropout_mask(const raf_layer_desc* desc, int32_t site, uint64_t step,

@@ -6,7 +6,8 @@ import numpy as np
 import torch
 
 from . import (PARAM_NAMES, RAF_BF16_AMP, RAF_LOSS_PARTIALS, make_adam_list, make_desc, make_tensors,
-               raf_adam_step, raf_layer_bwd, raf_layer_fwd, raf_layer_workspace, raf_loss_seed)
+               raf_adam_step, raf_adam_step_scaled, raf_grads_check, raf_layer_bwd, raf_layer_fwd,
+               raf_layer_workspace, raf_loss_seed, raf_loss_seed_scaled, raf_scaler_update)
 
 
 class DeviceLayer:
@@ -65,6 +66,20 @@ class DeviceLayer:
         a = self.adam
         raf_adam_step(self.adam_list, self.adam_count, a["lr"], a["beta1"], a["beta2"], a["eps"],
                       a.get("weight_decay", 0.0), t, 1.0 / self.cfg["loss_scale"], stream)
+
+    def train_step_dynamic(self, step, state, scaler, stream=None):
+        """The same pass under the dynamic loss scaler: every decision (scale, skip, Adam's step count) is taken on
+        the device from `state` (a device byte buffer initialised with raf_scaler_init).  `step` only numbers the
+        dropout masks."""
+        a = self.adam
+        self.fwd(step, stream)
+        raf_loss_seed_scaled(self.cfg["precision"], self.y, self.G, self.y.numel(), state, self.loss, self.dy,
+                             self.partial, stream)
+        self.bwd(step, stream)
+        raf_grads_check(self.adam_list, self.adam_count, state, stream)
+        raf_adam_step_scaled(self.adam_list, self.adam_count, a["lr"], a["beta1"], a["beta2"], a["eps"],
+                             a.get("weight_decay", 0.0), state, stream)
+        raf_scaler_update(state, scaler["growth_factor"], scaler["backoff_factor"], scaler["growth_interval"], stream)
 
     def train_step(self, t, stream=None):
         """forward, loss seed, backward, Adam: one pass of the whole hot path."""
