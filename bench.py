@@ -107,6 +107,8 @@ def main():
     ap.add_argument("--workload", default="bert_base")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline leg")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--dynamic-loss-scale", action="store_true",
+                    help="time the step under the device-resident dynamic loss scaler (layer workloads)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (5x) so FETCH_SIZE/WRITE_SIZE counters can be scaled")
     args = ap.parse_args()
@@ -129,18 +131,28 @@ def main():
     stream = torch.cuda.Stream()          # default priority
     K, W = args.steps, args.warmup
 
+    if args.dynamic_loss_scale:
+        import ctypes
+        scaler_state = torch.zeros(ctypes.sizeof(raf.ScalerState), dtype=torch.uint8, device="cuda")
+        raf.raf_scaler_init(scaler_state, cfg["loss_scale"])
+        torch.cuda.synchronize()
+        scaler_cfg = dict(growth_factor=2.0, backoff_factor=0.5, growth_interval=2000)
+        one_step = lambda t, st: lay.train_step_dynamic(t, scaler_state, scaler_cfg, st)
+    else:
+        one_step = lambda t, st: lay.train_step(t, st)
+
     with torch.cuda.stream(stream):
         graph = None
         t_step = 1
         for _ in range(max(W, 1)):
-            lay.train_step(t_step, stream)
+            one_step(t_step, stream)
             t_step += 1
         stream.synchronize()
         if not args.no_graph:
             # one HIP graph of the whole step; replays re-run the same kernels on the same buffers
             graph = torch.cuda.CUDAGraph()
             with torch.cuda.graph(graph, stream=stream):
-                lay.train_step(t_step, stream)
+                one_step(t_step, stream)
             for _ in range(3):
                 graph.replay()
             stream.synchronize()
@@ -152,7 +164,7 @@ def main():
             if graph is not None:
                 graph.replay()
             else:
-                lay.train_step(t_step, stream)
+                one_step(t_step, stream)
                 t_step += 1
         e1.record(stream)
         torch.cuda.synchronize()
@@ -208,7 +220,8 @@ def main():
         "dtype": "bf16" if cfg["precision"] == 1 else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "batch": cfg["batch"], "seq_len": cfg["seq"], "hidden": cfg["hidden"],
                    "heads": cfg["heads"], "ffn": cfg["ffn"], "dropout_p": cfg["dropout_p"],
-                   "launch": "eager" if graph is None else "hip_graph", "parallelism": "single GPU"},
+                   "launch": "eager" if graph is None else "hip_graph", "parallelism": "single GPU",
+                   "loss_scale": "dynamic" if args.dynamic_loss_scale else "static"},
         "tokens_per_s_padded": lay.T / (ms_per_step * 1e-3),
         "tokens_per_s_valid": valid_tokens / (ms_per_step * 1e-3),
         "step_gemm_tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
