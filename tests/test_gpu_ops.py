@@ -195,7 +195,8 @@ def test_softmax_fwd_bwd(precision, B, S, causal, p):
 # -------------------------------------------------------------- attention --
 @pytest.mark.parametrize("B,S,nh,causal,p", [(2, 32, 1, 0, 0.0), (3, 64, 2, 1, 0.1), (3, 96, 3, 0, 0.1),
                                              (3, 128, 2, 1, 0.2), (3, 160, 2, 0, 0.1), (3, 256, 2, 1, 0.1),
-                                             (2, 416, 1, 1, 0.1), (3, 512, 2, 0, 0.1), (1, 1024, 1, 1, 0.1)])
+                                             (2, 416, 1, 1, 0.1), (3, 512, 2, 0, 0.1), (1, 1024, 1, 1, 0.1),
+                                             (2, 2048, 1, 0, 0.1), (1, 4096, 1, 1, 0.0)])
 def test_attention_core_fwd_bwd(B, S, nh, causal, p):
     """The on-chip attention kernels (one block of keys for S <= 128, blockwise with running statistics beyond)
     against the oracle's attention core: context, then dQ | dK | dV, with key padding (a full, a ragged and an
