@@ -54,6 +54,15 @@ struct Vec8<float> {
   }
   // value as it will read back from storage
   static __device__ __forceinline__ float round(float v) { return v; }
+  // 8 elements as loaded, converted to float later (lets a kernel request the next row before it works on this one)
+  struct Raw { float4 a, b; };
+  static __device__ __forceinline__ Raw load_raw(const float* p) {
+    return Raw{*reinterpret_cast<const float4*>(p), *reinterpret_cast<const float4*>(p + 4)};
+  }
+  static __device__ __forceinline__ void unpack(const Raw& r, float (&o)[8]) {
+    o[0] = r.a.x; o[1] = r.a.y; o[2] = r.a.z; o[3] = r.a.w;
+    o[4] = r.b.x; o[5] = r.b.y; o[6] = r.b.z; o[7] = r.b.w;
+  }
 };
 
 template <>
@@ -74,6 +83,14 @@ struct Vec8<bf16_t> {
     *reinterpret_cast<uint4*>(p) = r;
   }
   static __device__ __forceinline__ float round(float v) { return (float)(__bf16)v; }
+  typedef uint4 Raw;
+  static __device__ __forceinline__ Raw load_raw(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
+  static __device__ __forceinline__ void unpack(const Raw& r, float (&o)[8]) {
+    o[0] = bf16_bits_to_f32(r.x & 0xffffu); o[1] = __uint_as_float(r.x & 0xffff0000u);
+    o[2] = bf16_bits_to_f32(r.y & 0xffffu); o[3] = __uint_as_float(r.y & 0xffff0000u);
+    o[4] = bf16_bits_to_f32(r.z & 0xffffu); o[5] = __uint_as_float(r.z & 0xffff0000u);
+    o[6] = bf16_bits_to_f32(r.w & 0xffffu); o[7] = __uint_as_float(r.w & 0xffff0000u);
+  }
 };
 
 __device__ __forceinline__ void load8f(const float* p, float (&o)[8]) { Vec8<float>::load(p, o); }

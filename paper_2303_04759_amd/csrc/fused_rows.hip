@@ -211,7 +211,7 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ a, co
 // sums for dgamma, dbeta and dbias in registers; a block reduces them through
 // LDS and writes one partial row; a second kernel sums the partial rows in a
 // fixed order, so the result does not depend on scheduling.
-constexpr int LN_BWD_MAX_BLOCKS = 512;
+constexpr int LN_BWD_MAX_BLOCKS = 256;
 constexpr int LN_BWD_THREADS = 256;
 
 template <typename T, int LPR, int NV, bool HAS_LN>
@@ -238,24 +238,48 @@ __global__ __launch_bounds__(LN_BWD_THREADS) void ln_bwd_kernel(const T* __restr
     if (HAS_LN && vec < nvec) load8f(gamma + vec * 8, gm[t]);
   }
 
-  for (long row = group; row < nrows; row += ngroups) {
-    float g[NV][8], xh[NV][8], res[NV][8];   // res: requested with the other operands, used after the row sums
-    float s1 = 0.f, s2 = 0.f;
-    float mean = 0.f, rs = 0.f;
+  // The operands of a row are requested one row ahead (kept as loaded, converted when used), so that the loads of the
+  // next row overlap the arithmetic and the stores of this one.
+  typedef typename Vec8<T>::Raw Raw;
+  struct RowIn {
+    Raw g[NV], g2[NV], z[NV], res[NV];
+    float mean, rs;
+  };
+  auto request = [&](long row, RowIn& in) {
+    in.mean = in.rs = 0.f;
     if (HAS_LN) {
-      mean = mu[row];
-      rs = rstd[row];
+      in.mean = mu[row];
+      in.rs = rstd[row];
     }
 #pragma unroll
     for (int t = 0; t < NV; ++t) {
       const int vec = lane + LPR * t;
       if (vec < nvec) {
         const long off = row * H + vec * 8;
-        Vec8<T>::load(dout + off, g[t]);
-        if (dres) Vec8<T>::load(dres + off, res[t]);
+        in.g[t] = Vec8<T>::load_raw(dout + off);
+        if (dout2) in.g2[t] = Vec8<T>::load_raw(dout2 + off);
+        if (HAS_LN) in.z[t] = Vec8<T>::load_raw(z + off);
+        if (dres) in.res[t] = Vec8<T>::load_raw(dres + off);
+      }
+    }
+  };
+  RowIn cur, nxt;
+  if (group < nrows) request(group, cur);
+  for (long row = group; row < nrows; row += ngroups) {
+    const bool more = row + ngroups < nrows;
+    if (more) request(row + ngroups, nxt);
+    float g[NV][8], xh[NV][8];
+    float s1 = 0.f, s2 = 0.f;
+    const float mean = cur.mean, rs = cur.rs;
+#pragma unroll
+    for (int t = 0; t < NV; ++t) {
+      const int vec = lane + LPR * t;
+      if (vec < nvec) {
+        const long off = row * H + vec * 8;
+        Vec8<T>::unpack(cur.g[t], g[t]);
         if (dout2) {
           float g2[8];
-          Vec8<T>::load(dout2 + off, g2);
+          Vec8<T>::unpack(cur.g2[t], g2);
 #pragma unroll
           for (int e = 0; e < 8; ++e) g[t][e] += g2[e];
         }
@@ -267,7 +291,7 @@ __global__ __launch_bounds__(LN_BWD_THREADS) void ln_bwd_kernel(const T* __restr
         }
         if (HAS_LN) {
           float zv[8];
-          Vec8<T>::load(z + off, zv);
+          Vec8<T>::unpack(cur.z[t], zv);
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
             xh[t][e] = (zv[e] - mean) * rs;
@@ -296,8 +320,10 @@ __global__ __launch_bounds__(LN_BWD_THREADS) void ln_bwd_kernel(const T* __restr
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[e] = HAS_LN ? rs * (g[t][e] - s1 - xh[t][e] * s2) : g[t][e];
         if (dres) {
+          float r[8];
+          Vec8<T>::unpack(cur.res[t], r);
 #pragma unroll
-          for (int e = 0; e < 8; ++e) o[e] += res[t][e];
+          for (int e = 0; e < 8; ++e) o[e] += r[e];
         }
         if (dz) Vec8<T>::store(dz + off, o);
         if (da) {
@@ -313,6 +339,7 @@ __global__ __launch_bounds__(LN_BWD_THREADS) void ln_bwd_kernel(const T* __restr
         }
       }
     }
+    if (more) cur = nxt;
   }
 
   // lanes of different groups inside a wave that own the same columns
