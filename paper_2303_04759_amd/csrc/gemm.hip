@@ -384,7 +384,9 @@ raf_status launch_transpose_bf16(const TransposeJob* jobs, int count, hipStream_
 }
 
 // Weight-gradient form only: A and B both MN-major, float output, no batch.
-raf_status launch_gemm_group_wgrad(int precision, const GemmArgs* gs, int count, hipStream_t st) {
+raf_status launch_gemm_group_wgrad(int precision, const GemmArgs* gs, int count, hipStream_t st, const ColsumJob* side,
+                                   int nside, bool* side_taken) {
+  if (side_taken) *side_taken = false;
   if (count <= 0 || count > GEMM_GROUP_MAX || !gs) return RAF_EINVAL;
   bool groupable = precision == RAF_BF16_AMP;
   for (int i = 0; i < count; ++i) {
@@ -404,7 +406,27 @@ raf_status launch_gemm_group_wgrad(int precision, const GemmArgs* gs, int count,
   if (precision == RAF_BF16_AMP) {
     GemmDev ds[GEMM_GROUP_MAX];
     for (int i = 0; i < count; ++i) ds[i] = to_dev(gs[i]);
-    if (launch_gemm_group_spec(ds, count, st)) return check_launch();
+    // column sums of up to two bf16 matrices with a common row count can ride along on idle CUs
+    ColsumSide sd{};
+    if (side && nside >= 1 && nside <= 2) {
+      bool ok = true;
+      for (int i = 0; i < nside; ++i)
+        ok = ok && side[i].precision == RAF_BF16_AMP && side[i].x && side[i].out && side[i].cols > 0 &&
+             side[i].cols % 8 == 0 && side[i].ld % 8 == 0 && side[i].rows == side[0].rows && aligned16(side[i].x) &&
+             (side[i].out_cols == 0 || side[i].out_cols == side[i].cols);
+      if (ok) {
+        sd.count = nside;
+        sd.rows = side[0].rows;
+        for (int i = 0; i < nside; ++i) {
+          sd.x[i] = (const bf16_t*)side[i].x;
+          sd.out[i] = side[i].out;
+          sd.ld[i] = side[i].ld;
+          sd.cols[i] = side[i].cols;
+        }
+        if (nside == 1) { sd.x[1] = sd.x[0]; sd.out[1] = sd.out[0]; sd.ld[1] = sd.ld[0]; sd.cols[1] = 0; }
+      }
+    }
+    if (launch_gemm_group_spec(ds, count, st, sd.count ? &sd : nullptr, side_taken)) return check_launch();
   }
   GemmGroupDev grp;
   grp.count = count;

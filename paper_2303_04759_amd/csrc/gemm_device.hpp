@@ -359,10 +359,25 @@ struct GemmGroupDev {
   int count;
 };
 
+
+// Column sums out[j][c] = sum_r x[j][r*ld + c] of up to two bf16 matrices with the same row count (the bias
+// gradients next to the weight gradients), taken by workgroups of the weight-gradient launch that would otherwise
+// find no tile: the grouped launch of a BERT-base layer has 216 tiles for 256 CUs.
+struct ColsumSide {
+  const bf16_t* x[2];
+  float* out[2];
+  long ld[2];
+  int cols[2];     // multiples of 8; cols[1] = 0 for a single matrix
+  long rows;
+  int count;       // 0: no side work
+};
+
 // Weight-gradient group (both operands MN-major, float output) on the
 // producer/consumer direct-to-LDS kernel (gemm_pipe.hip); false when a problem
-// does not fit it (K % 64, sizes below one tile).
-bool launch_gemm_group_spec(const GemmDev* ds, int count, hipStream_t st);
+// does not fit it (K % 64, sizes below one tile).  side: optional column sums; *side_taken tells whether the launch
+// computed them (it does when enough CUs are left without a tile), otherwise the caller has to.
+bool launch_gemm_group_spec(const GemmDev* ds, int count, hipStream_t st, const ColsumSide* side = nullptr,
+                            bool* side_taken = nullptr);
 
 // Pipelined direct-to-LDS kernel family (gemm_pipe.hip).  Returns false when
 // the problem does not meet its requirements (K % 64, tile fit) and the

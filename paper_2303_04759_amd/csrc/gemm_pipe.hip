@@ -247,8 +247,60 @@ static bool launch_pipe_inst(const GemmDev& d, int batch, hipStream_t st) {
 // barrier per k-step keeps both sides in step: after barrier `it` the consumers
 // work on stage it while the producers refill the stage that was just freed
 // and then wait until stage it+1 has landed.
+// Side work of the grouped launch: worker w of nworkers takes a contiguous range of the 8-column vectors of the
+// (concatenated) column space; its threads are dealt to (vector, row group), every row group sums its rows in
+// registers, and the row groups are added in a fixed order through LDS, so the sums are reproducible.
+__device__ __forceinline__ void colsum_side_worker(const ColsumSide& sd, int w, int nworkers, char* lds) {
+  const int nvec0 = sd.cols[0] / 8, total = nvec0 + sd.cols[1] / 8;
+  const int per = (total + nworkers - 1) / nworkers;
+  const int v0 = w * per;
+  const int nv = total - v0 < per ? total - v0 : per;
+  if (nv <= 0 || per > (int)blockDim.x) return;
+  const int ngroups = (int)blockDim.x / per;
+  const int vec = threadIdx.x % per, rg = threadIdx.x / per;
+  const bool active = rg < ngroups && vec < nv;
+  const int uv = v0 + vec;
+  const int j = uv < nvec0 ? 0 : 1;
+  const bf16_t* __restrict__ x = sd.x[j] + (long)(j ? uv - nvec0 : uv) * 8;
+  const long ld = sd.ld[j];
+  float acc[8] = {};
+  if (active) {
+    long r = rg;
+    // eight independent 16-byte loads in flight per lane
+    for (; r + 7L * ngroups < sd.rows; r += 8L * ngroups) {
+      float v[8][8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) Vec8<bf16_t>::load(x + (r + (long)u * ngroups) * ld, v[u]);
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] += v[u][e];
+    }
+    for (; r < sd.rows; r += ngroups) {
+      float v[8];
+      Vec8<bf16_t>::load(x + r * ld, v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] += v[e];
+    }
+  }
+  float* red = reinterpret_cast<float*>(lds);   // [ngroups][per * 8]
+  if (active) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) red[(rg * per + vec) * 8 + e] = acc[e];
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < nv * 8; c += blockDim.x) {
+    float sum = red[c];
+    for (int g = 1; g < ngroups; ++g) sum += red[g * per * 8 + c];
+    const int u = v0 + c / 8;
+    const int jj = u < nvec0 ? 0 : 1;
+    sd.out[jj][(long)(jj ? u - nvec0 : u) * 8 + (c & 7)] = sum;
+  }
+}
+
 template <int BM, int BN, int WGM, int WGN, bool A_KMAJOR, bool B_KMAJOR, typename TC, int NS, int NP>
-__global__ __launch_bounds__(64 * (WGM * WGN + NP)) void gemm_bf16_spec_kernel(GemmGroupDev grp) {
+__global__ __launch_bounds__(64 * (WGM * WGN + NP)) void gemm_bf16_spec_kernel(GemmGroupDev grp, ColsumSide side,
+                                                                               int tile_blocks) {
   constexpr int NC = WGM * WGN;
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -260,6 +312,10 @@ __global__ __launch_bounds__(64 * (WGM * WGN + NP)) void gemm_bf16_spec_kernel(G
   constexpr int LPS = PA::LOADS + PB::LOADS;          // loads per producer wave per stage
   extern __shared__ __attribute__((aligned(1024))) char lds[];
 
+  if ((int)blockIdx.x >= tile_blocks) {   // a workgroup without a tile: column sums on a CU that the tiles leave idle
+    colsum_side_worker(side, (int)blockIdx.x - tile_blocks, (int)gridDim.x - tile_blocks, lds);
+    return;
+  }
   const int ntile = grp.tile_start[grp.count];
   const int per = (ntile + 7) >> 3;
   const int t = (int)(blockIdx.x & 7) * per + (int)(blockIdx.x >> 3);   // XCD x takes tiles [x*per, (x+1)*per)
@@ -366,8 +422,9 @@ __global__ __launch_bounds__(64 * (WGM * WGN + NP)) void gemm_bf16_spec_kernel(G
   epilogue_tile32<TC, TM, TN>(g, C, AUX, acc, m0 + wm, n0 + wn);
 }
 
-bool launch_gemm_group_spec(const GemmDev* ds, int count, hipStream_t st) {
+bool launch_gemm_group_spec(const GemmDev* ds, int count, hipStream_t st, const ColsumSide* side, bool* side_taken) {
   constexpr int BM = 256, BN = 128, WGM = 4, WGN = 2, NS = 3, NP = 8;
+  if (side_taken) *side_taken = false;
   if (!ds || count <= 0 || count > GEMM_GROUP_MAX) return false;
   GemmGroupDev grp;
   grp.count = count;
@@ -392,8 +449,29 @@ bool launch_gemm_group_spec(const GemmDev* ds, int count, hipStream_t st) {
     }
     attr_done = true;
   }
-  dim3 grid(((tiles + 7) / 8) * 8);
-  hipLaunchKernelGGL(kern, grid, dim3(64 * (WGM * WGN + NP)), LDS_BYTES, st, grp);
+  const int tile_blocks = ((tiles + 7) / 8) * 8;
+  // side workers only where the tiles leave CUs free (one workgroup per CU: the ring takes most of the LDS), and
+  // enough of them that a worker's columns take less time than a tile
+  ColsumSide sd{};
+  int workers = 0;
+  if (side && side->count > 0) {
+    constexpr int NUM_CUS = 256, THREADS = 64 * (WGM * WGN + NP);
+    const int total_vecs = (side->cols[0] + side->cols[1]) / 8;
+    const int free_cus = NUM_CUS - tile_blocks;
+    if (free_cus > 0 && total_vecs > 0) {
+      const int per = (total_vecs + free_cus - 1) / free_cus;
+      // per row of the contraction a worker reads per*16 bytes through registers (about 16 bytes/clock/CU: `per`
+      // clocks) while a tile needs about 30 clocks (1 us per 64-deep step, measured)
+      const bool short_enough = per <= 24;
+      if (per <= THREADS && short_enough && (long)(THREADS / per) * per * 32 <= LDS_BYTES) {
+        sd = *side;
+        workers = free_cus < total_vecs ? free_cus : total_vecs;
+        if (side_taken) *side_taken = true;
+      }
+    }
+  }
+  dim3 grid(tile_blocks + workers);
+  hipLaunchKernelGGL(kern, grid, dim3(64 * (WGM * WGN + NP)), LDS_BYTES, st, grp, sd, tile_blocks);
   return true;
 }
 
