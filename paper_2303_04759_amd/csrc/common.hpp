@@ -289,11 +289,14 @@ inline GemmArgs gemm_args_default() {
 
 raf_status launch_gemm(int precision, const GemmArgs& g, hipStream_t st);
 // up to 4 independent weight-gradient GEMMs (A, B MN-major, float out) in one launch
-// side / nside: optional column sums (ColsumJob, at most two, bf16, same row count) that the launch may take along
-// on CUs its tiles leave idle; *side_taken tells whether it did, otherwise the caller launches them itself
+// side / nside: optional column sums (ColsumJob, at most two, bf16, same row count), reds / nred: optional second
+// stages of two-stage column sums (at most three), that the launch may take along on CUs its tiles leave idle;
+// *side_taken tells whether it did (all of them or none), otherwise the caller launches them itself
 struct ColsumJob;
+struct ReduceJob;
 raf_status launch_gemm_group_wgrad(int precision, const GemmArgs* gs, int count, hipStream_t st,
-                                   const ColsumJob* side = nullptr, int nside = 0, bool* side_taken = nullptr);
+                                   const ColsumJob* side = nullptr, int nside = 0, const ReduceJob* reds = nullptr,
+                                   int nred = 0, bool* side_taken = nullptr);
 // dst[c][r] = src[r][c] for up to 4 dense row-major bf16 matrices (rows, cols multiples of 8) in one launch
 struct TransposeJob {
   const void* src; void* dst; int rows, cols;

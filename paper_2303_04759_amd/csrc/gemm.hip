@@ -385,7 +385,7 @@ raf_status launch_transpose_bf16(const TransposeJob* jobs, int count, hipStream_
 
 // Weight-gradient form only: A and B both MN-major, float output, no batch.
 raf_status launch_gemm_group_wgrad(int precision, const GemmArgs* gs, int count, hipStream_t st, const ColsumJob* side,
-                                   int nside, bool* side_taken) {
+                                   int nside, const ReduceJob* reds, int nred, bool* side_taken) {
   if (side_taken) *side_taken = false;
   if (count <= 0 || count > GEMM_GROUP_MAX || !gs) return RAF_EINVAL;
   bool groupable = precision == RAF_BF16_AMP;
@@ -424,6 +424,13 @@ raf_status launch_gemm_group_wgrad(int precision, const GemmArgs* gs, int count,
           sd.cols[i] = side[i].cols;
         }
         if (nside == 1) { sd.x[1] = sd.x[0]; sd.out[1] = sd.out[0]; sd.ld[1] = sd.ld[0]; sd.cols[1] = 0; }
+        sd.nred = 0;
+        if (reds && nred > 0 && nred <= 3) {
+          for (int i = 0; i < nred; ++i) sd.red[i] = reds[i];
+          sd.nred = nred;
+        } else if (nred > 3) {
+          sd.count = 0;   // more second stages than the side workers take: the caller launches everything itself
+        }
       }
     }
     if (launch_gemm_group_spec(ds, count, st, sd.count ? &sd : nullptr, side_taken)) return check_launch();

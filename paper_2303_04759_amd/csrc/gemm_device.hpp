@@ -370,6 +370,9 @@ struct ColsumSide {
   int cols[2];     // multiples of 8; cols[1] = 0 for a single matrix
   long rows;
   int count;       // 0: no side work
+  // second stages of earlier two-stage column sums (sums over partial rows, see ReduceJob), taken after the above
+  ReduceJob red[3];
+  int nred;
 };
 
 // Weight-gradient group (both operands MN-major, float output) on the

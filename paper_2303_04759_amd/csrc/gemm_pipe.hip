@@ -255,10 +255,10 @@ __device__ __forceinline__ void colsum_side_worker(const ColsumSide& sd, int w, 
   const int per = (total + nworkers - 1) / nworkers;
   const int v0 = w * per;
   const int nv = total - v0 < per ? total - v0 : per;
-  if (nv <= 0 || per > (int)blockDim.x) return;
+  if (per > (int)blockDim.x) return;               // uniform over the launch; the host never asks for it
   const int ngroups = (int)blockDim.x / per;
   const int vec = threadIdx.x % per, rg = threadIdx.x / per;
-  const bool active = rg < ngroups && vec < nv;
+  const bool active = rg < ngroups && vec < nv;     // nv <= 0: a worker beyond the last vector idles through the barrier
   const int uv = v0 + vec;
   const int j = uv < nvec0 ? 0 : 1;
   const bf16_t* __restrict__ x = sd.x[j] + (long)(j ? uv - nvec0 : uv) * 8;
@@ -298,6 +298,48 @@ __device__ __forceinline__ void colsum_side_worker(const ColsumSide& sd, int w, 
   }
 }
 
+// out_k[c] = sum_p partial[p][k][c] for the columns of worker w: threads are dealt to (column, slice of the partial
+// rows), slices are added in a fixed order through LDS
+__device__ __forceinline__ void reduce_side_worker(const ReduceJob& job, int w, int nworkers, char* lds) {
+  const int chunk = (job.width_out + nworkers - 1) / nworkers;
+  const int c0 = w * chunk;
+  const int nc = job.width_out - c0 < chunk ? job.width_out - c0 : chunk;
+  float* red = reinterpret_cast<float*>(lds);   // [nslices][chunk]
+  const bool fits = chunk <= (int)blockDim.x;
+  const int nslices = fits ? (int)blockDim.x / chunk : 1;
+  const int cl = fits ? threadIdx.x % chunk : 0, slice = fits ? threadIdx.x / chunk : nslices;
+  const long width = (long)job.nout * job.ncols;   // stride between partial rows
+  __syncthreads();                                 // the previous user of the LDS buffer is done
+  if (nc > 0 && fits && slice < nslices) {
+    float acc = 0.f;
+    if (cl < nc) {
+      // eight loads in flight; rows past the end re-read the last row and are not added
+      for (int p = slice; p < job.nparts; p += 8 * nslices) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int q = p + u * nslices;
+          v[u] = job.partial[(long)(q < job.nparts ? q : job.nparts - 1) * width + c0 + cl];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += p + u * nslices < job.nparts ? v[u] : 0.f;
+      }
+    }
+    red[slice * chunk + cl] = acc;
+  }
+  __syncthreads();
+  if (nc > 0 && fits && slice == 0 && cl < nc) {
+    float sum = 0.f;
+    for (int sl = 0; sl < nslices; ++sl) sum += red[sl * chunk + cl];
+    const int c = c0 + cl;
+    const int k = c / job.ncols;
+    int cc = c % job.ncols;
+    if (job.perm_nvec > 0) cc = (cc % job.perm_nvec) * 8 + cc / job.perm_nvec;   // partial rows stored element-major
+    float* o = k == 0 ? job.o0 : (k == 1 ? job.o1 : job.o2);
+    if (o) o[cc] = sum;
+  }
+}
+
 template <int BM, int BN, int WGM, int WGN, bool A_KMAJOR, bool B_KMAJOR, typename TC, int NS, int NP>
 __global__ __launch_bounds__(64 * (WGM * WGN + NP)) void gemm_bf16_spec_kernel(GemmGroupDev grp, ColsumSide side,
                                                                                int tile_blocks) {
@@ -313,7 +355,12 @@ __global__ __launch_bounds__(64 * (WGM * WGN + NP)) void gemm_bf16_spec_kernel(G
   extern __shared__ __attribute__((aligned(1024))) char lds[];
 
   if ((int)blockIdx.x >= tile_blocks) {   // a workgroup without a tile: column sums on a CU that the tiles leave idle
-    colsum_side_worker(side, (int)blockIdx.x - tile_blocks, (int)gridDim.x - tile_blocks, lds);
+    const int w = (int)blockIdx.x - tile_blocks, nworkers = (int)gridDim.x - tile_blocks;
+    colsum_side_worker(side, w, nworkers, lds);
+    // static indices: a run-time index would copy the descriptors to scratch memory
+    if (side.nred > 0) reduce_side_worker(side.red[0], w, nworkers, lds);
+    if (side.nred > 1) reduce_side_worker(side.red[1], w, nworkers, lds);
+    if (side.nred > 2) reduce_side_worker(side.red[2], w, nworkers, lds);
     return;
   }
   const int ntile = grp.tile_start[grp.count];
@@ -463,9 +510,15 @@ bool launch_gemm_group_spec(const GemmDev* ds, int count, hipStream_t st, const 
       // per row of the contraction a worker reads per*16 bytes through registers (about 16 bytes/clock/CU: `per`
       // clocks) while a tile needs about 30 clocks (1 us per 64-deep step, measured)
       const bool short_enough = per <= 24;
-      if (per <= THREADS && short_enough && (long)(THREADS / per) * per * 32 <= LDS_BYTES) {
+      const int nw = free_cus < total_vecs ? free_cus : total_vecs;
+      bool red_ok = side->nred >= 0 && side->nred <= 3;
+      for (int i = 0; red_ok && i < side->nred; ++i)
+        red_ok = side->red[i].partial && side->red[i].nparts > 0 && side->red[i].ncols > 0 &&
+                 side->red[i].nout >= 1 && side->red[i].nout <= 3 && side->red[i].width_out > 0 &&
+                 (side->red[i].width_out + nw - 1) / nw <= THREADS;
+      if (per <= THREADS && short_enough && red_ok && (long)(THREADS / per) * per * 32 <= LDS_BYTES) {
         sd = *side;
-        workers = free_cus < total_vecs ? free_cus : total_vecs;
+        workers = nw;
         if (side_taken) *side_taken = true;
       }
     }

@@ -397,11 +397,12 @@ extern "C" raf_status raf_layer_bwd(const raf_layer_desc* desc, const raf_layer_
   wg[1] = wgrad_args(F, H, T, du, F, ffn_in, H, grads->w_1, H);
   wg[2] = wgrad_args(3 * H, H, T, dqkv, 3 * H, d.pre_ln ? n1 : x, H, grads->w_qkv, H);
   wg[3] = wgrad_args(H, H, T, da1, H, c, H, grads->w_o, H);
-  // db1 = column sums of du, dbqkv = column sums of dqkv (both still intact): taken inside the weight-gradient
-  // launch when its tiles leave CUs idle, else by their own launch; then every deferred reduction
+  // db1 = column sums of du, dbqkv = column sums of dqkv (both still intact) and every deferred reduction: taken
+  // inside the weight-gradient launch when its tiles leave CUs idle, else by their own two launches
   bool side_taken = false;
-  RAF_TRY(launch_gemm_group_wgrad(prec, wg, 4, st, cj, 2, &side_taken));
-  if (!side_taken) RAF_TRY(launch_colsum_group(cj, 2, rj, &nr, st));
+  RAF_TRY(launch_gemm_group_wgrad(prec, wg, 4, st, cj, 2, rj, nr, &side_taken));
+  if (side_taken) return RAF_OK;
+  RAF_TRY(launch_colsum_group(cj, 2, rj, &nr, st));
   return launch_reduce_group(rj, nr, st);
 }
 
