@@ -111,7 +111,7 @@ __device__ __forceinline__ void staged_tile(const GemmDev& g, int m0, int n0, in
   TC* __restrict__ C = (TC*)g.c + zb * g.sc0 + zi * g.sc1;
   bf16_t* __restrict__ AUX = g.aux ? (bf16_t*)g.aux + zb * g.sc0 + zi * g.sc1 : nullptr;
 
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
   const int wm = (wave / WGN) * WM, wn = (wave % WGN) * WN;
 
   f32x16_t acc[TM][TN];

@@ -136,7 +136,7 @@ __device__ __forceinline__ void pipe_body(const GemmDev& g, int tiles_m, int til
   TC* __restrict__ C = (TC*)g.c + zb * g.sc0 + zi * g.sc1;
   bf16_t* __restrict__ AUX = g.aux ? (bf16_t*)g.aux + zb * g.sc0 + zi * g.sc1 : nullptr;
 
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
   const int wm = (wave / WGN) * WM, wn = (wave % WGN) * WN;
 
   const bf16_t* srca[PA::LOADS];
@@ -378,7 +378,7 @@ __global__ __launch_bounds__(64 * (WGM * WGN + NP)) void gemm_bf16_spec_kernel(G
       tn = grp.tiles_n[q];
     }
   const int m0 = (lt / tn) * BM, n0 = (lt % tn) * BN;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nk = g.K / PBK;
 
   if (wave >= NC) {
