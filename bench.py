@@ -109,6 +109,9 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--dynamic-loss-scale", action="store_true",
                     help="time the step under the device-resident dynamic loss scaler (layer workloads)")
+    ap.add_argument("--steps-per-graph", type=int, default=1,
+                    help="consecutive steps captured into one HIP graph (layer workloads); the timed region still "
+                         "covers exactly --steps steps")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (5x) so FETCH_SIZE/WRITE_SIZE counters can be scaled")
     args = ap.parse_args()
@@ -143,6 +146,7 @@ def main():
 
     with torch.cuda.stream(stream):
         graph = None
+        multi = None
         t_step = 1
         for _ in range(max(W, 1)):
             one_step(t_step, stream)
@@ -156,16 +160,31 @@ def main():
             for _ in range(3):
                 graph.replay()
             stream.synchronize()
+            multi = None
+            G = max(1, args.steps_per_graph)
+            if G > 1:
+                multi = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(multi, stream=stream):
+                    for i in range(G):
+                        one_step(t_step + 1 + i, stream)
+                multi.replay()
+                stream.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         e0.record(stream)
-        for _ in range(K):
-            if graph is not None:
+        if graph is not None and multi is not None:
+            for _ in range(K // G):
+                multi.replay()
+            for _ in range(K % G):
                 graph.replay()
-            else:
-                one_step(t_step, stream)
-                t_step += 1
+        else:
+            for _ in range(K):
+                if graph is not None:
+                    graph.replay()
+                else:
+                    one_step(t_step, stream)
+                    t_step += 1
         e1.record(stream)
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
@@ -221,7 +240,8 @@ def main():
         "config": {"workload": args.workload, "batch": cfg["batch"], "seq_len": cfg["seq"], "hidden": cfg["hidden"],
                    "heads": cfg["heads"], "ffn": cfg["ffn"], "dropout_p": cfg["dropout_p"],
                    "launch": "eager" if graph is None else "hip_graph", "parallelism": "single GPU",
-                   "loss_scale": "dynamic" if args.dynamic_loss_scale else "static"},
+                   "loss_scale": "dynamic" if args.dynamic_loss_scale else "static",
+                   "steps_per_graph": (max(1, args.steps_per_graph) if graph is not None else 0)},
         "tokens_per_s_padded": lay.T / (ms_per_step * 1e-3),
         "tokens_per_s_valid": valid_tokens / (ms_per_step * 1e-3),
         "step_gemm_tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
