@@ -38,6 +38,7 @@ def test_struct_layout_matches_header():
     assert raf.LayerDesc.dropout_p.offset == 40 and raf.LayerDesc.seed.offset == 48
     assert C.sizeof(raf.LayerTensors) == 96
     assert C.sizeof(raf.AdamTensor) == 48
+    assert C.sizeof(raf.ScalerState) == 32 and raf.ScalerState.t.offset == 16 and raf.ScalerState.inv_bc2.offset == 28
 
 
 def good_cfg(**kw):
@@ -79,6 +80,20 @@ def test_null_and_misaligned_pointers_are_rejected_on_host(lib):
     assert lib.raf_adam_step(t, 1, 1e-3, 0.9, 0.999, 1e-8, 0.0, 0, 1.0, None) == raf.RAF_EINVAL    # t is 1-based
     assert lib.raf_op_gemm(1, 64, 64, 48, 4096, 64, 1, 4096, 64, 1, 4096, 64, 0, 1.0, 0, None, None, 0,
                            None) == raf.RAF_ENOTSUP
+    # dynamic loss scaler and attention operations: argument checks happen before any launch
+    assert lib.raf_scaler_init(None, 128.0, None) == raf.RAF_EINVAL
+    assert lib.raf_scaler_init(4096, 0.0, None) == raf.RAF_EINVAL
+    assert lib.raf_scaler_init(4096 + 4, 128.0, None) == raf.RAF_EINVAL
+    assert lib.raf_scaler_update(4096, 0.5, 0.5, 10, None) == raf.RAF_EINVAL        # growth factor below 1
+    assert lib.raf_scaler_update(4096, 2.0, 0.5, 0, None) == raf.RAF_EINVAL          # interval below 1
+    assert lib.raf_grads_check(None, 1, 4096, None) == raf.RAF_EINVAL
+    assert lib.raf_adam_step_scaled(None, 0, 1e-3, 0.9, 0.999, 1e-8, 0.0, None, None) == raf.RAF_EINVAL
+    assert lib.raf_loss_seed_scaled(1, 4096, 4096, 64, None, 4096, 4096, 4096, None) == raf.RAF_EINVAL
+    d32 = raf.make_desc(good_cfg())                                                  # fp32: no on-chip attention path
+    assert lib.raf_op_attention_fwd(C.byref(d32), 4096, None, 4096, None, 0, None) == raf.RAF_ENOTSUP
+    dbf = raf.make_desc(good_cfg(precision=1))
+    assert lib.raf_op_attention_fwd(C.byref(dbf), None, None, 4096, None, 0, None) == raf.RAF_EINVAL
+    assert lib.raf_op_attention_bwd(C.byref(dbf), 4096, 4096 + 2, None, None, None, 4096, None, 0, None) == raf.RAF_EINVAL
     assert raf.status_string(raf.RAF_ENOTSUP) == "unsupported shape or mode"
     assert raf.version().startswith("raf_mi355")
 
