@@ -357,11 +357,38 @@ static raf_status validate_mlm(const raf_mlm_desc* d) {
   return RAF_OK;
 }
 
+// out[i] = sum_s part[s*n + i] (fixed order), 8 elements per thread
+template <typename T>
+__global__ __launch_bounds__(256) void sum_slices_kernel(const float* __restrict__ part, int nslices, long n,
+                                                         T* __restrict__ out) {
+  const long i = ((long)blockIdx.x * 256 + threadIdx.x) * 8;
+  if (i >= n) return;
+  float acc[8] = {};
+  for (int s = 0; s < nslices; ++s) {
+    float v[8];
+    load8f(part + (long)s * n + i, v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] += v[e];
+  }
+  Vec8<T>::store(out + i, acc);
+}
+
 struct MlmPlan {
   size_t e;
   int n_pad, vp;
-  size_t r, t1, t2, t, mu, rstd, logits, dt, dt2, dt1, dr, loss_rows, partial, scratch_bytes;
+  size_t r, t1, t2, t, mu, rstd, logits, dt, dt2, dt1, dr, loss_rows, partial, dt_part, scratch_bytes;
+  int dt_splits;   // the vocabulary-deep product dt = dlogits . Word is taken in this many slices of the contraction
 };
+
+// dt has only n_pad/128 x hidden/128 output tiles (60 for the BERT-base head) under a contraction as deep as the
+// vocabulary: slicing the contraction fills the chip.  Largest count up to 16 that divides the 64-deep steps.
+static int dt_split_count(int vp) {
+  if (vp % 64) return 1;
+  const int steps = vp / 64;
+  for (int s = 16; s > 1; --s)
+    if (steps % s == 0 && steps / s >= 8) return s;
+  return 1;
+}
 static MlmPlan mlm_plan(const raf_mlm_desc& d) {
   MlmPlan p{};
   p.e = d.precision == RAF_F32 ? 4 : 2;
@@ -379,6 +406,8 @@ static MlmPlan mlm_plan(const raf_mlm_desc& d) {
   if (c1 > pf) pf = c1;
   if (c2 > pf) pf = c2;
   p.partial = bump256(o, pf * 4);
+  p.dt_splits = d.precision == RAF_BF16_AMP ? dt_split_count(p.vp) : 1;
+  p.dt_part = bump256(o, p.dt_splits > 1 ? (size_t)p.dt_splits * p.n_pad * d.hidden * 4 : 0);
   p.scratch_bytes = o;
   return p;
 }
@@ -549,7 +578,24 @@ extern "C" raf_status raf_mlm_head_fwd_bwd(const raf_mlm_desc* desc, const raf_m
   // backward
   RAF_TRY(launch_colsum(prec, logits, NP, VP, VP, (float*)grads->dec_b, partial, st, d.vocab));
   RAF_TRY(head_gemm(prec, st, VP, H, NP, logits, VP, 0, t, H, 0, grads->word, H, 1));          // dWord = dlogits^T t
-  RAF_TRY(head_gemm(prec, st, NP, H, VP, logits, VP, 1, w->word, H, 0, dt, H));                // dt = dlogits Word
+  if (p.dt_splits > 1) {
+    // dt = dlogits Word in slices of the contraction (float partial results), then their sum
+    GemmArgs g = gemm_args_default();
+    const int kc = VP / p.dt_splits;
+    g.M = NP; g.N = H; g.K = kc;
+    g.a = logits; g.lda = VP; g.a_kmajor = 1;
+    g.b = w->word; g.ldb = H; g.b_kmajor = 0;
+    g.c = sc + p.dt_part; g.ldc = H; g.out_f32 = 1;
+    g.batch = p.dt_splits;
+    g.sa[0] = kc; g.sb[0] = (long)kc * H; g.sc[0] = (long)NP * H;
+    RAF_TRY(launch_gemm(prec, g, st));
+    const long n = (long)NP * H;
+    hipLaunchKernelGGL((sum_slices_kernel<bf16_t>), dim3((n / 8 + 255) / 256), dim3(256), 0, st,
+                       (const float*)(sc + p.dt_part), p.dt_splits, n, (bf16_t*)dt);
+    RAF_TRY(check_launch());
+  } else {
+    RAF_TRY(head_gemm(prec, st, NP, H, VP, logits, VP, 1, w->word, H, 0, dt, H));              // dt = dlogits Word
+  }
   RAF_TRY(launch_ln_bwd(ld, 0, NP, dt, nullptr, t2, mu, rstd, (const float*)w->ln_g, nullptr, dt2, nullptr,
                         (float*)grads->ln_g, (float*)grads->ln_b, nullptr, partial, 0, st));
   const long nh = (long)NP * H;
