@@ -280,18 +280,18 @@ __device__ __forceinline__ void epilogue_tile16_staged(const GemmDev& g, bf16_t*
             store4(reinterpret_cast<bf16_t*>(s_aux + off), v);
             // GeLU is evaluated on the value the backward pass will read back
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = gelu_f((float)(bf16_t)v[e], g.gelu_tanh);
+            for (int e = 0; e < 4; ++e) v[e] = gelu_fast((float)(bf16_t)v[e], g.gelu_tanh);
           } else if constexpr (EPI == EPI_BIAS_GELU_DERIV) {
             float dy[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) gelu_and_grad_f(v[e], g.gelu_tanh, v[e], dy[e]);
+            for (int e = 0; e < 4; ++e) gelu_and_grad_fast(v[e], g.gelu_tanh, v[e], dy[e]);
             store4(reinterpret_cast<bf16_t*>(s_aux + off), dy);
           } else if constexpr (AUX_IN) {
             float u[4];
             load4(reinterpret_cast<const bf16_t*>(s_aux + off), u);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              if constexpr (EPI == EPI_MUL_GELU_GRAD) v[e] *= gelu_grad_f(u[e], g.gelu_tanh);
+              if constexpr (EPI == EPI_MUL_GELU_GRAD) v[e] *= gelu_grad_fast(u[e], g.gelu_tanh);
               else if constexpr (EPI == EPI_ADD_RES) v[e] += u[e];
               else v[e] *= u[e];
             }
