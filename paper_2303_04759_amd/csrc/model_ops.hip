@@ -240,20 +240,33 @@ __global__ __launch_bounds__(256) void softmax_ce_kernel(T* __restrict__ logits,
   const bool live = label >= 0 && label < vocab;
   float v[NVT][8];
   float mx = -INFINITY;
+  // every load of the row is issued before the first use and none sits under a branch (vectors past the end re-read
+  // the last one and are discarded): one memory round trip instead of one per vector
+  typename Vec8<T>::Raw raw[NVT];
 #pragma unroll
   for (int t = 0; t < NVT; ++t) {
     const int vec = threadIdx.x + 256 * t;
-    if (vec < nvec) {
-      Vec8<T>::load(row + vec * 8, v[t]);
+    raw[t] = Vec8<T>::load_raw(row + (vec < nvec ? vec : nvec - 1) * 8);
+  }
+#pragma unroll
+  for (int t = 0; t < NVT; ++t) {
+    const int vec = threadIdx.x + 256 * t;
+    Vec8<T>::unpack(raw[t], v[t]);
+    if (vec * 8 + 8 <= vocab) {          // whole vector inside the vocabulary (all but the last one or two)
+      float b[8];
+      load8f(bias + vec * 8, b);
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        const int c = vec * 8 + e;
-        v[t][e] = c < vocab ? v[t][e] + bias[c] : -INFINITY;
+        v[t][e] += b[e];
         mx = fmaxf(mx, v[t][e]);
       }
     } else {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) v[t][e] = -INFINITY;
+      for (int e = 0; e < 8; ++e) {
+        const int c = vec * 8 + e;
+        v[t][e] = (vec < nvec && c < vocab) ? v[t][e] + bias[c] : -INFINITY;
+        mx = fmaxf(mx, v[t][e]);
+      }
     }
   }
   mx = group_max<64>(mx);
