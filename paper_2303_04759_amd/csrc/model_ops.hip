@@ -94,15 +94,20 @@ __global__ __launch_bounds__(256) void embed_dword_kernel(const int32_t* __restr
   int id = ids[t0];
   id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
   const int lane = threadIdx.x & 63;
+  // the id list is scanned 256 positions at a time: four independent loads per lane and round trip (one load per
+  // round trip made the two scans, 128 round trips for 8192 positions, the whole cost of the kernel)
+  auto clamped = [&](int t, int limit) {
+    int other = ids[t < limit ? t : limit - 1];
+    other = other < 0 ? 0 : (other >= vocab ? vocab - 1 : other);
+    return t < limit ? other : -1;
+  };
   // is there an earlier position with the same (clamped) id?
-  for (int base = 0; base < t0; base += 64) {
-    const int t = base + lane;
-    int other = -1;
-    if (t < t0) {
-      other = ids[t];
-      other = other < 0 ? 0 : (other >= vocab ? vocab - 1 : other);
-    }
-    if (__ballot(other == id)) return;   // wave-uniform: every wave scans the same ids
+  for (int base = 0; base < t0; base += 256) {
+    int o[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) o[u] = clamped(base + 64 * u + lane, t0);
+    const bool hit = o[0] == id || o[1] == id || o[2] == id || o[3] == id;
+    if (__ballot(hit)) return;   // wave-uniform: every wave scans the same ids
   }
   // every thread takes part in the ballots (the scan must see all 64 candidates
   // of a chunk); a thread owns up to two 8-column vectors (H <= 4096)
@@ -118,25 +123,26 @@ __global__ __launch_bounds__(256) void embed_dword_kernel(const int32_t* __restr
       for (int e = 0; e < 8; ++e) acc[v][e] = 0.f;
     }
   }
-  for (int base = t0 + 1; base < nrows; base += 64) {
-    const int t = base + lane;
-    int other = -1;
-    if (t < nrows) {
-      other = ids[t];
-      other = other < 0 ? 0 : (other >= vocab ? vocab - 1 : other);
-    }
-    unsigned long long m = __ballot(other == id);
-    while (m) {
-      const int b = __builtin_ctzll(m);
-      m &= m - 1;
+  for (int base0 = t0 + 1; base0 < nrows; base0 += 256) {
+    int o[4];
 #pragma unroll
-      for (int v = 0; v < 2; ++v) {
-        const int vec = threadIdx.x + 256 * v;
-        if (vec < nvec) {
-          float x[8];
-          Vec8<T>::load(dz + (long)(base + b) * H + vec * 8, x);
+    for (int u = 0; u < 4; ++u) o[u] = clamped(base0 + 64 * u + lane, nrows);
 #pragma unroll
-          for (int e = 0; e < 8; ++e) acc[v][e] += x[e];
+    for (int u = 0; u < 4; ++u) {      // ascending positions: chunk by chunk, lowest bit first
+      const int base = base0 + 64 * u;
+      unsigned long long m = __ballot(o[u] == id);
+      while (m) {
+        const int b = __builtin_ctzll(m);
+        m &= m - 1;
+#pragma unroll
+        for (int v = 0; v < 2; ++v) {
+          const int vec = threadIdx.x + 256 * v;
+          if (vec < nvec) {
+            float x[8];
+            Vec8<T>::load(dz + (long)(base + b) * H + vec * 8, x);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[v][e] += x[e];
+          }
         }
       }
     }
