@@ -135,15 +135,24 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ a, co
   const int nvec = H / 8;
   float z[NV][8];
   float sum = 0.f;
+  // every operand of the row is requested before the first use (one memory round trip, not one per vector)
+  typename Vec8<T>::Raw rres[NV], ra[NV];
+#pragma unroll
+  for (int t = 0; t < NV; ++t) {
+    const int vec = lane + LPR * t;
+    const long off = row * H + (vec < nvec ? vec : nvec - 1) * 8;
+    rres[t] = Vec8<T>::load_raw(res + off);
+    if (a) ra[t] = Vec8<T>::load_raw(a + off);
+  }
 #pragma unroll
   for (int t = 0; t < NV; ++t) {
     const int vec = lane + LPR * t;
     if (vec < nvec) {
       const long off = row * H + vec * 8;
-      Vec8<T>::load(res + off, z[t]);
+      Vec8<T>::unpack(rres[t], z[t]);
       if (a) {
         float av[8];
-        Vec8<T>::load(a + off, av);
+        Vec8<T>::unpack(ra[t], av);
         if (drop.enabled) {
           float mult[8];
           drop_mult8(drop, (uint64_t)off, mult);
