@@ -112,6 +112,19 @@ __device__ __forceinline__ void tile_products(const char* tile, const bf16x8_t (
   }
 }
 
+// the two 16-row blocks of 32-row group u only: a[v][r] = acc[2u+v][r] of tile_products (the blockwise kernels take
+// one group at a time, which keeps 48 accumulator registers fewer alive)
+__device__ __forceinline__ void group_products(const char* tile, const bf16x8_t (&qf)[2], int u, f32x4_t (&a)[2]) {
+  const int m = threadIdx.x & 15;
+#pragma unroll
+  for (int v = 0; v < 2; ++v) {
+    const int row = 32 * u + 8 * (m >> 2) + 4 * v + (m & 3);
+    const f32x4_t zero = {0.f, 0.f, 0.f, 0.f};
+    a[v] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hd_frag(tile, row, 0), qf[0], zero, 0, 0, 0);
+    a[v] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hd_frag(tile, row, 1), qf[1], a[v], 0, 0, 0);
+  }
+}
+
 __device__ __forceinline__ uint4 pack8_bf16(const float (&v)[8]) {
   uint4 r;
   r.x = pack_bf16x2(v[0], v[1]); r.y = pack_bf16x2(v[2], v[3]);
@@ -557,12 +570,12 @@ __global__ __launch_bounds__(512) void attn_flash_dq_kernel(const bf16_t* __rest
     __syncthreads();                                      // block jb has landed; every wave is done with block jb-1
     if (jb + 1 < nkb) fetch(jb + 1);
     if (active) {
-      f32x4_t acc[ATT_TILES], dacc[ATT_TILES];
-      tile_products(kt, qf, acc, npairs);
-      tile_products(vt, gf, dacc, npairs);
 #pragma unroll
       for (int u = 0; u < ATT_PAIRS; ++u)
         if (u < npairs) {
+          f32x4_t acc[2], dacc[2];
+          group_products(kt, qf, u, acc);
+          group_products(vt, gf, u, dacc);
           float mult[8], dsv[8];
           if (drop.enabled) {
             drop_mult8(drop, (uint64_t)(row_off + key0 + 32 * u + jl), mult);
@@ -573,8 +586,8 @@ __global__ __launch_bounds__(512) void attn_flash_dq_kernel(const bf16_t* __rest
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
             const int j = key0 + 32 * u + jl + e;
-            const float pe = j < limit ? exp2_hw(acc[2 * u + (e >> 2)][e & 3] * alpha2 - L) : 0.f;
-            dsv[e] = alpha * pe * (dacc[2 * u + (e >> 2)][e & 3] * mult[e] - D);
+            const float pe = j < limit ? exp2_hw(acc[e >> 2][e & 3] * alpha2 - L) : 0.f;
+            dsv[e] = alpha * pe * (dacc[e >> 2][e & 3] * mult[e] - D);
           }
           const bf16x8_t df = __builtin_bit_cast(bf16x8_t, pack8_bf16(dsv));
 #pragma unroll
@@ -587,7 +600,7 @@ __global__ __launch_bounds__(512) void attn_flash_dq_kernel(const bf16_t* __rest
 }
 
 // dV = P~^T dC and dK = ds^T Q for the 128 keys of one block, over all query blocks
-__global__ __launch_bounds__(512) void attn_flash_dkv_kernel(const bf16_t* __restrict__ dc, const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(512, 4) void attn_flash_dkv_kernel(const bf16_t* __restrict__ dc, const bf16_t* __restrict__ qkv,
                                                              const float* __restrict__ lse, const float* __restrict__ dvec,
                                                              const int32_t* __restrict__ lens, bf16_t* __restrict__ dqkv,
                                                              int S, int H, int heads, int causal, float alpha2,
@@ -644,12 +657,12 @@ __global__ __launch_bounds__(512) void attn_flash_dkv_kernel(const bf16_t* __res
     __syncthreads();                                      // block ib has landed; every wave is done with block ib-1
     if (ib + 1 < ib1) fetch(ib + 1);
     if (active) {
-      f32x4_t acc[ATT_TILES], dacc[ATT_TILES];
-      tile_products(qt, kf, acc, npairs);                 // own key row x 8 consecutive queries per 32-query group
-      tile_products(ct, vf, dacc, npairs);
 #pragma unroll
       for (int u = 0; u < ATT_PAIRS; ++u)
         if (u < npairs) {
+          f32x4_t acc[2], dacc[2];
+          group_products(qt, kf, u, acc);                 // own key row x 8 consecutive queries of the 32-query group
+          group_products(ct, vf, u, dacc);
           const int qg = q0 + 32 * u + 8 * g;             // first of this lane's 8 queries in the group
           float Lv[8], Dv[8];
           *reinterpret_cast<float4*>(&Lv[0]) = *reinterpret_cast<const float4*>(lse_t + 32 * u + 8 * g);
@@ -668,9 +681,9 @@ __global__ __launch_bounds__(512) void attn_flash_dkv_kernel(const bf16_t* __res
             const float mult = drop.enabled ? (((theirs >> (m & 7)) & 1u) ? drop.scale : 0.f) : 1.f;
             const int q = qg + e;
             const bool admissible = k < len && (!causal || k <= q);
-            const float pe = admissible ? exp2_hw(acc[2 * u + (e >> 2)][e & 3] * alpha2 - Lv[e]) : 0.f;
+            const float pe = admissible ? exp2_hw(acc[e >> 2][e & 3] * alpha2 - Lv[e]) : 0.f;
             pd[e] = pe * mult;
-            dsv[e] = alpha * pe * (dacc[2 * u + (e >> 2)][e & 3] * mult - Dv[e]);
+            dsv[e] = alpha * pe * (dacc[e >> 2][e & 3] * mult - Dv[e]);
           }
           const bf16x8_t pf = __builtin_bit_cast(bf16x8_t, pack8_bf16(pd));
           const bf16x8_t df = __builtin_bit_cast(bf16x8_t, pack8_bf16(dsv));
