@@ -392,6 +392,15 @@ __global__ __launch_bounds__(512) void attn_bwd_full_kernel(const bf16_t* __rest
 // Dropout blocks cover 8 consecutive keys of one query, so there each lane generates the block of one (query,
 // key octet) of its 16 x 32 sub-block and the keep bits are exchanged with lane permutes.
 constexpr int FL_QB = 128;   // query rows per workgroup (8 waves x 16)
+// Block of the sequence that workgroup (blockIdx.x, blockIdx.y) takes.  Under a causal mask the work of a block
+// grows (query blocks) or shrinks (key blocks) along the sequence; two workgroups share a CU and are dealt to the
+// CUs round-robin, so every other round of 256 workgroups walks the sequence backwards and a long block meets a
+// short one instead of another long one.
+__device__ __forceinline__ int fl_seq_block() {
+  const int n = gridDim.x;
+  const long linear = (long)blockIdx.y * n + blockIdx.x;
+  return ((linear >> 8) & 1) ? n - 1 - (int)blockIdx.x : (int)blockIdx.x;
+}
 constexpr int FL_STAGE = 2 * HD_TILE;                      // K and V (or Q and dC) block
 constexpr int FL_DKV_STAGE = 2 * HD_TILE + 2 * FL_QB * 4;  // plus lse and D of the query rows
 
@@ -423,7 +432,7 @@ __global__ __launch_bounds__(512) void attn_flash_fwd_kernel(const bf16_t* __res
   const int bh = blockIdx.y, b = bh / heads, h = bh % heads;
   const long ld = 3L * H;
   const bf16_t* Q = qkv + ((long)b * S) * ld + h * 64;
-  const int q0 = (int)blockIdx.x * FL_QB;
+  const int q0 = fl_seq_block() * FL_QB;
   const int i0 = q0 + wave * ATT_ROWS;
   const bool active = i0 < S;                            // S is a multiple of 32: a wave is all in or all out
   const int i = i0 + (lane & 15);                        // this lane's query row
@@ -526,7 +535,7 @@ __global__ __launch_bounds__(512) void attn_flash_dq_kernel(const bf16_t* __rest
   const int bh = blockIdx.y, b = bh / heads, h = bh % heads;
   const long ld = 3L * H;
   const bf16_t* Q = qkv + ((long)b * S) * ld + h * 64;
-  const int q0 = (int)blockIdx.x * FL_QB;
+  const int q0 = fl_seq_block() * FL_QB;
   const int i0 = q0 + wave * ATT_ROWS;
   const bool active = i0 < S;
   const int i = i0 + (lane & 15);
@@ -611,7 +620,7 @@ __global__ __launch_bounds__(512, 4) void attn_flash_dkv_kernel(const bf16_t* __
   const long ld = 3L * H;
   const bf16_t* Q = qkv + ((long)b * S) * ld + h * 64;
   const bf16_t* DC = dc + ((long)b * S) * H + h * 64;
-  const int jb = blockIdx.x;
+  const int jb = fl_seq_block();
   const int kbase = jb * ATT_KC + wave * ATT_ROWS;       // first key row of this wave
   const bool active = kbase < S;
   const int m = lane & 15, g = lane >> 4;
