@@ -74,8 +74,21 @@ typedef struct {
   double dropout_p;  /* [0,1); the keep threshold is floor(dropout_p * 2^16) in double    */
   uint64_t seed;     /* dropout key                                                       */
   uint32_t layer_id; /* folded into the dropout counter (24 bits used)                    */
-  uint32_t reserved; /* must be 0                                                         */
+  uint32_t remat;    /* OR of raf_remat_bits: tensors the forward pass does not keep      */
 } raf_layer_desc;
+
+/* Rematerialisation (Section 3.1.5): a tensor named here is not written to
+ * `saved` by raf_layer_fwd; raf_layer_bwd regenerates it in scratch by replaying
+ * the operator that produced it (same kernel, same inputs: bit-identical values,
+ * so every output of the step is unchanged).  Which tensors to name under a byte
+ * budget is what raf_remat_plan decides.
+ *   RAF_REMAT_QKV   the [T,3H] output of the QKV projection (replay: that product)
+ *   RAF_REMAT_CTX   the [T,H] attention context (replay: the attention forward
+ *                   kernel; RAF_ENOTSUP where attention is not taken on chip, i.e. RAF_F32)
+ *   RAF_REMAT_FFN1  the two [T,F] outputs of the first feed-forward product: the
+ *                   activation and the second tensor kept with it for the
+ *                   adjoint (replay: that product with its GeLU epilogue) */
+typedef enum { RAF_REMAT_QKV = 1, RAF_REMAT_CTX = 2, RAF_REMAT_FFN1 = 4 } raf_remat_bits;
 
 /* The twelve parameter tensors of a layer, or their gradients.
  * Shapes ([out,in] row-major for matrices): w_qkv [3H,H] (rows: Q block, K

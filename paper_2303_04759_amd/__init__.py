@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libraf_mi355.so")
 RAF_F32, RAF_BF16_AMP = 0, 1
 RAF_OK, RAF_EINVAL, RAF_ENOTSUP, RAF_EWORKSPACE, RAF_EHIP = 0, -1, -2, -3, -4
 RAF_LOSS_PARTIALS = 1024
+RAF_REMAT_QKV, RAF_REMAT_CTX, RAF_REMAT_FFN1 = 1, 2, 4
 EPI_NONE, EPI_BIAS, EPI_BIAS_GELU, EPI_MUL_GELU_GRAD, EPI_ADD_RES, EPI_BIAS_GELU_DERIV, EPI_MUL_AUX = range(7)
 
 PARAM_NAMES = ("w_qkv", "b_qkv", "w_o", "b_o", "ln1_g", "ln1_b",
@@ -34,7 +35,7 @@ class LayerDesc(C.Structure):
     _fields_ = [("batch", C.c_int32), ("seq", C.c_int32), ("hidden", C.c_int32), ("heads", C.c_int32),
                 ("ffn", C.c_int32), ("pre_ln", C.c_int32), ("causal", C.c_int32), ("gelu_tanh", C.c_int32),
                 ("precision", C.c_int32), ("ln_eps", C.c_float), ("dropout_p", C.c_double),
-                ("seed", C.c_uint64), ("layer_id", C.c_uint32), ("reserved", C.c_uint32)]
+                ("seed", C.c_uint64), ("layer_id", C.c_uint32), ("remat", C.c_uint32)]
 
 
 class LayerTensors(C.Structure):
@@ -181,7 +182,7 @@ def make_desc(cfg):
     return LayerDesc(batch=cfg["batch"], seq=cfg["seq"], hidden=cfg["hidden"], heads=cfg["heads"], ffn=cfg["ffn"],
                      pre_ln=cfg.get("pre_ln", 0), causal=cfg.get("causal", 0), gelu_tanh=cfg.get("gelu_tanh", 0),
                      precision=cfg["precision"], ln_eps=cfg["ln_eps"], dropout_p=cfg["dropout_p"],
-                     seed=cfg["seed"], layer_id=cfg.get("layer_id", 0), reserved=0)
+                     seed=cfg["seed"], layer_id=cfg.get("layer_id", 0), remat=cfg.get("remat", 0))
 
 
 def make_tensors(d):
