@@ -332,6 +332,97 @@ raf_status raf_op_dropout_residual_ln_bwd(const raf_layer_desc *desc, int32_t si
                                           float *dbeta, float *dbias, float *partial, uint64_t step,
                                           void *hip_stream);
 
+/* ---- Memory passes on an operator list (host only, no GPU work; Sections 3.1.4
+ * "operator scheduling" and 3.1.5 "rematerialization").  The paper names the
+ * ingredients and prints no formulas; the rules used are stated with each call.
+ *
+ * An operator list in execution order, in CSR form.  A tensor has at most one
+ * producer and must be produced before its first reader; a tensor that no operator
+ * produces is external (parameters, inputs) and counts as resident throughout.
+ * Duplicate ids inside one operator's list count once.  All arrays are host memory,
+ * read only, owned by the caller. */
+typedef enum { RAF_TENSOR_REMAT_OK = 1, RAF_TENSOR_PERSISTENT = 2 } raf_tensor_flags;
+typedef struct {
+  int32_t n_ops, n_tensors;
+  const int32_t *in_begin;  /* [n_ops+1] offsets into in_ids: tensors op k reads        */
+  const int32_t *in_ids;
+  const int32_t *out_begin; /* [n_ops+1] offsets into out_ids: tensors op k writes      */
+  const int32_t *out_ids;
+  const double *latency;    /* [n_ops] run time of the operator, any unit, >= 0          */
+  const int64_t *bytes;     /* [n_tensors] >= 0                                          */
+  const uint8_t *flags;     /* [n_tensors] raf_tensor_flags: REMAT_OK = an intermediate
+                               that may be dropped and regenerated; PERSISTENT = must
+                               outlive the list (a result)                               */
+} raf_op_graph;
+
+/* Liveness estimate: mem_out[p] = bytes of all tensors alive while item p of the
+ * sequence runs (its inputs and outputs included).  A tensor is alive from the item
+ * that writes it to the last item that reads it before it is written again.
+ *   sequence: item k >= 0 runs operator k; item -1-t replays the producer of tensor
+ *   t and regenerates t alone.  NULL = operators 0..n_ops-1 in order (seq_len unused).
+ * RAF_EINVAL for a malformed graph or a sequence that reads a tensor before it exists. */
+raf_status raf_memory_profile(const raf_op_graph *graph, const int32_t *sequence, int32_t seq_len,
+                              int64_t *mem_out /* [seq_len or n_ops] */);
+
+/* Operator scheduling (Section 3.1.4): with p the bytes an operator produces and c
+ * the bytes that can be released once it has run, operators with p - c < 0 move
+ * forward and those with p - c > 0 backward.  Taken as list scheduling: of the
+ * operators whose inputs exist, the one with the smallest p - c runs next (ties in
+ * the given order).  order_out [n_ops]: a permutation of the operators that respects
+ * every dependence. */
+raf_status raf_schedule_ops(const raf_op_graph *graph, int32_t *order_out);
+
+typedef struct {
+  int64_t peak_before;  /* liveness estimate of the given order                            */
+  int64_t peak_after;   /* of the sequence with replays                                    */
+  int32_t fits;         /* 1 if every point is within the budget                           */
+  int32_t reserved;
+  double extra_latency; /* sum of the replayed operators' latencies                        */
+} raf_remat_summary;
+
+/* Rematerialisation (Section 3.1.5): the order is walked once; where the liveness
+ * estimate exceeds budget_bytes, alive intermediates are dropped in ascending cost
+ *   latency(producer) * (readers still to come) / bytes     (ties: larger, lower id)
+ * and a replay of the producer is placed directly in front of the next reader, until
+ * the point fits or nothing qualifies.  A tensor qualifies if it is REMAT_OK, the
+ * current item neither reads nor writes it, its next reader is not the very next
+ * item, and every input of its producer is still alive where the replay goes (one
+ * operator is replayed, never a chain).
+ *   sequence_out [sequence_cap], *sequence_len: the order with replays (item coding
+ *     as in raf_memory_profile); evicted_tensor/evicted_pos [evicted_cap], *n_evicted:
+ *     which tensor was dropped at which position of the final sequence.
+ * RAF_EWORKSPACE if a capacity is too small (the needed lengths and the summary are
+ * still written; 9*n_ops+8 items always suffice). */
+raf_status raf_remat_plan(const raf_op_graph *graph, int64_t budget_bytes, int32_t *sequence_out,
+                          int32_t sequence_cap, int32_t *sequence_len, int32_t *evicted_tensor,
+                          int32_t *evicted_pos, int32_t evicted_cap, int32_t *n_evicted,
+                          raf_remat_summary *summary);
+
+/* The operator list of `layers` identical layers run forward, a loss seed, and
+ * backward (the kernels of raf_layer_fwd / raf_layer_bwd in launch order, the grouped
+ * weight-gradient launch last in each layer), activations only: parameters,
+ * gradients and optimizer state are outside this budget.  Tensors that raf_layer_desc
+ * .remat can drop carry REMAT_OK, with owner_layer / owner_bit naming layer and bit
+ * (else -1 / 0); the context qualifies only where attention runs on chip.
+ *   replay_us [3] or NULL: measured run times of the QKV product, the attention
+ *   forward kernel and the first feed-forward product; NULL = an estimate from the
+ *   operation counts (800 TFLOP/s, 4 TB/s).
+ * Two-call protocol: with in_begin == NULL only sizes->n_ops, sizes->n_tensors,
+ * *n_in_ids and *n_out_ids are written; then call again with arrays of those sizes
+ * (in_begin/out_begin n_ops+1). */
+raf_status raf_layer_stack_graph(const raf_layer_desc *desc, int32_t layers, const double *replay_us,
+                                 raf_op_graph *sizes, int32_t *in_begin, int32_t *in_ids, int32_t *out_begin,
+                                 int32_t *out_ids, double *latency, int64_t *bytes, uint8_t *flags,
+                                 int32_t *owner_layer, int32_t *owner_bit, int32_t *n_in_ids, int32_t *n_out_ids);
+
+/* raf_remat_plan on that list: remat_out [layers] receives the raf_layer_desc.remat
+ * value of every layer under an activation budget of budget_bytes.  The kernels
+ * replay a dropped tensor at the start of the layer's backward call rather than in
+ * front of its reader; replayed tensors sit in the scratch buffer all layers share,
+ * so the peak is not affected. */
+raf_status raf_layer_stack_remat(const raf_layer_desc *desc, int32_t layers, int64_t budget_bytes,
+                                 const double *replay_us, uint32_t *remat_out, raf_remat_summary *summary);
+
 const char *raf_status_string(raf_status s);
 const char *raf_last_hip_error(void);
 /* Library version string, e.g. "raf_mi355 0.1 gfx950". */

@@ -71,6 +71,18 @@ class ScalerState(C.Structure):
                 ("t", C.c_int64), ("lr_over_bc1", C.c_float), ("inv_bc2", C.c_float)]
 
 
+class OpGraph(C.Structure):
+    _fields_ = [("n_ops", C.c_int32), ("n_tensors", C.c_int32), ("in_begin", C.POINTER(C.c_int32)),
+                ("in_ids", C.POINTER(C.c_int32)), ("out_begin", C.POINTER(C.c_int32)),
+                ("out_ids", C.POINTER(C.c_int32)), ("latency", C.POINTER(C.c_double)),
+                ("bytes", C.POINTER(C.c_int64)), ("flags", C.POINTER(C.c_uint8))]
+
+
+class RematSummary(C.Structure):
+    _fields_ = [("peak_before", C.c_int64), ("peak_after", C.c_int64), ("fits", C.c_int32), ("reserved", C.c_int32),
+                ("extra_latency", C.c_double)]
+
+
 _lib = None
 
 _SIGNATURES = {
@@ -115,6 +127,18 @@ _SIGNATURES = {
     "raf_op_ln_bwd_partial_floats": (C.c_size_t, [C.c_int32, C.c_int64]),
     "raf_op_dropout_residual_ln_bwd": (C.c_int, [C.POINTER(LayerDesc), C.c_int32, C.c_int64] + [C.c_void_p] * 13 +
                                        [C.c_uint64, C.c_void_p]),
+    "raf_memory_profile": (C.c_int, [C.POINTER(OpGraph), C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_int64)]),
+    "raf_schedule_ops": (C.c_int, [C.POINTER(OpGraph), C.POINTER(C.c_int32)]),
+    "raf_remat_plan": (C.c_int, [C.POINTER(OpGraph), C.c_int64, C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_int32),
+                                 C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_int32),
+                                 C.POINTER(RematSummary)]),
+    "raf_layer_stack_graph": (C.c_int, [C.POINTER(LayerDesc), C.c_int32, C.POINTER(C.c_double), C.POINTER(OpGraph),
+                                        C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                        C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_int64),
+                                        C.POINTER(C.c_uint8), C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                        C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
+    "raf_layer_stack_remat": (C.c_int, [C.POINTER(LayerDesc), C.c_int32, C.c_int64, C.POINTER(C.c_double),
+                                        C.POINTER(C.c_uint32), C.POINTER(RematSummary)]),
     "raf_status_string": (C.c_char_p, [C.c_int]),
     "raf_last_hip_error": (C.c_char_p, []),
     "raf_version": (C.c_char_p, []),
@@ -359,3 +383,90 @@ def raf_mlm_head_fwd_bwd(desc, w, x, sel, labels, loss_scale, loss_out, dx, grad
     _check(load_library().raf_mlm_head_fwd_bwd(C.byref(desc), C.byref(w), _ptr(x), _ptr(sel), _ptr(labels),
                                                float(loss_scale), _ptr(loss_out), _ptr(dx), C.byref(grads),
                                                _ptr(scratch), _stream(stream)), "raf_mlm_head_fwd_bwd")
+
+
+# ---- memory passes on an operator list (host only).  A graph is a dict(ops=[dict(inputs, outputs, latency)],
+# tensors=[dict(bytes, remat_ok, persistent)]); the wrappers only lay it out in the C structure.
+RAF_TENSOR_REMAT_OK, RAF_TENSOR_PERSISTENT = 1, 2
+
+
+class _GraphArrays:
+    def __init__(self, graph):
+        ops, tensors = graph["ops"], graph["tensors"]
+        in_begin, in_ids, out_begin, out_ids = [0], [], [0], []
+        for op in ops:
+            in_ids += list(op["inputs"])
+            out_ids += list(op["outputs"])
+            in_begin.append(len(in_ids))
+            out_begin.append(len(out_ids))
+        self.keep = [(C.c_int32 * len(in_begin))(*in_begin), (C.c_int32 * max(1, len(in_ids)))(*in_ids),
+                     (C.c_int32 * len(out_begin))(*out_begin), (C.c_int32 * max(1, len(out_ids)))(*out_ids),
+                     (C.c_double * max(1, len(ops)))(*[float(op["latency"]) for op in ops]),
+                     (C.c_int64 * max(1, len(tensors)))(*[int(t["bytes"]) for t in tensors]),
+                     (C.c_uint8 * max(1, len(tensors)))(*[(RAF_TENSOR_REMAT_OK if t["remat_ok"] else 0) |
+                                                          (RAF_TENSOR_PERSISTENT if t["persistent"] else 0)
+                                                          for t in tensors])]
+        k = self.keep
+        self.c = OpGraph(len(ops), len(tensors), k[0], k[1], k[2], k[3], k[4], k[5], k[6])
+
+
+def raf_memory_profile(graph, sequence=None):
+    g = _GraphArrays(graph)
+    n = len(graph["ops"]) if sequence is None else len(sequence)
+    out = (C.c_int64 * max(1, n))()
+    seq = None if sequence is None else (C.c_int32 * max(1, n))(*sequence)
+    _check(load_library().raf_memory_profile(C.byref(g.c), seq, n, out), "raf_memory_profile")
+    return list(out[:n])
+
+
+def raf_schedule_ops(graph):
+    g = _GraphArrays(graph)
+    n = len(graph["ops"])
+    out = (C.c_int32 * max(1, n))()
+    _check(load_library().raf_schedule_ops(C.byref(g.c), out), "raf_schedule_ops")
+    return list(out[:n])
+
+
+def raf_remat_plan(graph, budget):
+    g = _GraphArrays(graph)
+    cap = 9 * len(graph["ops"]) + 8
+    seq, ev_t, ev_p = (C.c_int32 * cap)(), (C.c_int32 * cap)(), (C.c_int32 * cap)()
+    n_seq, n_ev, summ = C.c_int32(), C.c_int32(), RematSummary()
+    _check(load_library().raf_remat_plan(C.byref(g.c), int(budget), seq, cap, C.byref(n_seq), ev_t, ev_p, cap,
+                                         C.byref(n_ev), C.byref(summ)), "raf_remat_plan")
+    return dict(sequence=list(seq[:n_seq.value]), evicted=list(zip(ev_t[:n_ev.value], ev_p[:n_ev.value])),
+                peak_before=summ.peak_before, peak_after=summ.peak_after, fits=bool(summ.fits),
+                extra_latency=summ.extra_latency)
+
+
+def raf_layer_stack_graph(desc, layers, replay_us=None):
+    """The library's operator list of a layer stack as a graph dict, plus owner_layer / owner_bit per tensor."""
+    lib = load_library()
+    rep = None if replay_us is None else (C.c_double * 3)(*replay_us)
+    sizes, n_in, n_out = OpGraph(), C.c_int32(), C.c_int32()
+    null32 = C.POINTER(C.c_int32)()
+    _check(lib.raf_layer_stack_graph(C.byref(desc), layers, rep, C.byref(sizes), null32, null32, null32, null32, None,
+                                     None, None, null32, null32, C.byref(n_in), C.byref(n_out)),
+           "raf_layer_stack_graph")
+    no, nt = sizes.n_ops, sizes.n_tensors
+    in_begin, in_ids = (C.c_int32 * (no + 1))(), (C.c_int32 * max(1, n_in.value))()
+    out_begin, out_ids = (C.c_int32 * (no + 1))(), (C.c_int32 * max(1, n_out.value))()
+    lat, byt, flg = (C.c_double * no)(), (C.c_int64 * nt)(), (C.c_uint8 * nt)()
+    own_l, own_b = (C.c_int32 * nt)(), (C.c_int32 * nt)()
+    _check(lib.raf_layer_stack_graph(C.byref(desc), layers, rep, C.byref(sizes), in_begin, in_ids, out_begin, out_ids,
+                                     lat, byt, flg, own_l, own_b, C.byref(n_in), C.byref(n_out)),
+           "raf_layer_stack_graph")
+    ops = [dict(inputs=list(in_ids[in_begin[k]:in_begin[k + 1]]), outputs=list(out_ids[out_begin[k]:out_begin[k + 1]]),
+                latency=lat[k]) for k in range(no)]
+    tensors = [dict(bytes=byt[t], remat_ok=bool(flg[t] & RAF_TENSOR_REMAT_OK),
+                    persistent=bool(flg[t] & RAF_TENSOR_PERSISTENT)) for t in range(nt)]
+    return dict(ops=ops, tensors=tensors), list(own_l), list(own_b)
+
+
+def raf_layer_stack_remat(desc, layers, budget, replay_us=None):
+    rep = None if replay_us is None else (C.c_double * 3)(*replay_us)
+    masks, summ = (C.c_uint32 * layers)(), RematSummary()
+    _check(load_library().raf_layer_stack_remat(C.byref(desc), layers, int(budget), rep, masks, C.byref(summ)),
+           "raf_layer_stack_remat")
+    return list(masks), dict(peak_before=summ.peak_before, peak_after=summ.peak_after, fits=bool(summ.fits),
+                             extra_latency=summ.extra_latency)

@@ -348,6 +348,8 @@ raf_status launch_softmax_bwd(const raf_layer_desc& d, const void* prob, const v
 // S <= 128 in bf16 AMP: no S x S tensor reaches memory.  Forward: ctx = P~ . V written to [T,H], the probabilities
 // are not stored.  Backward: P and the dropout mask are recomputed from qkv, the same lens and the same step; dQ, dK
 // and dV are written to dqkv [T,3H].
+// field and shape checks shared by every entry point that takes a layer description (layer.hip)
+raf_status validate_desc(const raf_layer_desc* d);
 bool attn_fused_supported(const raf_layer_desc& d);
 raf_status launch_attn_fwd_fused(const raf_layer_desc& d, const void* qkv, const int32_t* lens, void* ctx, uint64_t step,
                                  hipStream_t st);

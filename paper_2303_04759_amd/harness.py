@@ -98,7 +98,8 @@ class DeviceModel:
     EMBED = ("word", "pos", "emb_ln_g", "emb_ln_b")
     HEAD = ("head_w", "head_b", "head_ln_g", "head_ln_b", "dec_b")
 
-    def __init__(self, cfg, inputs, adam, device="cuda:0"):
+    def __init__(self, cfg, inputs, adam, device="cuda:0", remat=None):
+        """remat: per-layer raf_layer_desc.remat values (as raf_layer_stack_remat returns them), or None."""
         from . import (make_embed_desc, make_mlm_desc, make_mlm_tensors, raf_embed_workspace, raf_mlm_workspace)
         if not torch.cuda.is_available():
             raise RuntimeError("DeviceModel needs a GPU; there is no CPU path")
@@ -130,13 +131,15 @@ class DeviceModel:
         for l in range(self.L):
             c = dict(cfg)
             c["layer_id"] = cfg["layer_id_base"] + l
+            c["remat"] = int(remat[l]) if remat is not None else 0
             self.ldesc.append(make_desc(c))
         esv, esc = raf_embed_workspace(self.edesc)
-        lsv, lsc = raf_layer_workspace(self.ldesc[0]) if self.L else (256, 256)
+        lws = [raf_layer_workspace(d) for d in self.ldesc]
         msc = raf_mlm_workspace(self.mdesc)
         u8 = lambda n: torch.empty(max(int(n), 256), dtype=torch.uint8, device=dev)
-        self.esaved, self.scratch = u8(esv), u8(max(esc, lsc, msc))
-        self.lsaved = [u8(lsv) for _ in range(self.L)]
+        self.esaved, self.scratch = u8(esv), u8(max([esc, msc] + [sc for _, sc in lws]))
+        self.lsaved = [u8(sv) for sv, _ in lws]
+        self.saved_bytes = sum(sv for sv, _ in lws)
         act = lambda: torch.empty(self.T, H, dtype=cd, device=dev)
         self.x = [act() for _ in range(self.L + 1)]       # x[0] = embedding output, x[l+1] = layer l output
         self.dx = [act(), act()]                          # ping-pong gradient buffers

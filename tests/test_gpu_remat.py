@@ -8,8 +8,8 @@ import pytest
 import torch
 
 import paper_2303_04759_amd as raf
-from paper_2303_04759_amd.harness import DeviceLayer
-from workloads.synthetic import ADAM, CONFIGS, PARAM_NAMES, make_layer_inputs
+from paper_2303_04759_amd.harness import DeviceLayer, DeviceModel
+from workloads.synthetic import ADAM, CONFIGS, MODEL_CONFIGS, PARAM_NAMES, make_layer_inputs, make_model_inputs
 
 from gpu_util import announce
 from test_gpu_layer import run_and_compare
@@ -85,3 +85,27 @@ def test_rematerialisation_argument_checks():
         raf.raf_layer_workspace(raf.make_desc(dict(cfg, remat=8)))       # unknown bit
     with pytest.raises(raf.RafError):
         raf.raf_layer_workspace(raf.make_desc(dict(cfg, remat=CTX)))     # fp32: attention is not on chip
+
+
+def test_planned_model_step_is_bit_identical():
+    """Layer stack planned under half of its liveness estimate: same loss, gradients and weights as the model that
+    keeps everything, with the saved buffers smaller by what the plan drops."""
+    announce("remat planned model")
+    cfg = dict(MODEL_CONFIGS["bert_base_12l_mlm"], batch=8, layers=4, vocab=2000)
+    inp = make_model_inputs(cfg, seed=6)
+    desc = raf.make_desc(dict(cfg, layer_id=0))
+    graph, own_l, own_b = raf.raf_layer_stack_graph(desc, cfg["layers"])
+    peak = max(raf.raf_memory_profile(graph))
+    masks, summ = raf.raf_layer_stack_remat(desc, cfg["layers"], peak // 2)
+    assert summ["fits"] and summ["peak_after"] <= peak // 2 and any(masks)
+    base, plan = DeviceModel(cfg, inp, ADAM), DeviceModel(cfg, inp, ADAM, remat=masks)
+    dropped = sum(graph["tensors"][t]["bytes"] for t in range(len(own_l)) if own_b[t] & masks[own_l[t]])
+    assert base.saved_bytes - plan.saved_bytes == dropped > 0
+    for t in (1, 2):
+        base.train_step(t)
+        plan.train_step(t)
+    torch.cuda.synchronize()
+    assert torch.equal(base.loss, plan.loss)
+    for k in base.master:
+        assert torch.equal(base.grads[k], plan.grads[k]), k
+        assert torch.equal(base.master[k], plan.master[k]), k
