@@ -50,6 +50,51 @@ def gemm_launches(cfg):
     ]
 
 
+def measure_replay_us(cfg):
+    """Run times (us) of the three operators a rematerialising layer replays — the QKV product, the attention
+    forward kernel, the first feed-forward product with its GeLU epilogue — timed back to back on synthetic
+    operands of the workload's shape: the latencies the rematerialisation planner is given."""
+    import torch
+    import paper_2303_04759_amd as raf
+    dev = torch.device("cuda:0")
+    T, H, F = cfg["batch"] * cfg["seq"], cfg["hidden"], cfg["ffn"]
+    prec = cfg["precision"]
+    cd = torch.bfloat16 if prec == 1 else torch.float32
+    g = torch.Generator(device="cpu").manual_seed(0)
+    rnd = lambda *shape: (torch.randn(*shape, generator=g) * 0.05).to(dev).to(cd).contiguous()
+    x, wqkv, w1 = rnd(T, H), rnd(3 * H, H), rnd(F, H)
+    bqkv, b1 = torch.zeros(3 * H, device=dev), torch.zeros(F, device=dev)
+    qkv, ctx = torch.empty(T, 3 * H, dtype=cd, device=dev), torch.empty(T, H, dtype=cd, device=dev)
+    gact, aux = torch.empty(T, F, dtype=cd, device=dev), torch.empty(T, F, dtype=cd, device=dev)
+    lse = torch.empty(cfg["batch"] * cfg["heads"] * cfg["seq"], dtype=torch.float32, device=dev)
+    desc = raf.make_desc(dict(cfg, layer_id=0))
+    stream = torch.cuda.Stream()
+    epi = raf.EPI_BIAS_GELU_DERIV if prec == 1 else raf.EPI_BIAS_GELU
+    ops = [lambda: raf.raf_op_gemm(prec, T, 3 * H, H, x, H, 1, wqkv, H, 1, qkv, 3 * H, epilogue=raf.EPI_BIAS,
+                                   bias=bqkv, stream=stream),
+           lambda: raf.raf_op_attention_fwd(desc, qkv, None, ctx, lse, 1, stream),
+           lambda: raf.raf_op_gemm(prec, T, F, H, x, H, 1, w1, H, 1, gact, F, epilogue=epi, bias=b1, aux=aux,
+                                   gelu_tanh=cfg["gelu_tanh"], stream=stream)]
+    if prec != 1:
+        ops[1] = None           # attention is not one operator there (and its context is not droppable)
+    out = []
+    with torch.cuda.stream(stream):
+        for op in ops:
+            if op is None:
+                out.append(0.0)
+                continue
+            for _ in range(3):
+                op()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(20):
+                op()
+            e1.record(stream)
+            stream.synchronize()
+            out.append(e0.elapsed_time(e1) * 1000.0 / 20)
+    return out
+
+
 def bench_model(args, cfg):
     """Whole 12-layer model step (embedding, layers, MLM head, backward, Adam over all tensors)."""
     import numpy as np
@@ -62,11 +107,13 @@ def bench_model(args, cfg):
         # rematerialisation under a budget given as a fraction of the liveness estimate of the layer stack
         import paper_2303_04759_amd as raf
         desc = raf.make_desc(dict(cfg, layer_id=0))
-        graph_l, _, _ = raf.raf_layer_stack_graph(desc, cfg["layers"])
+        replay_us = None if args.estimated_replay_latency else measure_replay_us(cfg)
+        graph_l, _, _ = raf.raf_layer_stack_graph(desc, cfg["layers"], replay_us)
         peak = max(raf.raf_memory_profile(graph_l))
         budget = int(peak * args.activation_budget_frac)
-        remat, summ = raf.raf_layer_stack_remat(desc, cfg["layers"], budget)
+        remat, summ = raf.raf_layer_stack_remat(desc, cfg["layers"], budget, replay_us)
         remat_info = {"budget_bytes": budget, "layer_bits": remat, "planned_peak_bytes": summ["peak_after"],
+                      "replay_us": replay_us if replay_us is not None else "library estimate",
                       "unplanned_peak_bytes": summ["peak_before"], "fits": summ["fits"],
                       "planned_extra_us": summ["extra_latency"]}
     mod = DeviceModel(cfg, inp, ADAM, remat=remat)
@@ -131,6 +178,9 @@ def main():
     ap.add_argument("--activation-budget-frac", type=float, default=1.0,
                     help="model workloads: plan rematerialisation for an activation budget of this fraction of the "
                          "layer stack's liveness estimate (1.0 = keep everything)")
+    ap.add_argument("--estimated-replay-latency", action="store_true",
+                    help="with --activation-budget-frac: plan with the library's operation-count estimate of the "
+                         "replay latencies instead of timing the three replayed operators first")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (5x) so FETCH_SIZE/WRITE_SIZE counters can be scaled")
     args = ap.parse_args()
