@@ -109,3 +109,18 @@ def test_layer_stack_plan(name, over, layers):
     g2, _, _ = raf.raf_layer_stack_graph(desc, 1)
     lat = sorted(op["latency"] for op in g2["ops"] if op["latency"] > 0)
     assert len(lat) == 3 and lat[0] > 0
+
+
+@pytest.mark.parametrize("name,layers", [("bert_base", 12), ("gpt2_medium", 4)])
+def test_scheduling_rule_on_the_layer_stack(name, layers):
+    """The p - c rule applied to the library's own launch order: same order from library and oracle, still
+    executable, and no higher in peak (the peak sits at the turn from forward to backward, which no order moves)."""
+    graph, _, _ = raf.raf_layer_stack_graph(raf.make_desc(CONFIGS[name]), layers)
+    order = raf.raf_schedule_ops(graph)
+    assert order == memplan.schedule_ops(graph) and sorted(order) == list(range(len(order)))
+    moved = memplan.apply_order(graph, order)
+    assert max(raf.raf_memory_profile(moved)) <= max(raf.raf_memory_profile(graph))
+    # forward launches keep their places: nothing there releases memory early
+    n_fwd = next(k for k, op in enumerate(graph["ops"]) if any(graph["tensors"][t]["persistent"] for t in op["outputs"]))
+    first_moved = next((i for i, k in enumerate(order) if i != k), len(order))
+    assert first_moved > n_fwd // 2
