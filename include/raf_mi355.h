@@ -48,7 +48,7 @@ typedef enum {
   RAF_OK = 0,
   RAF_EINVAL = -1,     /* null / misaligned pointer, bad field value            */
   RAF_ENOTSUP = -2,    /* well-formed but outside the supported shapes          */
-  RAF_EWORKSPACE = -3, /* reserved                                              */
+  RAF_EWORKSPACE = -3, /* an output capacity given by the caller is too small      */
   RAF_EHIP = -4        /* a HIP launch failed; see raf_last_hip_error()         */
 } raf_status;
 

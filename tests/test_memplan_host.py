@@ -124,3 +124,17 @@ def test_scheduling_rule_on_the_layer_stack(name, layers):
     n_fwd = next(k for k, op in enumerate(graph["ops"]) if any(graph["tensors"][t]["persistent"] for t in op["outputs"]))
     first_moved = next((i for i, k in enumerate(order) if i != k), len(order))
     assert first_moved > n_fwd // 2
+
+
+def test_plan_capacity_error_reports_needed_lengths():
+    """Too small an output capacity: RAF_EWORKSPACE, with the needed lengths and the summary still written."""
+    import ctypes as C
+    lib = raf.load_library()
+    g = raf._GraphArrays(CHAIN)
+    seq, ev_t, ev_p = (C.c_int32 * 4)(), (C.c_int32 * 4)(), (C.c_int32 * 4)()
+    n_seq, n_ev, summ = C.c_int32(), C.c_int32(), raf.RematSummary()
+    rc = lib.raf_remat_plan(C.byref(g.c), 12, seq, 4, C.byref(n_seq), ev_t, ev_p, 4, C.byref(n_ev), C.byref(summ))
+    assert rc == raf.RAF_EWORKSPACE
+    assert (n_seq.value, n_ev.value, summ.peak_before, summ.peak_after, summ.fits) == (8, 1, 15, 11, 1)
+    assert lib.raf_remat_plan(None, 12, seq, 4, C.byref(n_seq), ev_t, ev_p, 4, C.byref(n_ev), C.byref(summ)) == raf.RAF_EINVAL
+    assert lib.raf_remat_plan(C.byref(g.c), 12, seq, 4, None, ev_t, ev_p, 4, C.byref(n_ev), C.byref(summ)) == raf.RAF_EINVAL
