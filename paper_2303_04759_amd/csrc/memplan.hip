@@ -411,7 +411,7 @@ extern "C" raf_status raf_layer_stack_graph(const raf_layer_desc* desc, int32_t 
                                             int32_t* n_in_ids, int32_t* n_out_ids) {
   raf_status rc = validate_desc(desc);
   if (rc != RAF_OK) return rc;
-  if (layers < 1 || layers > 4096 || !sizes || !n_in_ids || !n_out_ids) return RAF_EINVAL;
+  if (layers < 1 || layers > 512 || !sizes || !n_in_ids || !n_out_ids) return RAF_EINVAL;
   StackGraph S;
   if (!build_stack(*desc, layers, replay_us, S)) return RAF_EINVAL;
   sizes->n_ops = (int32_t)S.lat.size();
@@ -436,7 +436,7 @@ extern "C" raf_status raf_layer_stack_remat(const raf_layer_desc* desc, int32_t 
                                             const double* replay_us, uint32_t* remat_out, raf_remat_summary* summary) {
   raf_status rc = validate_desc(desc);
   if (rc != RAF_OK) return rc;
-  if (layers < 1 || layers > 4096 || !remat_out || !summary) return RAF_EINVAL;
+  if (layers < 1 || layers > 512 || !remat_out || !summary) return RAF_EINVAL;
   StackGraph S;
   if (!build_stack(*desc, layers, replay_us, S)) return RAF_EINVAL;
   const raf_op_graph g = view(S);

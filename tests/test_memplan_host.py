@@ -138,3 +138,14 @@ def test_plan_capacity_error_reports_needed_lengths():
     assert (n_seq.value, n_ev.value, summ.peak_before, summ.peak_after, summ.fits) == (8, 1, 15, 11, 1)
     assert lib.raf_remat_plan(None, 12, seq, 4, C.byref(n_seq), ev_t, ev_p, 4, C.byref(n_ev), C.byref(summ)) == raf.RAF_EINVAL
     assert lib.raf_remat_plan(C.byref(g.c), 12, seq, 4, None, ev_t, ev_p, 4, C.byref(n_ev), C.byref(summ)) == raf.RAF_EINVAL
+
+
+def test_layer_stack_argument_checks():
+    desc = raf.make_desc(CONFIGS["tiny"])
+    for layers in (0, -1, 513):
+        with pytest.raises(raf.RafError):
+            raf.raf_layer_stack_remat(desc, layers, 1 << 30)
+        with pytest.raises(raf.RafError):
+            raf.raf_layer_stack_graph(desc, layers)
+    with pytest.raises(raf.RafError):
+        raf.raf_layer_stack_remat(desc, 2, 1 << 30, [1.0, -1.0, 1.0])      # negative latency
