@@ -465,8 +465,8 @@ def raf_layer_stack_graph(desc, layers, replay_us=None):
 
 def raf_layer_stack_remat(desc, layers, budget, replay_us=None):
     rep = None if replay_us is None else (C.c_double * 3)(*replay_us)
-    masks, summ = (C.c_uint32 * layers)(), RematSummary()
+    masks, summ = (C.c_uint32 * max(1, layers))(), RematSummary()
     _check(load_library().raf_layer_stack_remat(C.byref(desc), layers, int(budget), rep, masks, C.byref(summ)),
            "raf_layer_stack_remat")
-    return list(masks), dict(peak_before=summ.peak_before, peak_after=summ.peak_after, fits=bool(summ.fits),
+    return list(masks[:layers]), dict(peak_before=summ.peak_before, peak_after=summ.peak_after, fits=bool(summ.fits),
                              extra_latency=summ.extra_latency)
