@@ -109,3 +109,39 @@ def test_planned_model_step_is_bit_identical():
     for k in base.master:
         assert torch.equal(base.grads[k], plan.grads[k]), k
         assert torch.equal(base.master[k], plan.master[k]), k
+
+
+def test_rematerialised_step_replays_in_a_graph():
+    """The rematerialising step is launches only (no memset or copy nodes): captured once and replayed, with eager
+    work and synchronisations between the replays, every replay must leave what the eager kept-activations step
+    leaves (same dropout step, weights restored before each replay)."""
+    announce("remat graph replay")
+    cfg0 = dict(CONFIGS["bert_base"], batch=4)
+    inp = make_layer_inputs(cfg0, seed=8, random_affine=True)
+    base = DeviceLayer(cfg0, inp, ADAM)
+    lay = DeviceLayer(dict(cfg0, remat=QKV | CTX | FFN1), inp, ADAM)
+    state0 = {k: (lay.master[k].clone(), None if lay.lowp[k] is None else lay.lowp[k].clone()) for k in PARAM_NAMES}
+    base.train_step(3)
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        lay.train_step(1, stream)                     # warm-up outside the graph
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            lay.train_step(3, stream)
+        for _ in range(3):
+            for k in PARAM_NAMES:                     # eager work between replays: back to the initial state
+                lay.master[k].copy_(state0[k][0])
+                if lay.lowp[k] is not None:
+                    lay.lowp[k].copy_(state0[k][1])
+                lay.m[k].zero_()
+                lay.v[k].zero_()
+            lay.y.zero_()
+            stream.synchronize()
+            graph.replay()
+            stream.synchronize()
+            assert torch.equal(lay.y, base.y) and torch.equal(lay.dx, base.dx) and torch.equal(lay.loss, base.loss)
+            for k in PARAM_NAMES:
+                assert torch.equal(lay.grads[k], base.grads[k]), k
+                assert torch.equal(lay.master[k], base.master[k]), k
