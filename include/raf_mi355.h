@@ -368,8 +368,10 @@ raf_status raf_memory_profile(const raf_op_graph *graph, const int32_t *sequence
  * the bytes that can be released once it has run, operators with p - c < 0 move
  * forward and those with p - c > 0 backward.  Taken as list scheduling: of the
  * operators whose inputs exist, the one with the smallest p - c runs next (ties in
- * the given order).  order_out [n_ops]: a permutation of the operators that respects
- * every dependence. */
+ * the given order).  c counts the inputs whose other readers have all run, and
+ * outputs that nothing reads (unless PERSISTENT).  The list only has to be acyclic
+ * here (RAF_EINVAL otherwise).  order_out [n_ops]: a permutation of the operators
+ * that respects every dependence. */
 raf_status raf_schedule_ops(const raf_op_graph *graph, int32_t *order_out);
 
 typedef struct {
