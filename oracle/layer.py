@@ -91,6 +91,13 @@ def masked_softmax(s, masked):
     return np.where(den > 0, e / np.where(den > 0, den, 1.0), 0.0)
 
 
+def softmax_dropout_bwd(prob, keep, scale, dprob_d):
+    """Adjoint of prob_d = softmax(s) * keep * scale with respect to s, given dprob_d:
+    dprob = dprob_d * keep * scale;  ds = prob * (dprob - sum_j dprob * prob)."""
+    dprob = dprob_d * keep * scale
+    return prob * (dprob - (dprob * prob).sum(axis=-1, keepdims=True))
+
+
 def _keep(cfg, site, step, shape):
     n = int(np.prod(shape))
     k = dropout_keep(cfg["seed"], cfg["layer_id"], site, step, n, cfg["dropout_p"])
@@ -139,8 +146,7 @@ def attention_core_backward(cfg, A, dc):
     dprob_d = np.einsum("bhid,bhjd->bhij", dc, A["v"])
     dv = np.einsum("bhij,bhid->bhjd", A["prob_d"], dc)
     # prob_d = prob * keep1 * scale ; prob = softmax(s)
-    dprob = dprob_d * A["keep1"] * scale
-    ds = A["prob"] * (dprob - (dprob * A["prob"]).sum(axis=-1, keepdims=True))
+    ds = softmax_dropout_bwd(A["prob"], A["keep1"], scale, dprob_d)
     # s = alpha q k^T
     dq = alpha * np.einsum("bhij,bhjd->bhid", ds, A["k"])
     dk = alpha * np.einsum("bhij,bhid->bhjd", ds, A["q"])

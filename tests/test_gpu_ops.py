@@ -181,13 +181,13 @@ def test_softmax_fwd_bwd(precision, B, S, causal, p):
     assert ((got == 0) == (ref == 0)).all() or precision == 1     # structural zeros: masked entries
     assert (got[np.broadcast_to(masked, got.shape)] == 0).all()
     assert (got_d[~keep] == 0).all()
-    # backward on the probabilities the device saved
+    # backward: the device works on the probabilities it saved, the reference is the oracle's adjoint on the
+    # oracle's own probabilities
     dpd = rnd(rng, (B, nh, S, S), precision)
     ds = torch.zeros_like(s_dev)
     raf.raf_op_softmax_bwd(desc, prob, prob_d, to_dev(dpd, dt), ds, 0.125)
     torch.cuda.synchronize()
-    dprob = dpd.astype(np.float64) * keep / (1 - p)
-    ref_ds = 0.125 * got * (dprob - (dprob * got).sum(-1, keepdims=True))
+    ref_ds = 0.125 * L.softmax_dropout_bwd(ref, keep, 1.0 / (1 - p), dpd.astype(np.float64))
     assert rel_fro(host(ds), ref_ds) <= BWD_TOL[precision]
     assert (host(ds)[np.broadcast_to(masked, got.shape)] == 0).all()
 
