@@ -14,8 +14,8 @@
  *     (Section 3, graph-generation phase);
  *   - elementwise / reduction operators are fused into their producers or with
  *     each other (Section 3.2.2).
- * The system "accepts a forward model and generates the training graph"
- * (Section 1); here the forward model is the plain-data descriptor below.
+ * The forward model is the only model input and the training graph is derived
+ * from it (Section 1); here the forward model is the plain-data descriptor below.
  *
  * General conventions (all entry points)
  *   - Every pointer marked [dev] is device memory owned by the caller; the
@@ -248,7 +248,8 @@ typedef struct {
   int32_t n_sel;     /* number of selected (masked) positions, >= 1             */
   int32_t precision; /* raf_precision */
   int32_t gelu_tanh;
-  float ln_eps;
+  float ln_eps;      /* > 0 (RAF_EINVAL otherwise): the selected rows are padded to the
+                        tile height with rows of zero variance                     */
   int32_t reserved;  /* must be 0 */
 } raf_mlm_desc;
 

@@ -730,13 +730,8 @@ raf_status launch_attn_bwd_full(const raf_layer_desc& d, const void* dc, const v
                                 uint64_t step, hipStream_t st) {
   if (!dc || !qkv || !dqkv) return RAF_EINVAL;
   if (!attn_fused_supported(d)) return RAF_ENOTSUP;
-  static bool attr_done = false;
-  if (!attr_done) {
-    if (hipFuncSetAttribute((const void*)attn_bwd_full_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            ATT_BWD_LDS) != hipSuccess)
-      return check_launch();
-    attr_done = true;
-  }
+  static LdsLimitOnce lds_limit;
+  if (!lds_limit.ensure((const void*)attn_bwd_full_kernel, ATT_BWD_LDS)) return RAF_EHIP;
   const DropSite drop = make_drop_site(d, 1, step);
   hipLaunchKernelGGL(attn_bwd_full_kernel, dim3(d.batch * d.heads), dim3(512), ATT_BWD_LDS, st, (const bf16_t*)dc,
                      (const bf16_t*)qkv, lens, (bf16_t*)dqkv, d.seq, d.hidden, d.heads, d.causal,
@@ -754,13 +749,8 @@ raf_status launch_attn_flash_fwd(const raf_layer_desc& d, const void* qkv, const
   if (!attn_flash_supported(d)) return RAF_ENOTSUP;
   const DropSite drop = make_drop_site(d, 1, step);
   dim3 grid((d.seq + FL_QB - 1) / FL_QB, d.batch * d.heads);
-  static bool attr_done = false;
-  if (!attr_done) {
-    if (hipFuncSetAttribute((const void*)attn_flash_fwd_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            2 * FL_STAGE) != hipSuccess)
-      return check_launch();
-    attr_done = true;
-  }
+  static LdsLimitOnce lds_limit;
+  if (!lds_limit.ensure((const void*)attn_flash_fwd_kernel, 2 * FL_STAGE)) return RAF_EHIP;
   hipLaunchKernelGGL(attn_flash_fwd_kernel, grid, dim3(512), 2 * FL_STAGE, st, (const bf16_t*)qkv, lens, (bf16_t*)ctx, lse, d.seq,
                      d.hidden, d.heads, d.causal, 0.125f * 1.44269504088896341f, drop);
   return check_launch();
@@ -774,15 +764,10 @@ raf_status launch_attn_flash_bwd(const raf_layer_desc& d, const void* dc, const 
   const DropSite drop = make_drop_site(d, 1, step);
   const float alpha2 = 0.125f * 1.44269504088896341f;
   dim3 grid((d.seq + FL_QB - 1) / FL_QB, d.batch * d.heads);
-  static bool attr_done = false;
-  if (!attr_done) {
-    if (hipFuncSetAttribute((const void*)attn_flash_dq_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            2 * FL_STAGE) != hipSuccess ||
-        hipFuncSetAttribute((const void*)attn_flash_dkv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            2 * FL_DKV_STAGE) != hipSuccess)
-      return check_launch();
-    attr_done = true;
-  }
+  static LdsLimitOnce lds_dq, lds_dkv;
+  if (!lds_dq.ensure((const void*)attn_flash_dq_kernel, 2 * FL_STAGE) ||
+      !lds_dkv.ensure((const void*)attn_flash_dkv_kernel, 2 * FL_DKV_STAGE))
+    return RAF_EHIP;
   hipLaunchKernelGGL(attn_flash_dq_kernel, grid, dim3(512), 2 * FL_STAGE, st, (const bf16_t*)dc, (const bf16_t*)qkv,
                      (const bf16_t*)ctx, lse, lens, (bf16_t*)dqkv, dvec, d.seq, d.hidden, d.heads, d.causal, alpha2,
                      0.125f, drop);

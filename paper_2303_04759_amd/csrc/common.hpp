@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "raf_mi355.h"
 
 namespace raf {
@@ -25,6 +27,26 @@ inline raf_status check_launch() {
   }
   return RAF_OK;
 }
+// Raises a kernel's dynamic-LDS limit once per device.  One object per kernel instantiation (a function-local
+// static); safe from several host threads: two racing callers both set the same value.
+struct LdsLimitOnce {
+  std::atomic<uint64_t> done{0};
+  bool ensure(const void* kern, int bytes) {
+    int dev = 0;
+    const bool tracked = hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64;
+    const uint64_t bit = tracked ? (uint64_t)1 << dev : 0;
+    if (tracked && (done.load(std::memory_order_acquire) & bit)) return true;
+    const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e != hipSuccess) {   // recorded for raf_last_hip_error and cleared: callers may fall back to another kernel
+      (void)hipGetLastError();
+      set_hip_error(e);
+      return false;
+    }
+    done.fetch_or(bit, std::memory_order_release);
+    return true;
+  }
+};
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // ------------------------------------------------------- typed 8-vectors --

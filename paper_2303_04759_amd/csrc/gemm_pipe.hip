@@ -220,14 +220,8 @@ static bool launch_pipe_inst(const GemmDev& d, int batch, hipStream_t st) {
   constexpr int NW = WGM * WGN;
   constexpr int LDS_BYTES = NS * (PipeTile<BM, AK, NW>::BYTES + PipeTile<BN, BKM, NW>::BYTES);
   auto kern = gemm_bf16_pipe_kernel<BM, BN, WGM, WGN, AK, BKM, TC, NS>;
-  static bool attr_done = false;   // per instantiation
-  if (!attr_done) {
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess) {
-      (void)hipGetLastError();
-      return false;
-    }
-    attr_done = true;
-  }
+  static LdsLimitOnce lds_limit;   // per instantiation
+  if (!lds_limit.ensure((const void*)kern, LDS_BYTES)) return false;
   const int tiles_m = (d.M + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
   const int ntile = tiles_m * tiles_n;
   const int remap = batch == 1 ? 1 : 0;
@@ -488,14 +482,8 @@ bool launch_gemm_group_spec(const GemmDev* ds, int count, hipStream_t st, const 
   constexpr int LDS_BYTES = NS * (BM + BN) * PBK * 2;
   static_assert(LDS_BYTES <= 160 * 1024, "ring exceeds the LDS of a CU");
   auto kern = gemm_bf16_spec_kernel<BM, BN, WGM, WGN, false, false, float, NS, NP>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess) {
-      (void)hipGetLastError();
-      return false;
-    }
-    attr_done = true;
-  }
+  static LdsLimitOnce lds_limit;   // per instantiation
+  if (!lds_limit.ensure((const void*)kern, LDS_BYTES)) return false;
   const int tile_blocks = ((tiles + 7) / 8) * 8;
   // side workers only where the tiles leave CUs free (one workgroup per CU: the ring takes most of the LDS), and
   // enough of them that a worker's columns take less time than a tile
@@ -873,14 +861,8 @@ static bool launch_w48s_inst(const GemmDev& d, hipStream_t st) {
   static_assert((NS - 2) * ((BM / 8 + BN / 8 + NP - 1) / NP) <= 24, "in-flight loads exceed wait_vmcnt_dyn");
   static_assert(64 * (WGM * WGN * KS + NP) <= 1024, "workgroup too large");
   auto kern = gemm_bf16_w48s_kernel<WGM, WGN, NB, NS, KS, NP, TC>;
-  static bool attr_done = false;   // per instantiation
-  if (!attr_done) {
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess) {
-      (void)hipGetLastError();
-      return false;
-    }
-    attr_done = true;
-  }
+  static LdsLimitOnce lds_limit;   // per instantiation
+  if (!lds_limit.ensure((const void*)kern, LDS_BYTES)) return false;
   const int tiles_m = (d.M + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
   const int ntile = tiles_m * tiles_n;
   dim3 grid(((ntile + 7) / 8) * 8);
@@ -897,14 +879,8 @@ static bool launch_w48_inst(const GemmDev& d, hipStream_t st) {
   static_assert(LDS_BYTES <= 160 * 1024, "ring exceeds the LDS of a CU");
   static_assert((NS - 2) * ((BM / 8 + BN / 8 + WGM * WGN * KS - 1) / (WGM * WGN * KS)) <= 24, "in-flight loads exceed wait_vmcnt_dyn");
   auto kern = gemm_bf16_w48_kernel<WGM, WGN, NS, KS, TC>;
-  static bool attr_done = false;   // per instantiation
-  if (!attr_done) {
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess) {
-      (void)hipGetLastError();
-      return false;
-    }
-    attr_done = true;
-  }
+  static LdsLimitOnce lds_limit;   // per instantiation
+  if (!lds_limit.ensure((const void*)kern, LDS_BYTES)) return false;
   const int tiles_m = (d.M + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
   const int ntile = tiles_m * tiles_n;
   dim3 grid(((ntile + 7) / 8) * 8);

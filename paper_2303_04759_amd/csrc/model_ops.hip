@@ -370,7 +370,10 @@ static raf_status validate_mlm(const raf_mlm_desc* d) {
   if (!d) return RAF_EINVAL;
   if (d->rows <= 0 || d->hidden <= 0 || d->vocab <= 0 || d->n_sel <= 0 || d->n_sel > d->rows) return RAF_EINVAL;
   if (d->precision != RAF_F32 && d->precision != RAF_BF16_AMP) return RAF_EINVAL;
-  if ((d->gelu_tanh | 1) != 1 || d->reserved != 0 || !(d->ln_eps >= 0.f)) return RAF_EINVAL;
+  // ln_eps must be positive here: the selected rows are padded to the GEMM tile height with zero rows, which reach
+  // the LayerNorm as constant rows (gelu of the bias), variance exactly 0; with eps = 0 they would turn into NaN and
+  // spread through the tied decoder's gradient.
+  if ((d->gelu_tanh | 1) != 1 || d->reserved != 0 || !(d->ln_eps > 0.f)) return RAF_EINVAL;
   if ((d->hidden % 32) || d->hidden > 4096) return RAF_ENOTSUP;
   if (vocab_pad_of(d->vocab) > 256 * 8 * CE_MAX_VEC) return RAF_ENOTSUP;
   return RAF_OK;

@@ -4,6 +4,8 @@ import sys
 import numpy as np
 import torch
 
+from oracle.adam import adam_step
+
 
 def announce(*what):
     """Name the case before any GPU work, flushed, so a lost box still tells which case ran."""
@@ -16,6 +18,59 @@ def rel_fro(a, b):
     b = np.asarray(b, dtype=np.float64).reshape(-1)
     den = np.linalg.norm(b)
     return float(np.linalg.norm(a - b) / (den if den > 0 else 1.0))
+
+
+BWD_TOL = {0: 1e-4, 1: 3e-2}      # relative Frobenius, gradients and updates: fp32 mode / bf16 AMP
+
+
+def comparable(cfg, k, shape):
+    """All elements except the key block of b_qkv.  The key-bias gradient vanishes identically (a constant added to
+    every key of a row cancels in the softmax), so Adam's sign-like step there is decided by rounding noise on either
+    side; it is the one place excluded from the updated-weight comparisons."""
+    sel = np.ones(shape, dtype=bool)
+    if k == "b_qkv":
+        sel[cfg["hidden"]:2 * cfg["hidden"]] = False
+    return sel
+
+
+def check_update(cfg, k, t, prec, adam, before, dev, ref, min_conditioned=0.9):
+    """One parameter tensor after one optimizer step.  before/dev: device values (w, m, v[, g]) before and after the
+    step; ref: the oracle's free-running trajectory (w_before, w, m, v).  Returns the update's relative error."""
+    tol = BWD_TOL[prec]
+    ls = cfg["loss_scale"]
+    # (1) the optimizer kernel itself, on every element of every tensor: the oracle's rule applied to the device's own
+    # inputs.  The update is compared as w_after - w_before; the bound is fp32 rounding of the master weight
+    # (half an ulp of |w| against a step of about lr) plus the rounding of the derived constants.
+    w1, m1, v1 = adam_step(before["w"], dev["g"], before["m"], before["v"], t, adam["lr"], adam["beta1"], adam["beta2"],
+                           adam["eps"], adam.get("weight_decay", 0.0), 1.0 / ls)
+    dw_k, dw_o = dev["w"] - before["w"], w1 - before["w"]
+    bound = 2.0 ** -23 * np.maximum(np.abs(before["w"]), np.abs(dev["w"])) + 2e-5 * np.abs(dw_o) + 1e-12
+    assert (np.abs(dw_k - dw_o) <= bound).all(), ("adam kernel dw", k, t, float(np.abs(dw_k - dw_o).max()))
+    assert rel_fro(dev["m"], m1) <= 1e-5 and rel_fro(dev["v"], v1) <= 1e-5, ("adam kernel m/v", k, t)
+    # (2) against the oracle's trajectory.  Moments are smooth in g: whole tensors, at the stated tolerance.
+    if np.linalg.norm(ref["m"]) > 1e-12:
+        e_m, e_v = rel_fro(dev["m"], ref["m"]), rel_fro(dev["v"], ref["v"])
+        assert e_m <= tol and e_v <= tol, ("m/v", k, t, e_m, e_v)
+    sel = comparable(cfg, k, dev["w"].shape)
+    # updated weights, whole tensor (key-bias block excepted) where |w| >> lr: matrices and LayerNorm gains
+    if k.startswith("w_") or k.endswith("_g") or k in ("word", "pos", "head_w"):
+        e_w = rel_fro(dev["w"][sel], ref["w"][sel])
+        assert e_w <= tol, ("w", k, t, e_w)
+    # the update itself.  Adam's step lr*m_hat/(sqrt(v_hat)+eps) is sign-like at small t: an element whose first
+    # moment is below the rounding error of the gradient takes a step of either sign on either side.  Elements with
+    # |m| above tol * rms(m) (at least 90 % of every tensor) must agree to the tolerance; all must respect the
+    # step bound.  Vectors that start at zero (biases, LayerNorm shifts) have w_after = update, so this is their
+    # updated-weight check.
+    m_ref = ref["m"][sel]
+    cond = np.abs(m_ref) > tol * np.sqrt(np.mean(m_ref ** 2))
+    cond |= (m_ref == 0) & (dev["m"][sel] == 0)          # rows no sample touched: no step on either side
+    assert cond.mean() >= min_conditioned, ("conditioned fraction", k, t, cond.mean())
+    dw_dev, dw_ref = (dev["w"] - before["w"])[sel], (ref["w"] - ref["w_before"])[sel]
+    e_dw = rel_fro(dw_dev[cond], dw_ref[cond])
+    assert e_dw <= (2e-2 if prec == 0 else tol), ("dw", k, t, e_dw)
+    # |step| <= lr * max(1, (1-b1)/sqrt(1-b2)) / (1-b1^t) ... <= 3.2 lr for t <= 3 with these betas
+    assert np.abs(dev["w"] - before["w"]).max() <= 4.0 * adam["lr"], ("step bound", k, t)
+    return e_dw
 
 
 def to_dev(a, dtype):

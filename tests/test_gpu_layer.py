@@ -11,7 +11,7 @@ from paper_2303_04759_amd.harness import DeviceLayer
 from oracle.step import train_step
 from workloads.synthetic import ADAM, CONFIGS, PARAM_NAMES, make_layer_inputs
 
-from gpu_util import announce, host, rel_fro
+from gpu_util import announce, check_update, host, rel_fro
 
 pytestmark = pytest.mark.gpu
 
@@ -20,6 +20,8 @@ BWD_TOL = {0: 1e-4, 1: 3e-2}
 
 
 def run_and_compare(cfg, seed, steps, random_affine=False, lens_override=None, check_lower=False):
+    """`steps` consecutive optimizer steps on the device and on the oracle, each side running freely from its own
+    state (no re-synchronisation), so steps 2 and 3 exercise Adam with non-zero moments."""
     inp = make_layer_inputs(cfg, seed=seed, random_affine=random_affine)
     if lens_override is not None:
         inp["seq_lens"] = np.asarray(lens_override, dtype=np.int32)
@@ -31,7 +33,7 @@ def run_and_compare(cfg, seed, steps, random_affine=False, lens_override=None, c
     hyper = dict(ADAM, loss_scale=cfg["loss_scale"])
     report = {}
     for t in range(1, steps + 1):
-        w_before = {k: host(lay.master[k]) for k in PARAM_NAMES}
+        before = {k: dict(w=host(lay.master[k]), m=host(lay.m[k]), v=host(lay.v[k])) for k in PARAM_NAMES}
         lay.train_step(t)
         torch.cuda.synchronize()
         ref = train_step(cfg, p, m, v, inp["x"], inp["G"], inp["seq_lens"], t, hyper)
@@ -48,47 +50,18 @@ def run_and_compare(cfg, seed, steps, random_affine=False, lens_override=None, c
         worst_dw = 0.0
         for k in PARAM_NAMES:
             g_ref = ref["grads"][k].reshape(p[k].shape)
-            e_g = rel_fro(host(lay.grads[k]), g_ref)
+            g_dev = host(lay.grads[k])
+            e_g = rel_fro(g_dev, g_ref)
             assert e_g <= BWD_TOL[prec], ("grad", k, t, e_g)
             worst = max(worst, e_g)
-            # Updated weights.  Adam's step lr*m_hat/(sqrt(v_hat)+eps) is sign-like in g at small t,
-            # so where the true gradient is (near) zero - e.g. the key bias, whose gradient vanishes
-            # identically - the step's sign is decided by rounding noise on either side.  Such
-            # elements (|g| below the gradient tolerance times the tensor's rms) are only required
-            # to respect Adam's step bound; all others must match to the stated tolerance.
-            w_dev, w_ref = host(lay.master[k]), ref["params"][k]
-            g_un = g_ref / cfg["loss_scale"]
-            cond = np.abs(g_un) > BWD_TOL[prec] * np.sqrt(np.mean(g_un ** 2))
-            e_w = rel_fro(w_dev[cond], w_ref[cond])
-            assert e_w <= BWD_TOL[prec], ("w", k, t, e_w)
-            assert cond.mean() > (0.6 if k != "b_qkv" else 0.3), ("conditioned fraction", k, cond.mean())
-            # |step| <= lr * (1-b1^t)^-1 * ... <= ~3.2*lr for t <= 3 with these betas
-            assert np.abs(w_dev - w_before[k]).max() <= 4.0 * ADAM["lr"], ("step bound", k, t)
-            # the update itself: at small t Adam is sign-like (dw ~ -lr*sign(g)), so an element whose
-            # tiny gradient changes sign under bf16 rounding moves by 2*lr; reported, bounded in fp32 only
-            e_dw = rel_fro((w_dev - w_before[k])[cond], (w_ref - w_before[k])[cond])
+            dev = dict(w=host(lay.master[k]), m=host(lay.m[k]), v=host(lay.v[k]), g=g_dev)
+            e_dw = check_update(cfg, k, t, prec, ADAM, before[k], dev,
+                                dict(w_before=p[k], w=ref["params"][k], m=ref["m"][k], v=ref["v"][k]))
             worst_dw = max(worst_dw, e_dw)
-            if prec == 0:
-                assert e_dw <= 2e-2, ("dw", k, t, e_dw)
-            e_m = rel_fro(host(lay.m[k]), ref["m"][k])
-            e_v = rel_fro(host(lay.v[k]), ref["v"][k])
-            if np.linalg.norm(ref["m"][k]) > 1e-12:
-                assert e_m <= BWD_TOL[prec] and e_v <= 2 * BWD_TOL[prec], ("mv", k, t, e_m, e_v)
             if lay.lowp[k] is not None:
                 assert torch.equal(lay.lowp[k], lay.master[k].to(torch.bfloat16)), k
         report[t] = dict(y=e_y, dx=e_dx, worst_grad=worst, worst_dw=worst_dw)
         p, m, v = ref["params"], ref["m"], ref["v"]
-        # keep the two trajectories on the same weights: the update is sign-like at small t, so
-        # compare each step from the oracle's state rounded the way the device stores it
-        for k in PARAM_NAMES:
-            lay.master[k].copy_(torch.from_numpy(p[k].astype(np.float32)))
-            lay.m[k].copy_(torch.from_numpy(m[k].astype(np.float32)))
-            lay.v[k].copy_(torch.from_numpy(v[k].astype(np.float32)))
-            if lay.lowp[k] is not None:
-                lay.lowp[k].copy_(lay.master[k].to(torch.bfloat16))
-            p[k] = host(lay.master[k])
-            m[k] = host(lay.m[k])
-            v[k] = host(lay.v[k])
     if check_lower:
         # a bf16 run that is closer than ~1e-4 would mean bf16 is not being exercised
         assert report[1]["y"] > 1e-4
@@ -135,12 +108,12 @@ def test_bert_base_full_size_bf16_amp():
 
 def test_bert_large_full_size_bf16_amp():
     announce("layer bert_large full")
-    run_and_compare(CONFIGS["bert_large"], seed=0, steps=1)
+    run_and_compare(CONFIGS["bert_large"], seed=0, steps=3)
 
 
 def test_gpt2_medium_full_size_bf16_amp():
     announce("layer gpt2_medium full")
-    run_and_compare(CONFIGS["gpt2_medium"], seed=0, steps=1)
+    run_and_compare(CONFIGS["gpt2_medium"], seed=0, steps=3)
 
 
 def test_determinism_and_step_dependence():

@@ -11,7 +11,7 @@ from oracle import model as M
 from oracle.layer import PARAM_NAMES
 from workloads.synthetic import ADAM, MODEL_CONFIGS, make_model_inputs
 
-from gpu_util import announce, host, rel_fro
+from gpu_util import announce, check_update, host, rel_fro
 
 pytestmark = pytest.mark.gpu
 
@@ -27,13 +27,13 @@ def oracle_state(inp):
     return P, layers, zP, zL
 
 
-def run_model(cfg, seed, check_weights=True):
+def run_model(cfg, seed):
     inp = make_model_inputs(cfg, seed=seed)
     mod = DeviceModel(cfg, inp, ADAM)
     prec = cfg["precision"]
     P, layers, zP, zL = oracle_state(inp)
     hyper = dict(ADAM, loss_scale=cfg["loss_scale"])
-    w_before = {k: host(v) for k, v in mod.master.items()}
+    before = {k: dict(w=host(mod.master[k]), m=host(mod.m[k]), v=host(mod.v[k])) for k in mod.master}
     mod.train_step(1)
     torch.cuda.synchronize()
     ref = M.model_train_step(cfg, P, layers, zP, zP, zL, zL, inp["ids"], inp["seq_lens"], inp["sel"], inp["labels"], 1,
@@ -43,40 +43,37 @@ def run_model(cfg, seed, check_weights=True):
     assert e_x <= FWD_TOL[prec], ("xL", e_x)
     loss = float(mod.loss.item())
     assert abs(loss - ref["loss"]) <= FWD_TOL[prec] * abs(ref["loss"]), (loss, ref["loss"])
-    worst = 0.0
-    names = list(M.EMBED_PARAMS + M.HEAD_PARAMS)
+    worst, worst_dw = 0.0, 0.0
     V = cfg["vocab"]
-    for k in names:
-        g_dev, g_ref = host(mod.grads[k]), ref["grads"][k].reshape(inp["P"][k].shape)
-        if k == "word":
+
+    def check(key, name, g_ref, w_old, w_ref, m_ref, v_ref):
+        nonlocal worst, worst_dw
+        g_dev = host(mod.grads[key])
+        g_ref = g_ref.reshape(g_dev.shape)
+        if name == "word":
             assert (g_dev[V:] == 0).all()          # padded table rows take no gradient
         e = rel_fro(g_dev, g_ref)
-        assert e <= BWD_TOL[prec], ("grad", k, e)
+        assert e <= BWD_TOL[prec], ("grad", key, e)
         worst = max(worst, e)
+        # gradients, both moments, the optimizer kernel on every element, updated weights and the update itself
+        # (the rules are check_update's); the word table's gradient is dominated by the few hundred rows the batch
+        # uses, so fewer of its elements lie above the rounding floor
+        dev = dict(w=host(mod.master[key]), m=host(mod.m[key]), v=host(mod.v[key]), g=g_dev)
+        shape = dev["w"].shape
+        e_dw = check_update(cfg, name, 1, prec, ADAM, before[key], dev,
+                            dict(w_before=w_old.reshape(shape), w=w_ref.reshape(shape), m=m_ref.reshape(shape),
+                                 v=v_ref.reshape(shape)), min_conditioned=0.5 if name == "word" else 0.9)
+        worst_dw = max(worst_dw, e_dw)
+        if mod.lowp[key] is not None:
+            assert torch.equal(mod.lowp[key], mod.master[key].to(torch.bfloat16)), key
+
+    for k in M.EMBED_PARAMS + M.HEAD_PARAMS:
+        check(k, k, ref["grads"][k], P[k], ref["P"][k], ref["mP"][k], ref["vP"][k])
     for l in range(cfg["layers"]):
         for k in PARAM_NAMES:
-            e = rel_fro(host(mod.grads[(l, k)]), ref["layer_grads"][l][k])
-            assert e <= BWD_TOL[prec], ("grad", l, k, e)
-            worst = max(worst, e)
-    if check_weights:
-        # updated weights on well-conditioned elements (see test_gpu_layer.py for the reasoning)
-        def check(key, g_ref, w_ref):
-            g_un = g_ref / cfg["loss_scale"]
-            rms = np.sqrt(np.mean(g_un ** 2))
-            cond = np.abs(g_un) > BWD_TOL[prec] * rms
-            w_dev = host(mod.master[key])
-            if cond.any():
-                assert rel_fro(w_dev[cond], w_ref[cond]) <= BWD_TOL[prec], ("w", key)
-            assert np.abs(w_dev - w_before[key]).max() <= 4.0 * ADAM["lr"], ("step bound", key)
-            if mod.lowp[key] is not None:
-                assert torch.equal(mod.lowp[key], mod.master[key].to(torch.bfloat16)), key
-        for k in names:
-            check(k, ref["grads"][k].reshape(inp["P"][k].shape), ref["P"][k])
-        for l in range(cfg["layers"]):
-            for k in PARAM_NAMES:
-                check((l, k), ref["layer_grads"][l][k].reshape(inp["layers"][l][k].shape), ref["layers"][l][k])
-    print("model parity: xL %.2e loss dev %.6g ref %.6g worst grad %.2e n_sel %d" % (e_x, loss, ref["loss"], worst,
-                                                                                     len(inp["sel"])), flush=True)
+            check((l, k), k, ref["layer_grads"][l][k], layers[l][k], ref["layers"][l][k], ref["mL"][l][k], ref["vL"][l][k])
+    print("model parity: xL %.2e loss dev %.6g ref %.6g worst grad %.2e worst update %.2e n_sel %d" % (
+        e_x, loss, ref["loss"], worst, worst_dw, len(inp["sel"])), flush=True)
 
 
 def test_tiny_model_fp32():
@@ -100,12 +97,12 @@ def test_small_model_bf16_amp():
 def test_bert_base_model_reduced_depth_bf16_amp():
     announce("model bert-base shapes, 3 layers, batch 16")
     cfg = dict(MODEL_CONFIGS["bert_base_12l_mlm"], batch=16, layers=3)
-    run_model(cfg, seed=3, check_weights=False)
+    run_model(cfg, seed=3)
 
 
 def test_full_bert_base_12_layer_model_bf16_amp():
     announce("model full size: 12 layers, batch 64, vocab 30522")
-    run_model(MODEL_CONFIGS["bert_base_12l_mlm"], seed=0, check_weights=False)
+    run_model(MODEL_CONFIGS["bert_base_12l_mlm"], seed=0)
 
 
 def test_model_is_deterministic():
