@@ -333,6 +333,24 @@ raf_status raf_op_dropout_residual_ln_bwd(const raf_layer_desc *desc, int32_t si
                                           float *dbeta, float *dbias, float *partial, uint64_t step,
                                           void *hip_stream);
 
+/* The same operator for callers that cannot allocate device memory (code under HIP
+ * graph capture, serving loops and harnesses that forbid hipMalloc): identical to
+ * raf_op_dropout_residual_ln_bwd except that the partial-sum buffer is a device array
+ * inside the library, RAF_NOALLOC_LN_BWD_PARTIAL_FLOATS floats (3 MiB) per GPU, held
+ * until the process ends.  Same kernels, bit-identical results.  The call allocates
+ * nothing.  RAF_EWORKSPACE when raf_op_ln_bwd_partial_floats(hidden, rows) exceeds
+ * that size (hidden > 1024 with the present kernels); nothing is launched then.  All
+ * calls on one GPU share the array: calls that overlap on one GPU (different streams
+ * or host threads) race and must be serialised by the caller; calls in stream order
+ * need no clearing in between.  The first call on a device looks the array up (it may
+ * load the code object): make it outside a graph capture. */
+#define RAF_NOALLOC_LN_BWD_PARTIAL_FLOATS (256 * 3 * 1024)
+raf_status raf_op_dropout_residual_ln_bwd_noalloc(const raf_layer_desc *desc, int32_t site, int64_t rows,
+                                                  const void *dout, const void *dout2, const void *z,
+                                                  const float *mu, const float *rstd, const float *gamma,
+                                                  const void *dres, void *dz, void *da, float *dgamma, float *dbeta,
+                                                  float *dbias, uint64_t step, void *hip_stream);
+
 /* ---- Memory passes on an operator list (host only, no GPU work; Sections 3.1.4
  * "operator scheduling" and 3.1.5 "rematerialization").  The paper names the
  * ingredients and prints no formulas; the rules used are stated with each call.

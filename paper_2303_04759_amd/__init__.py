@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libraf_mi355.so")
 RAF_F32, RAF_BF16_AMP = 0, 1
 RAF_OK, RAF_EINVAL, RAF_ENOTSUP, RAF_EWORKSPACE, RAF_EHIP = 0, -1, -2, -3, -4
 RAF_LOSS_PARTIALS = 1024
+RAF_NOALLOC_LN_BWD_PARTIAL_FLOATS = 256 * 3 * 1024
 RAF_REMAT_QKV, RAF_REMAT_CTX, RAF_REMAT_FFN1 = 1, 2, 4
 EPI_NONE, EPI_BIAS, EPI_BIAS_GELU, EPI_MUL_GELU_GRAD, EPI_ADD_RES, EPI_BIAS_GELU_DERIV, EPI_MUL_AUX = range(7)
 
@@ -127,6 +128,8 @@ _SIGNATURES = {
     "raf_op_ln_bwd_partial_floats": (C.c_size_t, [C.c_int32, C.c_int64]),
     "raf_op_dropout_residual_ln_bwd": (C.c_int, [C.POINTER(LayerDesc), C.c_int32, C.c_int64] + [C.c_void_p] * 13 +
                                        [C.c_uint64, C.c_void_p]),
+    "raf_op_dropout_residual_ln_bwd_noalloc": (C.c_int, [C.POINTER(LayerDesc), C.c_int32, C.c_int64] +
+                                               [C.c_void_p] * 12 + [C.c_uint64, C.c_void_p]),
     "raf_memory_profile": (C.c_int, [C.POINTER(OpGraph), C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_int64)]),
     "raf_schedule_ops": (C.c_int, [C.POINTER(OpGraph), C.POINTER(C.c_int32)]),
     "raf_remat_plan": (C.c_int, [C.POINTER(OpGraph), C.c_int64, C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_int32),
@@ -336,6 +339,14 @@ def raf_op_dropout_residual_ln_bwd(desc, site, rows, dout, dout2, z, mu, rstd, g
         C.byref(desc), int(site), int(rows), _ptr(dout), _ptr(dout2), _ptr(z), _ptr(mu), _ptr(rstd), _ptr(gamma),
         _ptr(dres), _ptr(dz), _ptr(da), _ptr(dgamma), _ptr(dbeta), _ptr(dbias), _ptr(partial), int(step),
         _stream(stream)), "raf_op_dropout_residual_ln_bwd")
+
+
+def raf_op_dropout_residual_ln_bwd_noalloc(desc, site, rows, dout, dout2, z, mu, rstd, gamma, dres, dz, da, dgamma,
+                                           dbeta, dbias, step, stream=None):
+    _check(load_library().raf_op_dropout_residual_ln_bwd_noalloc(
+        C.byref(desc), int(site), int(rows), _ptr(dout), _ptr(dout2), _ptr(z), _ptr(mu), _ptr(rstd), _ptr(gamma),
+        _ptr(dres), _ptr(dz), _ptr(da), _ptr(dgamma), _ptr(dbeta), _ptr(dbias), int(step), _stream(stream)),
+        "raf_op_dropout_residual_ln_bwd_noalloc")
 
 
 def make_embed_desc(cfg):
