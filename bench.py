@@ -20,13 +20,22 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
-# HBM bytes per launch of the dominant kernel on the bert_base workload, from the two rocprofv3 --pmc
-# runs summarised in profiles/bench_bert_base_hbm_traffic.txt (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00,
-# factors from a plain 256 MiB copy): 42.3 MB read + 6.3 MB written.
-DOMINANT_KERNEL_TRAFFIC_BYTES = {"bert_base": 48.6e6}
-DOMINANT_KERNEL_NAME = {"bert_base": "gemm_bf16_w48s_kernel<128x96 tiles, 8 consumer + 8 producer waves, 3 stages, K-major "
-                                     "operands> (the five products with N = hidden: out/ffn2 forward, ffn1/out/qkv "
-                                     "input gradients)"}
+PROFILES = os.path.join(ROOT, "profiles")
+
+
+def profiled_traffic(workload, kernel_key):
+    """HBM bytes per launch of a kernel as measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE runs, each scaled
+    by what the counter reads for a plain copy of known size): read from the machine-readable lines
+    '# traffic_bytes_per_launch <kernel key> <bytes>' of profiles/bench_<workload>_hbm_traffic.txt, which the same
+    counter runs wrote.  None when that workload or kernel has no counter profile."""
+    try:
+        for line in open(os.path.join(PROFILES, "bench_%s_hbm_traffic.txt" % workload)):
+            f = line.split()
+            if len(f) == 4 and f[0] == "#" and f[1] == "traffic_bytes_per_launch" and f[2] == kernel_key:
+                return float(f[3])
+    except OSError:
+        pass
+    return None
 
 
 def gemm_launches(cfg):
@@ -48,6 +57,176 @@ def gemm_launches(cfg):
         ("dq", S, 64, S, 1, 0, 0, 0, z), ("dk", S, 64, S, 0, 0, 0, 0, z),
         ("qkv_wgrad", 3 * H, H, T, 0, 0, 1, 0, 1), ("qkv_dgrad", T, H, 3 * H, 1, 1, 0, 4, 1),
     ]
+
+
+# ------------------------------------------------------------------ per-kernel report --
+def launch_work(cfg, n_params_matrix, n_params_vector):
+    """Algorithmic work of every launch class of one bf16 layer step, in launch order per class:
+    class -> list of (operator label, bound, flops or bytes).  Bytes are the tensors an operator has to read and write
+    once (what SURVEY-style accounting calls algorithmic), not what an implementation happens to move."""
+    B, S, H, F = cfg["batch"], cfg["seq"], cfg["hidden"], cfg["ffn"]
+    T = B * S
+    e = 2 if cfg["precision"] == 1 else 4
+    TH, TF = T * H * e, T * F * e
+    pre = bool(cfg["pre_ln"])
+    fl = lambda M, N, K: 2.0 * M * N * K
+    w = {}
+    w["gemm"] = [("qkv_fwd", "mfma", fl(T, 3 * H, H)), ("out_fwd", "mfma", fl(T, H, H)),
+                 ("ffn1_fwd+gelu", "mfma", fl(T, F, H)), ("ffn2_fwd", "mfma", fl(T, H, F)),
+                 ("ffn2_dgrad*gelu'", "mfma", fl(T, F, H)), ("ffn1_dgrad", "mfma", fl(T, H, F)),
+                 ("out_dgrad", "mfma", fl(T, H, H)), ("qkv_dgrad+res", "mfma", fl(T, H, 3 * H))]
+    w["wgrad_group"] = [("4 weight gradients (+ bias/LayerNorm column sums on idle CUs)", "mfma",
+                         fl(3 * H, H, T) + fl(H, H, T) + fl(F, H, T) + fl(H, F, T))]
+    if pre:
+        w["ln_fwd"] = [("ln1", "hbm", 2 * TH), ("dropout+residual+ln2", "hbm", 4 * TH), ("dropout+residual", "hbm", 3 * TH)]
+        w["ln_bwd"] = [("dropout3 adjoint", "hbm", 2 * TH), ("ln2 adjoint+residual", "hbm", 5 * TH),
+                       ("ln1 adjoint+residual", "hbm", 4 * TH)]
+    else:
+        w["ln_fwd"] = [("dropout+residual+ln1", "hbm", 4 * TH), ("dropout+residual+ln2", "hbm", 4 * TH)]
+        w["ln_bwd"] = [("ln2 adjoint", "hbm", 4 * TH), ("ln1 adjoint (two incoming gradients)", "hbm", 5 * TH)]
+    w["attn_fwd"] = [("scores+mask+softmax+dropout+context", "hbm", 4 * TH)]
+    w["attn_bwd"] = [("attention adjoint (dQ,dK,dV)", "hbm", 7 * TH)]
+    w["attn_bwd_dq"] = [("attention adjoint dQ", "hbm", 6 * TH)]
+    w["attn_bwd_dkv"] = [("attention adjoint dK,dV", "hbm", 6 * TH)]
+    w["transpose"] = [("4 weight transposes", "hbm", 2 * 2 * n_params_matrix)]
+    w["loss_seed"] = [("loss seed", "hbm", 3 * TH)]
+    w["loss_final"] = [("loss partial sums", "hbm", 4096)]
+    w["adam"] = [("fused Adam, 12 tensors", "hbm", 30 * n_params_matrix + 28 * n_params_vector)]
+    w["colsum"] = [("bias-gradient column sums", "hbm", TF + 3 * TH)]
+    w["reduce"] = [("second stage of column sums", "hbm", None)]
+    return w
+
+
+KERNEL_CLASSES = (("gemm_bf16_spec_kernel", "wgrad_group"), ("gemm_bf16_group_kernel", "wgrad_group"),
+                  ("gemm_bf16_", "gemm"), ("gemm_f32", "gemm"), ("attn_fwd_fused", "attn_fwd"),
+                  ("attn_flash_fwd", "attn_fwd"), ("attn_bwd_full", "attn_bwd"), ("attn_flash_dq", "attn_bwd_dq"),
+                  ("attn_flash_dkv", "attn_bwd_dkv"), ("ln_fwd_kernel", "ln_fwd"), ("ln_bwd_kernel", "ln_bwd"),
+                  ("transpose_bf16", "transpose"), ("loss_seed", "loss_seed"), ("loss_final", "loss_final"),
+                  ("adam_kernel", "adam"), ("colsum_kernel", "colsum"), ("reduce_partials", "reduce"))
+
+
+def short_kernel_name(name):
+    """Readable kernel name without the argument list.  rocprofv3 leaves names with a bf16 template argument mangled
+    (_ZN3raf<len><name>I<args>E...): those are decoded here as far as this library's kernels need (integer, bool,
+    bf16 and float template arguments)."""
+    import re
+    m = re.match(r"_ZN3raf(\d+)", name)
+    if m:
+        n = int(m.group(1))
+        base, rest = name[m.end():m.end() + n], name[m.end() + n:]
+        targs = []
+        if rest.startswith("I"):
+            rest = rest[1:]
+            while rest and not rest.startswith("E"):
+                lit = re.match(r"L([ibjlm])(n?\d+)E", rest)
+                if lit:
+                    v = lit.group(2).replace("n", "-")
+                    targs.append({"0": "false", "1": "true"}[v] if lit.group(1) == "b" else v)
+                    rest = rest[lit.end():]
+                elif rest.startswith("DF16b"):
+                    targs.append("bf16")
+                    rest = rest[5:]
+                elif rest[0] in "fdi":
+                    targs.append({"f": "float", "d": "double", "i": "int"}[rest[0]])
+                    rest = rest[1:]
+                else:
+                    targs.append("...")
+                    break
+        return base + ("<" + ",".join(targs) + ">" if targs else "")
+    name = name.replace("void ", "").replace("raf::", "")
+    depth = 0
+    for i, ch in enumerate(name):      # cut at the argument list (the first '(' outside template brackets)
+        depth += ch == "<"
+        depth -= ch == ">"
+        if ch == "(" and depth == 0:
+            return name[:i]
+    return name
+
+
+def kernel_breakdown(args, cfg, n_params_matrix, n_params_vector, steps=10, warmup=3):
+    """Every kernel of the step with its time INSIDE the step and its roofline fraction.
+
+    The step is run eagerly (one dispatch per kernel) in a child process under `rocprofv3 --kernel-trace`; the
+    per-dispatch begin/end stamps of the last `steps` steps are averaged per launch position, each position is given
+    its operator and algorithmic work (launch_work), and positions are summed per kernel instantiation.  Returns
+    (list, None) or (None, reason)."""
+    import csv
+    import glob
+    import shutil
+    import subprocess
+    import tempfile
+    if shutil.which("rocprofv3") is None:
+        return None, "rocprofv3 not on PATH"
+    out_dir = tempfile.mkdtemp(prefix="raf_bench_trace_", dir="/tmp")
+    cmd = ["rocprofv3", "--kernel-trace", "--output-format", "csv", "-d", out_dir, "-o", "trace", "--",
+           sys.executable, os.path.abspath(__file__), "--workload", args.workload, "--steps", str(steps), "--warmup",
+           str(warmup), "--no-graph", "--no-cpu", "--trace-child"]
+    try:
+        r = subprocess.run(cmd, cwd="/tmp", env=dict(os.environ, TMPDIR="/tmp"), stdout=subprocess.PIPE,
+                           stderr=subprocess.STDOUT, text=True, timeout=400)
+    except Exception as ex:      # a time-out included: the child is killed by run()
+        shutil.rmtree(out_dir, ignore_errors=True)
+        return None, "profiler run failed: %r" % (ex,)
+    files = glob.glob(os.path.join(out_dir, "**", "*kernel_trace.csv"), recursive=True)
+    if r.returncode != 0 or not files:
+        shutil.rmtree(out_dir, ignore_errors=True)
+        return None, "profiler run gave rc %d and %d trace files: %s" % (r.returncode, len(files), r.stdout[-300:])
+    rows = [x for x in csv.DictReader(open(files[0])) if "raf" in x["Kernel_Name"]]
+    shutil.rmtree(out_dir, ignore_errors=True)
+    rows.sort(key=lambda x: int(x["Start_Timestamp"]))
+    total_steps = steps + max(warmup, 1)
+    if not rows or len(rows) % total_steps:
+        return None, "%d library dispatches do not divide into %d steps" % (len(rows), total_steps)
+    n = len(rows) // total_steps
+    timed = rows[-steps * n:]
+    names = [x["Kernel_Name"] for x in timed[:n]]
+    for k in range(steps):
+        if [x["Kernel_Name"] for x in timed[k * n:(k + 1) * n]] != names:
+            return None, "launch order differs between steps"
+    dur_us = [sum(int(timed[k * n + i]["End_Timestamp"]) - int(timed[k * n + i]["Start_Timestamp"])
+                  for k in range(steps)) / steps / 1e3 for i in range(n)]
+    span_us = sum(int(timed[k * n + n - 1]["End_Timestamp"]) - int(timed[k * n]["Start_Timestamp"])
+                  for k in range(steps)) / steps / 1e3
+    work = launch_work(cfg, n_params_matrix, n_params_vector)
+    seen, agg, order = {}, {}, []
+    for i, name in enumerate(names):
+        cls = next((c for key, c in KERNEL_CLASSES if key in name), None)
+        k = seen.get(cls, 0)
+        seen[cls] = k + 1
+        op, bound, amount = (work[cls][k] if cls in work and k < len(work[cls]) else ("?", None, None))
+        if name not in agg:
+            agg[name] = dict(kernel=short_kernel_name(name), ops=[], launches_per_step=0, us_per_step=0.0, bound=bound,
+                             work_per_step=0.0 if amount is not None else None)
+            order.append(name)
+        a = agg[name]
+        a["ops"].append("%s %.1f us" % (op, dur_us[i]))
+        a["launches_per_step"] += 1
+        a["us_per_step"] += dur_us[i]
+        if amount is None or a["work_per_step"] is None or bound != a["bound"]:
+            a["work_per_step"] = None
+        else:
+            a["work_per_step"] += amount
+    out = []
+    for name in sorted(order, key=lambda q: -agg[q]["us_per_step"]):
+        a = agg[name]
+        a["us_per_step"] = round(a["us_per_step"], 2)
+        if a["work_per_step"] is not None and a["bound"] is not None:
+            rate = a["work_per_step"] / (a["us_per_step"] * 1e-6)
+            if a["bound"] == "mfma":
+                a.update(achieved=round(rate / 1e12, 1), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                         frac=round(rate / 1e12 / PEAK_BF16_TFLOPS, 4))
+            else:
+                a.update(achieved=round(rate / 1e9, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                         frac=round(rate / 1e9 / PEAK_HBM_GBS, 4))
+        out.append(a)
+    gemm_us = sum(a["us_per_step"] for a in out if a["bound"] == "mfma")
+    gemm_fl = sum(a["work_per_step"] for a in out if a["bound"] == "mfma" and a["work_per_step"])
+    summary = {"launches_per_step": n, "sum_of_kernels_us": round(sum(dur_us), 1), "first_start_to_last_end_us": round(span_us, 1),
+               "all_gemms_us": round(gemm_us, 1),
+               "all_gemms_frac_of_mfma_peak": round(gemm_fl / (gemm_us * 1e-6) / 1e12 / PEAK_BF16_TFLOPS, 4) if gemm_us else None,
+               "source": "rocprofv3 --kernel-trace of %d eager steps in a child process" % steps}
+    return {"summary": summary, "per_kernel": out}, None
+
 
 
 def measure_replay_us(cfg):
@@ -181,6 +360,10 @@ def main():
     ap.add_argument("--estimated-replay-latency", action="store_true",
                     help="with --activation-budget-frac: plan with the library's operation-count estimate of the "
                          "replay latencies instead of timing the three replayed operators first")
+    ap.add_argument("--no-kernels", action="store_true",
+                    help="skip the per-kernel report (an eager run of the step in a child process under rocprofv3)")
+    ap.add_argument("--trace-child", action="store_true",
+                    help="(used by the per-kernel report) run the eager steps only: no roofline replay, no report")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (5x) so FETCH_SIZE/WRITE_SIZE counters can be scaled")
     args = ap.parse_args()
@@ -258,6 +441,9 @@ def main():
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
         ms_per_step = e0.elapsed_time(e1) / K
+        if args.trace_child:
+            print(json.dumps({"ms_per_step": ms_per_step, "steps": K, "warmup": W}))
+            return
 
         # ---- roofline of the dominant kernel, timed with events on the launch stream: the K-major bf16 MFMA GEMM
         # instantiation that takes the most time per step, i.e. the one behind the five products with N = hidden
@@ -288,6 +474,8 @@ def main():
         dom_ms = e0.elapsed_time(e1) / (reps * len(dom))
         dom_flops = sum(2.0 * M * N * Kd for (_, M, N, Kd, *_r) in dom) / len(dom)
         achieved = dom_flops / (dom_ms * 1e-3) / 1e12
+        dom_name = ("K-major bf16 MFMA GEMM instantiation behind the %d products with N = hidden (%s)"
+                    % (len(dom), ", ".join(g[0] for g in dom)))
 
     if args.calibrate_copy:
         src = torch.zeros(128 * 1024 * 1024, dtype=torch.bfloat16, device="cuda")     # 256 MiB
@@ -315,12 +503,25 @@ def main():
         "tokens_per_s_valid": valid_tokens / (ms_per_step * 1e-3),
         "step_gemm_tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
         "wall_ms_per_step": wall * 1e3 / K,
-        "roofline": {"bound": "mfma", "kernel": DOMINANT_KERNEL_NAME.get(args.workload, "K-major bf16 MFMA GEMM, products with N = hidden"),
-                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+        "roofline": {"bound": "mfma", "kernel": dom_name, "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "avg_launch_us": dom_ms * 1e3,
                      "flops_per_launch": dom_flops,
-                     "traffic": DOMINANT_KERNEL_TRAFFIC_BYTES.get(args.workload), "traffic_unit": "bytes/launch"},
+                     "timing": "HIP events on the launch stream around %d back-to-back replays of the kernel's %d "
+                               "launches per step (same shapes and epilogues)" % (reps, len(dom)),
+                     "traffic": profiled_traffic(args.workload, "dominant"), "traffic_unit": "bytes/launch"},
     }
+    if not args.no_kernels:
+        n_mat = sum(int(np.prod(inp["params"][k].shape)) for k in inp["params"] if k.startswith("w_"))
+        n_vec = sum(int(np.prod(inp["params"][k].shape)) for k in inp["params"] if not k.startswith("w_"))
+        kernels, why = kernel_breakdown(args, cfg, n_mat, n_vec)
+        out["kernels"] = kernels if kernels is not None else {"unavailable": why}
+        if kernels is not None:
+            # the dominant kernel's figures inside the step (cold operands, neighbours' tails), beside the replay above
+            for a in kernels["per_kernel"]:
+                if a["bound"] == "mfma" and a["launches_per_step"] == len(dom) and a.get("frac") is not None:
+                    out["roofline"]["in_step_avg_launch_us"] = round(a["us_per_step"] / a["launches_per_step"], 2)
+                    out["roofline"]["in_step_frac"] = a["frac"]
+                    break
     if not args.no_cpu:
         from oracle.step import train_step
         p = {k: v.astype(np.float64) for k, v in inp["params"].items()}
