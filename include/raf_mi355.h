@@ -339,7 +339,8 @@ raf_status raf_op_dropout_residual_ln_bwd(const raf_layer_desc *desc, int32_t si
  * inside the library, RAF_NOALLOC_LN_BWD_PARTIAL_FLOATS floats (3 MiB) per GPU, held
  * until the process ends.  Same kernels, bit-identical results.  The call allocates
  * nothing.  RAF_EWORKSPACE when raf_op_ln_bwd_partial_floats(hidden, rows) exceeds
- * that size (hidden > 1024 with the present kernels); nothing is launched then.  All
+ * that size (with the present kernels it holds hidden = 768 up to 5456 rows and hidden
+ * = 1024 up to 4096 rows); nothing is launched then.  All
  * calls on one GPU share the array: calls that overlap on one GPU (different streams
  * or host threads) race and must be serialised by the caller; calls in stream order
  * need no clearing in between.  The first call on a device looks the array up (it may

@@ -221,9 +221,8 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ a, co
 // LDS and writes one partial row; a second kernel sums the partial rows in a
 // fixed order, so the result does not depend on scheduling.
 constexpr int LN_BWD_MAX_BLOCKS = 256;
-constexpr int LN_BWD_THREADS = 256;
 
-template <typename T, int LPR, int NV, bool HAS_LN>
+template <typename T, int LPR, int NV, bool HAS_LN, int LN_BWD_THREADS>
 __global__ __launch_bounds__(LN_BWD_THREADS) void ln_bwd_kernel(const T* __restrict__ dout, const T* __restrict__ dout2,
                                                      const T* __restrict__ z, const float* __restrict__ mu,
                                                      const float* __restrict__ rstd, const float* __restrict__ gamma,
@@ -397,6 +396,158 @@ __global__ __launch_bounds__(LN_BWD_THREADS) void ln_bwd_kernel(const T* __restr
   for (int c = threadIdx.x; c < 3 * H; c += LN_BWD_THREADS) {
     float v = red[c];
     for (int sl = 1; sl < slices; ++sl) v += red[sl * 3 * H + c];
+    partial[(long)blockIdx.x * 3 * H + c] = v;
+  }
+}
+
+// The same operator with one row per lane group and no row loop: 512 threads (two or more wavefronts per SIMD, so
+// the arithmetic of one overlaps the memory round trips of another), every operand of the row requested up front,
+// and the three column contributions of a row reduced across the lane groups of a wavefront and handed to LDS as
+// soon as they exist instead of being carried in registers.  Partial rows have the layout of ln_bwd_kernel.
+constexpr int LN_ROW_THREADS = 512;
+
+// Adds the eight values of a column vector over the lane groups of a wavefront that own the same columns and stores
+// the totals at dst[e * nvec + vec].  Groups narrower than half a wavefront are first folded with xor shuffles; the two
+// halves are then folded with v_permlane32_swap, which exchanges the upper half of one register with the lower half of
+// another: after swapping (a, b) the sum of the pair holds a's total in lanes 0..31 and b's in lanes 32..63, one
+// exchange and one store instruction per two elements.
+template <int LPR>
+__device__ __forceinline__ void store_column_totals(float* dst, float (&v)[8], int nvec, int vec, bool on) {
+  const int wlane = threadIdx.x & 63;
+  if (LPR == 64) {
+    if (on) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dst[e * nvec + vec] = v[e];
+    }
+    return;
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e)
+#pragma unroll
+    for (int o = LPR; o < 32; o <<= 1) v[e] += __shfl_xor(v[e], o, WAVE);
+  const int half = wlane >> 5;
+  const bool writer = on && (wlane & 31) < LPR;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[2 * j]), __float_as_uint(v[2 * j + 1]), false, false);
+    const float total = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    if (writer) dst[(2 * j + half) * nvec + vec] = total;
+  }
+}
+
+template <typename T, int LPR, int NV, bool HAS_LN>
+__global__ __launch_bounds__(LN_ROW_THREADS) void ln_bwd_row_kernel(
+    const T* __restrict__ dout, const T* __restrict__ dout2, const T* __restrict__ z, const float* __restrict__ mu,
+    const float* __restrict__ rstd, const float* __restrict__ gamma, const T* __restrict__ dres, T* __restrict__ dz,
+    T* __restrict__ da, float* __restrict__ partial, long nrows, int H, DropSite drop, DropSite drop_in) {
+  extern __shared__ float red[];   // [wavefront][3][8][H/8]: column vec*8+e of sum k sits at k*H + e*(H/8) + vec
+  constexpr int NWAVE = LN_ROW_THREADS / 64;
+  const int lane = threadIdx.x & (LPR - 1);
+  const int nvec = H / 8;
+  const long row_raw = (long)blockIdx.x * (LN_ROW_THREADS / LPR) + threadIdx.x / LPR;
+  const bool live = row_raw < nrows;
+  const long row = live ? row_raw : nrows - 1;   // a group without a row reads the last one and contributes zeros
+  float* mine = red + (threadIdx.x >> 6) * 3 * H;
+  typedef typename Vec8<T>::Raw Raw;
+  Raw rg[NV], rg2[NV], rz[NV], rres[NV];
+#pragma unroll
+  for (int t = 0; t < NV; ++t) {
+    const int vec = lane + LPR * t;
+    const long off = row * H + (vec < nvec ? vec : nvec - 1) * 8;
+    rg[t] = Vec8<T>::load_raw(dout + off);
+    if (dout2) rg2[t] = Vec8<T>::load_raw(dout2 + off);
+    if (HAS_LN) rz[t] = Vec8<T>::load_raw(z + off);
+    if (dres) rres[t] = Vec8<T>::load_raw(dres + off);
+  }
+  float mean = 0.f, rs = 0.f;
+  if (HAS_LN) {
+    mean = mu[row];
+    rs = rstd[row];
+  }
+  float g[NV][8], xh[NV][8];
+  float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int t = 0; t < NV; ++t) {
+    const int vec = lane + LPR * t;
+    const bool on = vec < nvec;
+    const long off = row * H + (on ? vec : nvec - 1) * 8;
+    Vec8<T>::unpack(rg[t], g[t]);
+    if (dout2) {
+      float g2[8];
+      Vec8<T>::unpack(rg2[t], g2);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) g[t][e] += g2[e];
+    }
+    if (drop_in.enabled) {   // the incoming gradient passes a dropout that follows the LayerNorm
+      float mult[8];
+      drop_mult8(drop_in, (uint64_t)off, mult);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) g[t][e] *= mult[e];
+    }
+    if (!(on && live)) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) g[t][e] = 0.f;
+    }
+    if (HAS_LN) {
+      float zv[8], gm[8], cg[8], cb[8];
+      Vec8<T>::unpack(rz[t], zv);
+      load8f(gamma + (on ? vec : nvec - 1) * 8, gm);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        xh[t][e] = (zv[e] - mean) * rs;
+        cg[e] = g[t][e] * xh[t][e];
+        cb[e] = g[t][e];
+        g[t][e] *= gm[e];           // dxhat
+        s1 += g[t][e];
+        s2 += g[t][e] * xh[t][e];
+      }
+      store_column_totals<LPR>(mine, cg, nvec, vec, on);
+      store_column_totals<LPR>(mine + H, cb, nvec, vec, on);
+    }
+  }
+  if (HAS_LN) {
+    s1 = group_sum<LPR>(s1) / (float)H;
+    s2 = group_sum<LPR>(s2) / (float)H;
+  }
+#pragma unroll
+  for (int t = 0; t < NV; ++t) {
+    const int vec = lane + LPR * t;
+    const bool on = vec < nvec;
+    const long off = row * H + (on ? vec : nvec - 1) * 8;
+    float o[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = HAS_LN ? rs * (g[t][e] - s1 - xh[t][e] * s2) : g[t][e];
+    if (dres) {
+      float r[8];
+      Vec8<T>::unpack(rres[t], r);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] += r[e];
+    }
+    if (dz && on && live) Vec8<T>::store(dz + off, o);
+    if (da) {
+      if (drop.enabled) {
+        float mult[8];
+        drop_mult8(drop, (uint64_t)off, mult);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] *= mult[e];
+      }
+      if (on && live) Vec8<T>::store(da + off, o);
+      else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = 0.f;
+      }
+      store_column_totals<LPR>(mine + 2 * H, o, nvec, vec, on);
+    }
+  }
+  __syncthreads();
+  const int k_begin = HAS_LN ? 0 : 2 * H, k_end = da ? 3 * H : 2 * H;
+  for (int c = (int)threadIdx.x; c < 3 * H; c += LN_ROW_THREADS) {
+    float v = 0.f;
+    if (c >= k_begin && c < k_end) {   // sums this call does not form (no LayerNorm, no da) are written as zeros
+      v = red[c];
+#pragma unroll
+      for (int w = 1; w < NWAVE; ++w) v += red[w * 3 * H + c];
+    }
     partial[(long)blockIdx.x * 3 * H + c] = v;
   }
 }
@@ -600,18 +751,67 @@ raf_status launch_ln_fwd(const raf_layer_desc& d, int site, int64_t rows, const 
   return check_launch();
 }
 
-static int ln_bwd_blocks(int hidden, int64_t rows) {
+// Which of the two adjoint kernels a shape takes, and with how many workgroups (= partial rows): one row per lane
+// group (ln_bwd_row_kernel) while its LDS copies fit and the partial rows stay few, the looping kernel otherwise.
+constexpr int LN_ROW_MAX_BLOCKS = 1024;
+struct LnBwdPlan {
+  bool row_kernel;
+  int blocks;
+};
+static LnBwdPlan ln_bwd_plan(int hidden, int64_t rows) {
   const RowGeom g = row_geom(hidden);
-  const long groups_per_block = LN_BWD_THREADS / g.lpr;
+  const long per_block = LN_ROW_THREADS / g.lpr;
+  const long nb_row = (rows + per_block - 1) / per_block;
+  const size_t lds_row = (size_t)(LN_ROW_THREADS / 64) * 3 * hidden * sizeof(float);
+  if (lds_row <= 144 * 1024 && nb_row <= LN_ROW_MAX_BLOCKS) return LnBwdPlan{true, (int)(nb_row < 1 ? 1 : nb_row)};
+  const long groups_per_block = 256 / g.lpr;
   long nb = (rows + groups_per_block - 1) / groups_per_block;   // one row per group until the block cap
   if (nb < 1) nb = 1;
   if (nb > LN_BWD_MAX_BLOCKS) nb = LN_BWD_MAX_BLOCKS;
-  return (int)nb;
+  return LnBwdPlan{false, (int)nb};
 }
 
 size_t ln_bwd_partial_floats(int hidden, int64_t rows) {
   if (hidden <= 0 || rows <= 0) return 0;
-  return (size_t)ln_bwd_blocks(hidden, rows) * 3 * (size_t)hidden;
+  return (size_t)ln_bwd_plan(hidden, rows).blocks * 3 * (size_t)hidden;
+}
+
+struct LnBwdArgs {
+  const void *dout, *dout2, *z, *dres;
+  const float *mu, *rstd, *gamma;
+  void *dz, *da;
+  float* partial;
+  long rows;
+  int H;
+  DropSite drop, drop_in;
+  int slices;
+};
+template <typename T, int LPR, int NV, bool HAS_LN, int TH>
+static bool launch_ln_bwd_inst(const LnBwdArgs& a, int nb, size_t shm, hipStream_t st) {
+  auto kern = ln_bwd_kernel<T, LPR, NV, HAS_LN, TH>;
+  static LdsLimitOnce lds_limit;   // per instantiation
+  if (shm > 48 * 1024 && !lds_limit.ensure((const void*)kern, (int)shm)) return false;
+  hipLaunchKernelGGL(kern, dim3(nb), dim3(TH), shm, st, (const T*)a.dout, (const T*)a.dout2, (const T*)a.z, a.mu, a.rstd,
+                     a.gamma, (const T*)a.dres, (T*)a.dz, (T*)a.da, a.partial, a.rows, a.H, a.drop, a.drop_in, a.slices);
+  return true;
+}
+template <typename T, int LPR, int NV, bool HAS_LN>
+static bool launch_ln_bwd_row_inst(const LnBwdArgs& a, int nb, size_t shm, hipStream_t st) {
+  auto kern = ln_bwd_row_kernel<T, LPR, NV, HAS_LN>;
+  static LdsLimitOnce lds_limit;   // per instantiation
+  if (shm > 48 * 1024 && !lds_limit.ensure((const void*)kern, (int)shm)) return false;
+  hipLaunchKernelGGL(kern, dim3(nb), dim3(LN_ROW_THREADS), shm, st, (const T*)a.dout, (const T*)a.dout2, (const T*)a.z,
+                     a.mu, a.rstd, a.gamma, (const T*)a.dres, (T*)a.dz, (T*)a.da, a.partial, a.rows, a.H, a.drop,
+                     a.drop_in);
+  return true;
+}
+template <typename T, int LPR, int NV>
+static bool launch_ln_bwd_geom(const LnBwdArgs& a, bool row_kernel, int nb, size_t shm, hipStream_t st) {
+  if (row_kernel)
+    return a.gamma ? launch_ln_bwd_row_inst<T, LPR, NV, true>(a, nb, shm, st)
+                   : launch_ln_bwd_row_inst<T, LPR, NV, false>(a, nb, shm, st);
+  return a.gamma ? launch_ln_bwd_inst<T, LPR, NV, true, 256>(a, nb, shm, st)
+                 : launch_ln_bwd_inst<T, LPR, NV, false, 256>(a, nb, shm, st);
 }
 
 raf_status launch_ln_bwd(const raf_layer_desc& d, int site, int64_t rows, const void* dout, const void* dout2,
@@ -629,36 +829,23 @@ raf_status launch_ln_bwd(const raf_layer_desc& d, int site, int64_t rows, const 
     return RAF_EINVAL;
   if (!row_shape_ok(d.hidden)) return RAF_ENOTSUP;
   if ((uint64_t)rows * d.hidden / 4 > 0xffffffffull) return RAF_ENOTSUP;
-  const DropSite drop = make_drop_site(d, site, step);
-  const DropSite drop_in = make_drop_site(d, site_in, step);
   const int H = d.hidden;
-  const int nb = ln_bwd_blocks(H, rows);
-  const int slices = H <= 1024 ? 4 : (H <= 2048 ? 2 : 1);   // LDS copies of the column sums: at most 48 KiB
+  const LnBwdPlan plan = ln_bwd_plan(H, rows);
+  const int nb = plan.blocks;
+  // LDS copies of the column sums (3 * H floats each): one per wavefront in the row kernel, at most 48 KiB otherwise
+  const int slices = plan.row_kernel ? LN_ROW_THREADS / 64 : (H <= 1024 ? 4 : (H <= 2048 ? 2 : 1));
   const size_t shm = (size_t)slices * 3 * H * sizeof(float);
-#define CALL(LPR, NV)                                                                                               \
-  {                                                                                                                 \
-    if (d.precision == RAF_F32) {                                                                                   \
-      if (gamma)                                                                                                    \
-        hipLaunchKernelGGL((ln_bwd_kernel<float, LPR, NV, true>), dim3(nb), dim3(LN_BWD_THREADS), shm, st, (const float*)dout, \
-                           (const float*)dout2, (const float*)z, mu, rstd, gamma, (const float*)dres, (float*)dz,   \
-                           (float*)da, partial, (long)rows, H, drop, drop_in, slices);                                               \
-      else                                                                                                          \
-        hipLaunchKernelGGL((ln_bwd_kernel<float, LPR, NV, false>), dim3(nb), dim3(LN_BWD_THREADS), shm, st,                    \
-                           (const float*)dout, (const float*)dout2, (const float*)z, mu, rstd, gamma,               \
-                           (const float*)dres, (float*)dz, (float*)da, partial, (long)rows, H, drop, drop_in, slices);               \
-    } else {                                                                                                        \
-      if (gamma)                                                                                                    \
-        hipLaunchKernelGGL((ln_bwd_kernel<bf16_t, LPR, NV, true>), dim3(nb), dim3(LN_BWD_THREADS), shm, st,                    \
-                           (const bf16_t*)dout, (const bf16_t*)dout2, (const bf16_t*)z, mu, rstd, gamma,            \
-                           (const bf16_t*)dres, (bf16_t*)dz, (bf16_t*)da, partial, (long)rows, H, drop, drop_in, slices);   \
-      else                                                                                                          \
-        hipLaunchKernelGGL((ln_bwd_kernel<bf16_t, LPR, NV, false>), dim3(nb), dim3(LN_BWD_THREADS), shm, st,                   \
-                           (const bf16_t*)dout, (const bf16_t*)dout2, (const bf16_t*)z, mu, rstd, gamma,            \
-                           (const bf16_t*)dres, (bf16_t*)dz, (bf16_t*)da, partial, (long)rows, H, drop, drop_in, slices);   \
-    }                                                                                                               \
+  const LnBwdArgs a{dout, dout2, z, dres, mu, rstd, gamma, dz, da, partial, (long)rows, H,
+                    make_drop_site(d, site, step), make_drop_site(d, site_in, step), slices};
+  bool ok = false;
+#define CALL(LPR, NV)                                                                       \
+  {                                                                                         \
+    if (d.precision == RAF_F32) ok = launch_ln_bwd_geom<float, LPR, NV>(a, plan.row_kernel, nb, shm, st); \
+    else ok = launch_ln_bwd_geom<bf16_t, LPR, NV>(a, plan.row_kernel, nb, shm, st);                \
   }
   RAF_DISPATCH_GEOM(row_geom(H), CALL);
 #undef CALL
+  if (!ok) return RAF_EHIP;
   raf_status rc = check_launch();
   if (rc != RAF_OK) return rc;
   const ReduceJob job{partial, nb, H, 3, gamma ? dgamma : nullptr, gamma ? dbeta : nullptr, da ? dbias : nullptr, 3 * H, H / 8};
