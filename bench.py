@@ -100,7 +100,7 @@ def launch_work(cfg, n_params_matrix, n_params_vector):
 KERNEL_CLASSES = (("gemm_bf16_spec_kernel", "wgrad_group"), ("gemm_bf16_group_kernel", "wgrad_group"),
                   ("gemm_bf16_", "gemm"), ("gemm_f32", "gemm"), ("attn_fwd_fused", "attn_fwd"),
                   ("attn_flash_fwd", "attn_fwd"), ("attn_bwd_full", "attn_bwd"), ("attn_flash_dq", "attn_bwd_dq"),
-                  ("attn_flash_dkv", "attn_bwd_dkv"), ("ln_fwd_kernel", "ln_fwd"), ("ln_bwd_kernel", "ln_bwd"),
+                  ("attn_flash_dkv", "attn_bwd_dkv"), ("ln_fwd_kernel", "ln_fwd"), ("ln_bwd_", "ln_bwd"),
                   ("transpose_bf16", "transpose"), ("loss_seed", "loss_seed"), ("loss_final", "loss_final"),
                   ("adam_kernel", "adam"), ("colsum_kernel", "colsum"), ("reduce_partials", "reduce"))
 
