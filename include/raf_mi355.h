@@ -94,9 +94,16 @@ typedef enum { RAF_REMAT_QKV = 1, RAF_REMAT_CTX = 2, RAF_REMAT_FFN1 = 4 } raf_re
  * Shapes ([out,in] row-major for matrices): w_qkv [3H,H] (rows: Q block, K
  * block, V block), b_qkv [3H], w_o [H,H], b_o [H], ln1_g/ln1_b [H],
  * w_1 [F,H], b_1 [F], w_2 [H,F], b_2 [H], ln2_g/ln2_b [H].
- * As weights: w_* in compute dtype, all vectors float.  As gradients: all float. */
+ * As weights: w_* in compute dtype, all vectors float.  As gradients: all float.
+ * wt_*: optional, read by raf_layer_bwd in RAF_BF16_AMP mode only (ignored
+ * elsewhere, and in a gradient struct): bfloat16 transposed copies [in,out] of the
+ * four matrices (wt_qkv [H,3H], wt_o [H,H], wt_1 [H,F], wt_2 [F,H]), which the
+ * input-gradient products contract over.  All four non-NULL: they must hold exactly
+ * the transposes of w_* (raf_adam_step keeps them so through raf_adam_tensor.lowp_t).
+ * Any of them NULL: the backward pass forms the transposes itself in scratch. */
 typedef struct {
   void *w_qkv, *b_qkv, *w_o, *b_o, *ln1_g, *ln1_b, *w_1, *b_1, *w_2, *b_2, *ln2_g, *ln2_b;
+  void *wt_qkv, *wt_o, *wt_1, *wt_2;
 } raf_layer_tensors;
 
 /* Sizes in bytes of the two caller-provided buffers of a layer.
@@ -141,7 +148,13 @@ raf_status raf_loss_seed(int32_t precision, const void *y, const void *G, int64_
 
 /* One tensor of the optimizer's list.  master/grad/m/v: [dev] float[n];
  * lowp: [dev] bfloat16[n] copy of the updated master (the AMP cast fused into
- * the producer, Section 3.1.2), or NULL.  n >= 0; pointers 16-byte aligned. */
+ * the producer, Section 3.1.2), or NULL.  n >= 0; pointers 16-byte aligned.
+ * lowp_t: [dev] bfloat16 [cols, rows], or NULL: a second copy of the updated master,
+ * transposed, the tensor being viewed as a [rows, cols] row-major matrix
+ * (rows * cols == n, both multiples of 8, else RAF_EINVAL): the operand layout the
+ * input-gradient products of raf_layer_bwd want (raf_layer_tensors.wt_*), written by
+ * the optimizer so that no transpose pass runs in the backward pass.  rows and cols
+ * are ignored when lowp_t is NULL. */
 typedef struct {
   float *master;
   const float *grad;
@@ -149,6 +162,8 @@ typedef struct {
   float *v;
   void *lowp;
   int64_t n;
+  void *lowp_t;
+  int32_t rows, cols;
 } raf_adam_tensor;
 
 /* Fused multi-tensor Adam (optimizer inside the step, in-place update; Section 3).

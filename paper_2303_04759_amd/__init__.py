@@ -39,8 +39,11 @@ class LayerDesc(C.Structure):
                 ("seed", C.c_uint64), ("layer_id", C.c_uint32), ("remat", C.c_uint32)]
 
 
+WT_NAMES = ("wt_qkv", "wt_o", "wt_1", "wt_2")      # optional transposed bf16 copies of the four matrices
+
+
 class LayerTensors(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in PARAM_NAMES]
+    _fields_ = [(n, C.c_void_p) for n in PARAM_NAMES + WT_NAMES]
 
 
 class EmbedDesc(C.Structure):
@@ -63,7 +66,8 @@ class MlmTensors(C.Structure):
 
 class AdamTensor(C.Structure):
     _fields_ = [("master", C.c_void_p), ("grad", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p),
-                ("lowp", C.c_void_p), ("n", C.c_int64)]
+                ("lowp", C.c_void_p), ("n", C.c_int64), ("lowp_t", C.c_void_p), ("rows", C.c_int32),
+                ("cols", C.c_int32)]
 
 
 class ScalerState(C.Structure):
@@ -213,10 +217,12 @@ def make_desc(cfg):
 
 
 def make_tensors(d):
-    """LayerTensors from a dict name -> tensor."""
+    """LayerTensors from a dict name -> tensor (the wt_* entries are optional)."""
     t = LayerTensors()
     for n in PARAM_NAMES:
         setattr(t, n, _ptr(d[n]))
+    for n in WT_NAMES:
+        setattr(t, n, _ptr(d.get(n)))
     return t
 
 
@@ -275,11 +281,15 @@ def read_scaler_state(state):
 
 
 def make_adam_list(entries):
-    """entries: iterable of (master, grad, m, v, lowp_or_None) tensors -> (ctypes array, count)."""
+    """entries: iterable of (master, grad, m, v, lowp_or_None[, lowp_t_or_None]) tensors -> (ctypes array, count).
+    With lowp_t the master must be a matrix; its [rows, cols] are passed along."""
     entries = list(entries)
     arr = (AdamTensor * max(1, len(entries)))()
-    for i, (w, g, m, v, lowp) in enumerate(entries):
-        arr[i] = AdamTensor(_ptr(w), _ptr(g), _ptr(m), _ptr(v), _ptr(lowp), w.numel())
+    for i, e in enumerate(entries):
+        w, g, m, v, lowp = e[:5]
+        lowp_t = e[5] if len(e) > 5 else None
+        rows, cols = (w.shape[0], w.shape[1]) if lowp_t is not None else (0, 0)
+        arr[i] = AdamTensor(_ptr(w), _ptr(g), _ptr(m), _ptr(v), _ptr(lowp), w.numel(), _ptr(lowp_t), rows, cols)
     return arr, len(entries)
 
 

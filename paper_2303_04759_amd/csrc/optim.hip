@@ -8,6 +8,9 @@ namespace raf {
 
 constexpr int ADAM_MAX_TENSORS = 48;       // per launch (kernel-argument budget)
 constexpr int ADAM_CHUNK = 256 * 4 * 4;    // elements per block
+// tensors with a transposed copy are walked in tiles of 32 rows x 128 columns (= one chunk): row pieces of 512 bytes
+// on the float side, 64-byte column pieces on the transposed bf16 side (measured against 64 x 64 and 16 x 256)
+constexpr int ADAM_TILE_R = 32, ADAM_TILE_C = ADAM_CHUNK / ADAM_TILE_R;
 
 struct AdamTable {
   float* master[ADAM_MAX_TENSORS];
@@ -15,7 +18,9 @@ struct AdamTable {
   float* m[ADAM_MAX_TENSORS];
   float* v[ADAM_MAX_TENSORS];
   bf16_t* lowp[ADAM_MAX_TENSORS];
+  bf16_t* lowp_t[ADAM_MAX_TENSORS];        // transposed bf16 copy, or null
   long n[ADAM_MAX_TENSORS];
+  int rows[ADAM_MAX_TENSORS], cols[ADAM_MAX_TENSORS];   // matrix view of a tensor with lowp_t
   int block_start[ADAM_MAX_TENSORS + 1];   // first block of each tensor
   int count;
 };
@@ -48,6 +53,63 @@ __global__ __launch_bounds__(256) void adam_kernel(AdamTable tab, AdamHyper h, c
   float* __restrict__ Mo = tab.m[ti];
   float* __restrict__ Vo = tab.v[ti];
   bf16_t* __restrict__ L = tab.lowp[ti];
+  bf16_t* __restrict__ LT = tab.lowp_t[ti];
+  if (LT) {
+    // A matrix that also keeps a transposed bf16 copy: one tile per block.  Each thread updates pieces of 4 consecutive
+    // elements, leaves the rounded weights in an LDS tile stored transposed, and the block then writes the tile's
+    // columns as rows of the transposed copy, 16 bytes per store.
+    __shared__ uint16_t tile[ADAM_TILE_C][ADAM_TILE_R + 2];   // [column][row] of the tile
+    constexpr int LANES_C = ADAM_TILE_C / 4;                   // threads along a row piece
+    constexpr int ROWS_PASS = 256 / LANES_C;                   // rows per pass of the workgroup
+    const int rows = tab.rows[ti], cols = tab.cols[ti];
+    const int tiles_c = (cols + ADAM_TILE_C - 1) / ADAM_TILE_C;
+    const int tb = (int)blockIdx.x - tab.block_start[ti];
+    const int r0 = (tb / tiles_c) * ADAM_TILE_R, c0 = (tb % tiles_c) * ADAM_TILE_C;
+    const int cl = (threadIdx.x % LANES_C) * 4;
+#pragma unroll
+    for (int it = 0; it < ADAM_TILE_R / ROWS_PASS; ++it) {
+      const int rl = it * ROWS_PASS + (threadIdx.x / LANES_C);
+      const int r = r0 + rl, c = c0 + cl;
+      if (r < rows && c < cols) {      // cols is a multiple of 8: a 4-element piece is inside or outside as a whole
+        const long i = (long)r * cols + c;
+        float4 w = *reinterpret_cast<const float4*>(W + i);
+        const float4 g = *reinterpret_cast<const float4*>(G + i);
+        float4 m = *reinterpret_cast<const float4*>(Mo + i);
+        float4 v = *reinterpret_cast<const float4*>(Vo + i);
+        adam_update(w.x, g.x, m.x, v.x, h);
+        adam_update(w.y, g.y, m.y, v.y, h);
+        adam_update(w.z, g.z, m.z, v.z, h);
+        adam_update(w.w, g.w, m.w, v.w, h);
+        *reinterpret_cast<float4*>(W + i) = w;
+        *reinterpret_cast<float4*>(Mo + i) = m;
+        *reinterpret_cast<float4*>(Vo + i) = v;
+        uint2 p;
+        p.x = pack_bf16x2(w.x, w.y);
+        p.y = pack_bf16x2(w.z, w.w);
+        if (L) *reinterpret_cast<uint2*>(L + i) = p;
+        tile[cl + 0][rl] = (uint16_t)(p.x & 0xffffu);
+        tile[cl + 1][rl] = (uint16_t)(p.x >> 16);
+        tile[cl + 2][rl] = (uint16_t)(p.y & 0xffffu);
+        tile[cl + 3][rl] = (uint16_t)(p.y >> 16);
+      }
+    }
+    __syncthreads();
+    // transposed copy: row (c0 + tc) of [cols, rows], 8 consecutive elements (16 bytes) per store
+    constexpr int PIECES = ADAM_TILE_R / 8;                    // 16-byte pieces per tile column
+    for (int q = threadIdx.x; q < ADAM_TILE_C * PIECES; q += 256) {
+      const int tc = q / PIECES, rl = (q % PIECES) * 8;
+      if (c0 + tc < cols && r0 + rl < rows) {   // rows is a multiple of 8
+        const uint16_t* src = &tile[tc][rl];
+        uint4 o;
+        o.x = (uint32_t)src[0] | ((uint32_t)src[1] << 16);
+        o.y = (uint32_t)src[2] | ((uint32_t)src[3] << 16);
+        o.z = (uint32_t)src[4] | ((uint32_t)src[5] << 16);
+        o.w = (uint32_t)src[6] | ((uint32_t)src[7] << 16);
+        *reinterpret_cast<uint4*>(LT + (long)(c0 + tc) * rows + r0 + rl) = o;
+      }
+    }
+    return;
+  }
   const long base = (long)(blockIdx.x - tab.block_start[ti]) * ADAM_CHUNK;
 #pragma unroll
   for (int it = 0; it < 4; ++it) {
@@ -224,6 +286,10 @@ static raf_status check_adam_list(const raf_adam_tensor* list, int32_t count) {
     if (!a.master || !a.grad || !a.m || !a.v) return RAF_EINVAL;
     if (!aligned16(a.master) || !aligned16(a.grad) || !aligned16(a.m) || !aligned16(a.v) || !aligned16(a.lowp))
       return RAF_EINVAL;
+    if (a.lowp_t) {
+      if (!aligned16(a.lowp_t) || a.rows <= 0 || a.cols <= 0 || (a.rows % 8) || (a.cols % 8)) return RAF_EINVAL;
+      if ((int64_t)a.rows * a.cols != a.n) return RAF_EINVAL;
+    }
   }
   return RAF_OK;
 }
@@ -240,11 +306,13 @@ static raf_status for_each_adam_table(const raf_adam_tensor* list, int32_t count
     while (i < count && tab.count < ADAM_MAX_TENSORS) {
       const raf_adam_tensor& a = list[i++];
       if (a.n == 0) continue;
-      const long nb = (a.n + ADAM_CHUNK - 1) / ADAM_CHUNK;
+      const long nb = a.lowp_t ? (long)((a.rows + ADAM_TILE_R - 1) / ADAM_TILE_R) * ((a.cols + ADAM_TILE_C - 1) / ADAM_TILE_C)
+                               : (a.n + ADAM_CHUNK - 1) / ADAM_CHUNK;
       if (blocks + nb > 0x7fffffff) return RAF_ENOTSUP;
       const int k = tab.count++;
       tab.master[k] = a.master; tab.grad[k] = a.grad; tab.m[k] = a.m; tab.v[k] = a.v;
       tab.lowp[k] = (bf16_t*)a.lowp; tab.n[k] = a.n;
+      tab.lowp_t[k] = (bf16_t*)a.lowp_t; tab.rows[k] = a.lowp_t ? a.rows : 0; tab.cols[k] = a.lowp_t ? a.cols : 0;
       tab.block_start[k] = (int)blocks;
       blocks += nb;
     }

@@ -11,7 +11,9 @@ from . import (PARAM_NAMES, RAF_BF16_AMP, RAF_LOSS_PARTIALS, make_adam_list, mak
 
 
 class DeviceLayer:
-    def __init__(self, cfg, inputs, adam, device="cuda:0", scratch=None):
+    def __init__(self, cfg, inputs, adam, device="cuda:0", scratch=None, transposed_copies=True):
+        """transposed_copies: keep [in,out] bf16 copies of the matrices (written by raf_adam_step) and hand them to
+        raf_layer_bwd; False: the backward pass transposes the weights itself on every call."""
         if not torch.cuda.is_available():
             raise RuntimeError("DeviceLayer needs a GPU; there is no CPU path")
         self.cfg = dict(cfg)
@@ -32,6 +34,9 @@ class DeviceLayer:
                        for k in PARAM_NAMES}
         self.lowp = {k: (self.master[k].to(torch.bfloat16) if (self.amp and k.startswith("w_")) else None)
                      for k in PARAM_NAMES}
+        # transposed bf16 copies of the four matrices for the input-gradient products, kept up to date by the optimizer
+        self.lowp_t = {k: (self.lowp[k].t().contiguous() if (self.lowp[k] is not None and transposed_copies) else None)
+                       for k in PARAM_NAMES}
         self.m = {k: torch.zeros_like(v) for k, v in self.master.items()}
         self.v = {k: torch.zeros_like(v) for k, v in self.master.items()}
         self.grads = {k: torch.empty_like(v) for k, v in self.master.items()}
@@ -44,11 +49,12 @@ class DeviceLayer:
         self.dx = torch.empty_like(self.y)
         self.loss = torch.zeros(1, dtype=torch.float32, device=dev)
         self.partial = torch.empty(RAF_LOSS_PARTIALS, dtype=torch.float32, device=dev)
-        self.w_struct = make_tensors({k: (self.lowp[k] if self.lowp[k] is not None else self.master[k])
-                                      for k in PARAM_NAMES})
+        wd = {k: (self.lowp[k] if self.lowp[k] is not None else self.master[k]) for k in PARAM_NAMES}
+        wd.update({"wt" + k[1:]: self.lowp_t[k] for k in PARAM_NAMES if self.lowp_t[k] is not None})
+        self.w_struct = make_tensors(wd)
         self.g_struct = make_tensors(self.grads)
         self.adam_list, self.adam_count = make_adam_list(
-            (self.master[k], self.grads[k], self.m[k], self.v[k], self.lowp[k]) for k in PARAM_NAMES)
+            (self.master[k], self.grads[k], self.m[k], self.v[k], self.lowp[k], self.lowp_t[k]) for k in PARAM_NAMES)
 
     # one call per C entry point, in step order
     def fwd(self, step, stream=None):
@@ -115,7 +121,7 @@ class DeviceModel:
         self.sel, self.labels = i32(inputs["sel"]), i32(inputs["labels"])
         self.n_sel = int(self.sel.numel())
         # parameters: master (f32), optional bf16 copy for matrices/tables, Adam state, gradients
-        self.master, self.lowp, self.m, self.v, self.grads = {}, {}, {}, {}, {}
+        self.master, self.lowp, self.lowp_t, self.m, self.v, self.grads = {}, {}, {}, {}, {}, {}
         matrices = {"word", "pos", "head_w"}
         for k in self.EMBED + self.HEAD:
             self._add_param(k, f32(inputs["P"][k]), k in matrices)
@@ -145,18 +151,25 @@ class DeviceModel:
         self.dx = [act(), act()]                          # ping-pong gradient buffers
         self.loss = torch.zeros(1, dtype=torch.float32, device=dev)
         w = lambda k: self.lowp[k] if self.lowp[k] is not None else self.master[k]
-        self.lw = [make_tensors({k: w((l, k)) for k in PARAM_NAMES}) for l in range(self.L)]
+        self.lw = []
+        for l in range(self.L):
+            wd = {k: w((l, k)) for k in PARAM_NAMES}
+            wd.update({"wt" + k[1:]: self.lowp_t[(l, k)] for k in PARAM_NAMES if self.lowp_t[(l, k)] is not None})
+            self.lw.append(make_tensors(wd))
         self.lg = [make_tensors({k: self.grads[(l, k)] for k in PARAM_NAMES}) for l in range(self.L)]
         names = dict(head_w="head_w", head_b="head_b", ln_g="head_ln_g", ln_b="head_ln_b", word="word", dec_b="dec_b")
         self.mw = make_mlm_tensors({a: w(b) for a, b in names.items()})
         self.mg = make_mlm_tensors({a: self.grads[b] for a, b in names.items()})
         keys = list(self.master)
         self.adam_list, self.adam_count = make_adam_list(
-            (self.master[k], self.grads[k], self.m[k], self.v[k], self.lowp[k]) for k in keys)
+            (self.master[k], self.grads[k], self.m[k], self.v[k], self.lowp[k], self.lowp_t[k]) for k in keys)
 
     def _add_param(self, key, master, has_lowp):
         self.master[key] = master
         self.lowp[key] = master.to(torch.bfloat16) if (self.amp and has_lowp) else None
+        # layer matrices also keep the transposed copy the input-gradient products read (written by the optimizer)
+        layer_matrix = isinstance(key, tuple) and self.lowp[key] is not None
+        self.lowp_t[key] = self.lowp[key].t().contiguous() if layer_matrix else None
         self.m[key] = torch.zeros_like(master)
         self.v[key] = torch.zeros_like(master)
         self.grads[key] = torch.zeros_like(master)

@@ -58,8 +58,9 @@ def run_and_compare(cfg, seed, steps, random_affine=False, lens_override=None, c
             e_dw = check_update(cfg, k, t, prec, ADAM, before[k], dev,
                                 dict(w_before=p[k], w=ref["params"][k], m=ref["m"][k], v=ref["v"][k]))
             worst_dw = max(worst_dw, e_dw)
-            if lay.lowp[k] is not None:
+            if lay.lowp[k] is not None:   # the bf16 weights and their transposed copy, bit for bit
                 assert torch.equal(lay.lowp[k], lay.master[k].to(torch.bfloat16)), k
+                assert torch.equal(lay.lowp_t[k], lay.lowp[k].t()), k
         report[t] = dict(y=e_y, dx=e_dx, worst_grad=worst, worst_dw=worst_dw)
         p, m, v = ref["params"], ref["m"], ref["v"]
     if check_lower:
@@ -116,6 +117,21 @@ def test_gpt2_medium_full_size_bf16_amp():
     run_and_compare(CONFIGS["gpt2_medium"], seed=0, steps=3)
 
 
+def test_backward_with_its_own_transposes_is_bit_identical():
+    """raf_layer_bwd without the caller's transposed weight copies forms them in scratch: same results, bit for bit."""
+    announce("layer transposes in scratch")
+    cfg = dict(CONFIGS["bert_base"], batch=4)
+    inp = make_layer_inputs(cfg, seed=5)
+    a, b = DeviceLayer(cfg, inp, ADAM), DeviceLayer(cfg, inp, ADAM, transposed_copies=False)
+    for t in (1, 2):
+        a.train_step(t)
+        b.train_step(t)
+    torch.cuda.synchronize()
+    assert torch.equal(a.y, b.y) and torch.equal(a.dx, b.dx)
+    for k in PARAM_NAMES:
+        assert torch.equal(a.grads[k], b.grads[k]) and torch.equal(a.master[k], b.master[k]), k
+
+
 def test_determinism_and_step_dependence():
     announce("layer determinism")
     cfg = CONFIGS["bert_base"]
@@ -149,6 +165,7 @@ def test_checkpoint_resume_is_bit_exact():
         c.master[k].copy_(b.master[k]); c.m[k].copy_(b.m[k]); c.v[k].copy_(b.v[k])
         if c.lowp[k] is not None:
             c.lowp[k].copy_(b.lowp[k])
+            c.lowp_t[k].copy_(b.lowp_t[k])
     for t in (3, 4):
         c.train_step(t)
     torch.cuda.synchronize()

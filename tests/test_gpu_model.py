@@ -66,6 +66,8 @@ def run_model(cfg, seed):
         worst_dw = max(worst_dw, e_dw)
         if mod.lowp[key] is not None:
             assert torch.equal(mod.lowp[key], mod.master[key].to(torch.bfloat16)), key
+        if mod.lowp_t[key] is not None:
+            assert torch.equal(mod.lowp_t[key], mod.lowp[key].t()), key
 
     for k in M.EMBED_PARAMS + M.HEAD_PARAMS:
         check(k, k, ref["grads"][k], P[k], ref["P"][k], ref["mP"][k], ref["vP"][k])

@@ -339,6 +339,46 @@ def test_adam_multi_tensor_matches_oracle():
                 assert torch.equal(Ld[i], Wd[i].to(torch.bfloat16))
 
 
+def test_adam_transposed_copy_is_the_exact_transpose_and_changes_nothing_else():
+    """Tensors with a transposed bf16 copy are walked in 64 x 64 tiles: same update as the flat walk, bit for bit, the
+    copy is the transpose of the bf16 weights, and elements outside ragged edge tiles are left alone."""
+    announce("adam transposed copy")
+    rng = np.random.default_rng(5)
+    shapes = [(8, 8), (64, 64), (72, 200), (320, 1056), (768, 2304), (136, 40)]
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    for t in (1, 2):
+        flat, tiled = [], []
+        for (r, c) in shapes:
+            w = rng.standard_normal((r, c)).astype(np.float32)
+            g = (64 * rng.standard_normal((r, c))).astype(np.float32)
+            m = (0.1 * rng.standard_normal((r, c))).astype(np.float32)
+            v = (rng.standard_normal((r, c)) ** 2).astype(np.float32)
+            for dst, with_t in ((flat, False), (tiled, True)):
+                wd, gd, md, vd = dev(w), dev(g), dev(m), dev(v)
+                ld = torch.zeros(r, c, dtype=torch.bfloat16, device="cuda")
+                # the transposed copy sits inside a guarded buffer: nothing outside [c, r] may be written
+                guard = torch.full((c * r + 128,), 7.0, dtype=torch.bfloat16, device="cuda")
+                dst.append((wd, gd, md, vd, ld, guard[64:64 + c * r].view(c, r) if with_t else None, guard))
+        for group in (flat, tiled):
+            lst, cnt = raf.make_adam_list([e[:6] for e in group])
+            raf.raf_adam_step(lst, cnt, 1e-3, 0.9, 0.999, 1e-8, 0.01, t, 1.0 / 64)
+        torch.cuda.synchronize()
+        for a, b in zip(flat, tiled):
+            for k in range(5):
+                if k != 1:
+                    assert torch.equal(a[k], b[k]), (t, tuple(a[0].shape), k)
+            assert torch.equal(b[5], b[4].t()), (t, tuple(a[0].shape))
+            assert (b[6][:64] == 7.0).all() and (b[6][-64:] == 7.0).all()
+    # the matrix view must cover the tensor, with both sides multiples of 8
+    wd = torch.zeros(16, 24, device="cuda")
+    bad = raf.AdamTensor(wd.data_ptr(), wd.data_ptr(), wd.data_ptr(), wd.data_ptr(), None, 16 * 24, wd.data_ptr(), 16, 20)
+    with pytest.raises(raf.RafError):
+        raf.raf_adam_step((raf.AdamTensor * 1)(bad), 1, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, 1.0)
+    bad.rows, bad.cols = 12, 32
+    with pytest.raises(raf.RafError):
+        raf.raf_adam_step((raf.AdamTensor * 1)(bad), 1, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, 1.0)
+
+
 def test_loss_seed():
     announce("loss-seed")
     rng = np.random.default_rng(3)

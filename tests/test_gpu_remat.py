@@ -135,6 +135,7 @@ def test_rematerialised_step_replays_in_a_graph():
                 lay.master[k].copy_(state0[k][0])
                 if lay.lowp[k] is not None:
                     lay.lowp[k].copy_(state0[k][1])
+                    lay.lowp_t[k].copy_(state0[k][1].t())
                 lay.m[k].zero_()
                 lay.v[k].zero_()
             lay.y.zero_()
