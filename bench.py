@@ -78,20 +78,23 @@ def launch_work(cfg, n_params_matrix, n_params_vector):
     w["wgrad_group"] = [("4 weight gradients (+ bias/LayerNorm column sums on idle CUs)", "mfma",
                          fl(3 * H, H, T) + fl(H, H, T) + fl(F, H, T) + fl(H, F, T))]
     if pre:
-        w["ln_fwd"] = [("ln1", "hbm", 2 * TH), ("dropout+residual+ln2", "hbm", 4 * TH), ("dropout+residual", "hbm", 3 * TH)]
+        w["ln_fwd"] = [("ln1", "hbm", 2 * TH), ("dropout+residual+ln2", "hbm", 4 * TH),
+                       ("dropout+residual + loss seed", "hbm", 5 * TH)]
         w["ln_bwd"] = [("dropout3 adjoint", "hbm", 2 * TH), ("ln2 adjoint+residual", "hbm", 5 * TH),
                        ("ln1 adjoint+residual", "hbm", 4 * TH)]
     else:
-        w["ln_fwd"] = [("dropout+residual+ln1", "hbm", 4 * TH), ("dropout+residual+ln2", "hbm", 4 * TH)]
+        # the last forward kernel also takes the loss seed (reads G, writes dy): raf_layer_fwd_loss
+        w["ln_fwd"] = [("dropout+residual+ln1", "hbm", 4 * TH), ("dropout+residual+ln2 + loss seed", "hbm", 6 * TH)]
         w["ln_bwd"] = [("ln2 adjoint", "hbm", 4 * TH), ("ln1 adjoint (two incoming gradients)", "hbm", 5 * TH)]
     w["attn_fwd"] = [("scores+mask+softmax+dropout+context", "hbm", 4 * TH)]
     w["attn_bwd"] = [("attention adjoint (dQ,dK,dV)", "hbm", 7 * TH)]
     w["attn_bwd_dq"] = [("attention adjoint dQ", "hbm", 6 * TH)]
     w["attn_bwd_dkv"] = [("attention adjoint dK,dV", "hbm", 6 * TH)]
     w["transpose"] = [("4 weight transposes", "hbm", 2 * 2 * n_params_matrix)]
-    w["loss_seed"] = [("loss seed", "hbm", 3 * TH)]
+    w["loss_seed"] = [("loss seed", "hbm", 3 * TH)]      # only when the loss seed is taken by its own call
     w["loss_final"] = [("loss partial sums", "hbm", 4096)]
-    w["adam"] = [("fused Adam, 12 tensors", "hbm", 30 * n_params_matrix + 28 * n_params_vector)]
+    # per matrix element: g 4 r; m, v, master 12 r + 12 w; bf16 copy 2 w; transposed bf16 copy 2 w
+    w["adam"] = [("fused Adam, 12 tensors (+ transposed bf16 copies)", "hbm", 32 * n_params_matrix + 28 * n_params_vector)]
     w["colsum"] = [("bias-gradient column sums", "hbm", TF + 3 * TH)]
     w["reduce"] = [("second stage of column sums", "hbm", None)]
     return w

@@ -203,6 +203,19 @@ raf_status raf_scaler_init(raf_scaler_state *state, float init_scale, void *hip_
 raf_status raf_loss_seed_scaled(int32_t precision, const void *y, const void *G, int64_t n,
                                 const raf_scaler_state *state, float *loss_out, void *dy, float *partial,
                                 void *hip_stream);
+/* raf_layer_fwd and raf_loss_seed in one call: the kernel that writes y also forms
+ * dy = loss_scale * G and the partial sums of loss = sum(y * G) (y as stored), so the
+ * loss (Section 2.1: part of the training graph) costs no pass of its own (fusion of an
+ * elementwise + reduction operator into its producer, Section 3.2.2).  y and dy are
+ * bit-identical to the two separate calls; the loss differs by the order of the float
+ * summation only.  state == NULL: loss_scale is used; otherwise the scale is read from
+ * the device-resident state (as raf_loss_seed_scaled does) and loss_scale is ignored.
+ * The partial sums live in scratch. */
+raf_status raf_layer_fwd_loss(const raf_layer_desc *desc, const raf_layer_tensors *w, const void *x,
+                              const int32_t *seq_lens, void *y, const void *G, float loss_scale,
+                              const raf_scaler_state *state, float *loss_out, void *dy, void *saved, void *scratch,
+                              uint64_t step, void *hip_stream);
+
 /* state->found_inf = 1 if any element of any list[i].grad is inf or nan (it is not cleared here). */
 raf_status raf_grads_check(const raf_adam_tensor *list, int32_t count, raf_scaler_state *state, void *hip_stream);
 /* raf_adam_step with t = state->t + 1 and inv_loss_scale = state->inv_scale, both read on the

@@ -96,6 +96,9 @@ _SIGNATURES = {
                                 C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]),
     "raf_layer_bwd": (C.c_int, [C.POINTER(LayerDesc), C.POINTER(LayerTensors), C.c_void_p, C.c_void_p, C.c_void_p,
                                 C.c_void_p, C.c_void_p, C.POINTER(LayerTensors), C.c_void_p, C.c_uint64, C.c_void_p]),
+    "raf_layer_fwd_loss": (C.c_int, [C.POINTER(LayerDesc), C.POINTER(LayerTensors), C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_uint64, C.c_void_p]),
     "raf_loss_seed": (C.c_int, [C.c_int32, C.c_void_p, C.c_void_p, C.c_int64, C.c_float, C.c_void_p, C.c_void_p,
                                 C.c_void_p, C.c_void_p]),
     "raf_adam_step": (C.c_int, [C.POINTER(AdamTensor), C.c_int32, C.c_double, C.c_double, C.c_double, C.c_double,
@@ -235,6 +238,12 @@ def raf_layer_workspace(desc):
 def raf_layer_fwd(desc, w, x, seq_lens, y, saved, scratch, step, stream=None):
     _check(load_library().raf_layer_fwd(C.byref(desc), C.byref(w), _ptr(x), _ptr(seq_lens), _ptr(y), _ptr(saved),
                                         _ptr(scratch), int(step), _stream(stream)), "raf_layer_fwd")
+
+
+def raf_layer_fwd_loss(desc, w, x, seq_lens, y, G, loss_scale, state, loss_out, dy, saved, scratch, step, stream=None):
+    _check(load_library().raf_layer_fwd_loss(C.byref(desc), C.byref(w), _ptr(x), _ptr(seq_lens), _ptr(y), _ptr(G),
+                                             float(loss_scale), _ptr(state), _ptr(loss_out), _ptr(dy), _ptr(saved),
+                                             _ptr(scratch), int(step), _stream(stream)), "raf_layer_fwd_loss")
 
 
 def raf_layer_bwd(desc, w, x, dy, seq_lens, saved, dx, grads, scratch, step, stream=None):

@@ -385,9 +385,15 @@ raf_status launch_attn_flash_bwd(const raf_layer_desc& d, const void* dc, const 
                                  hipStream_t st);
 raf_status launch_attn_bwd_full(const raf_layer_desc& d, const void* dc, const void* qkv, const int32_t* lens, void* dqkv,
                                 uint64_t step, hipStream_t st);
+// Loss seed taken by the kernel that writes the layer's output: partial sums of out * G (one per workgroup, ln_fwd_blocks
+// of them) and dy = scale * G; scale_ptr != nullptr: the scale is read from device memory
+struct LossSeedDev {
+  const void* G; void* dy; float* partial; float scale; const float* scale_ptr;
+};
+int ln_fwd_blocks(int hidden, int64_t rows);
 raf_status launch_ln_fwd(const raf_layer_desc& d, int site, int64_t rows, const void* a, const void* res,
                          const float* gamma, const float* beta, void* out, void* z_out, float* mu, float* rstd,
-                         uint64_t step, hipStream_t st);
+                         uint64_t step, hipStream_t st, const LossSeedDev* loss = nullptr);
 // Deferred second stages.  The column sums that only the optimizer reads (LayerNorm and bias gradients) are
 // produced in two stages: per-block partial rows, then a reduction over the partial rows.  A caller with several of
 // them can collect the second stages (and whole column-sum problems) and run each kind in one launch at the end of

@@ -123,27 +123,48 @@ __global__ __launch_bounds__(256) void softmax_bwd_kernel(const T* __restrict__ 
 }
 
 // -------------------------------------------- dropout + residual + LN fwd --
-template <typename T, int LPR, int NV>
+// LOSS: the kernel that produces the layer's output also takes the loss seed of the benchmark workload on it:
+// loss partial sums of out * G (out as stored, one partial per workgroup) and dy = loss_scale * G.
+template <typename T, int LPR, int NV, bool LOSS>
 __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ a, const T* __restrict__ res,
                                                      const float* __restrict__ gamma, const float* __restrict__ beta,
                                                      T* __restrict__ out, T* __restrict__ z_out, float* __restrict__ mu,
                                                      float* __restrict__ rstd, long nrows, int H, float eps,
-                                                     DropSite drop) {
+                                                     DropSite drop, LossSeedDev ls) {
   const int lane = threadIdx.x & (LPR - 1);
-  const long row = ((long)blockIdx.x * 256 + threadIdx.x) / LPR;
-  if (row >= nrows) return;
+  const long row_raw = ((long)blockIdx.x * 256 + threadIdx.x) / LPR;
+  const bool live = row_raw < nrows;
+  if (!LOSS && !live) return;
+  const long row = live ? row_raw : nrows - 1;   // LOSS: a group without a row stays for the block sum and adds zero
   const int nvec = H / 8;
   float z[NV][8];
   float sum = 0.f;
   // every operand of the row is requested before the first use (one memory round trip, not one per vector)
-  typename Vec8<T>::Raw rres[NV], ra[NV];
+  typename Vec8<T>::Raw rres[NV], ra[NV], rG[NV];
 #pragma unroll
   for (int t = 0; t < NV; ++t) {
     const int vec = lane + LPR * t;
     const long off = row * H + (vec < nvec ? vec : nvec - 1) * 8;
     rres[t] = Vec8<T>::load_raw(res + off);
     if (a) ra[t] = Vec8<T>::load_raw(a + off);
+    if (LOSS) rG[t] = Vec8<T>::load_raw((const T*)ls.G + off);
   }
+  float loss_scale = ls.scale, loss_acc = 0.f;
+  if (LOSS && ls.scale_ptr) loss_scale = *ls.scale_ptr;   // dynamic loss scale, device-resident
+  // out[vec] is final: store it and take the loss seed on the value as stored
+  auto emit = [&](int t, int vec, float (&o)[8]) {
+    if (live) Vec8<T>::store(out + row * H + vec * 8, o);
+    if (LOSS) {
+      float g[8];
+      Vec8<T>::unpack(rG[t], g);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        loss_acc += Vec8<T>::round(o[e]) * g[e];
+        g[e] *= loss_scale;
+      }
+      if (live) Vec8<T>::store((T*)ls.dy + row * H + vec * 8, g);
+    }
+  };
 #pragma unroll
   for (int t = 0; t < NV; ++t) {
     const int vec = lane + LPR * t;
@@ -177,41 +198,50 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ a, co
 #pragma unroll
     for (int t = 0; t < NV; ++t) {
       const int vec = lane + LPR * t;
-      if (vec < nvec) Vec8<T>::store(out + row * H + vec * 8, z[t]);
+      if (vec < nvec) emit(t, vec, z[t]);
     }
-    return;
-  }
-  const float mean = group_sum<LPR>(sum) / (float)H;
-  float sq = 0.f;
+  } else {
+    const float mean = group_sum<LPR>(sum) / (float)H;
+    float sq = 0.f;
 #pragma unroll
-  for (int t = 0; t < NV; ++t) {
-    const int vec = lane + LPR * t;
-    if (vec < nvec) {
+    for (int t = 0; t < NV; ++t) {
+      const int vec = lane + LPR * t;
+      if (vec < nvec) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float d = z[t][e] - mean;
-        sq += d * d;
+        for (int e = 0; e < 8; ++e) {
+          const float d = z[t][e] - mean;
+          sq += d * d;
+        }
       }
     }
-  }
-  const float var = group_sum<LPR>(sq) / (float)H;
-  const float rs = 1.0f / sqrtf(var + eps);
+    const float var = group_sum<LPR>(sq) / (float)H;
+    const float rs = 1.0f / sqrtf(var + eps);
 #pragma unroll
-  for (int t = 0; t < NV; ++t) {
-    const int vec = lane + LPR * t;
-    if (vec < nvec) {
-      float gm[8], bt[8], o[8];
-      load8f(gamma + vec * 8, gm);
-      load8f(beta + vec * 8, bt);
+    for (int t = 0; t < NV; ++t) {
+      const int vec = lane + LPR * t;
+      if (vec < nvec) {
+        float gm[8], bt[8], o[8];
+        load8f(gamma + vec * 8, gm);
+        load8f(beta + vec * 8, bt);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) o[e] = (z[t][e] - mean) * rs * gm[e] + bt[e];
-      Vec8<T>::store(out + row * H + vec * 8, o);
-      if (z_out) Vec8<T>::store(z_out + row * H + vec * 8, z[t]);
+        for (int e = 0; e < 8; ++e) o[e] = (z[t][e] - mean) * rs * gm[e] + bt[e];
+        emit(t, vec, o);
+        if (z_out && live) Vec8<T>::store(z_out + row * H + vec * 8, z[t]);
+      }
+    }
+    if (lane == 0 && live) {
+      mu[row] = mean;
+      rstd[row] = rs;
     }
   }
-  if (lane == 0) {
-    mu[row] = mean;
-    rstd[row] = rs;
+  if (LOSS) {
+    // one partial per workgroup, summed in a fixed order (lanes of a wavefront, then the four wavefronts)
+    __shared__ float red[4];
+    if (!live) loss_acc = 0.f;
+    loss_acc = group_sum<64>(loss_acc);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = loss_acc;
+    __syncthreads();
+    if (threadIdx.x == 0) ls.partial[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
   }
 }
 
@@ -721,33 +751,44 @@ raf_status launch_softmax_bwd(const raf_layer_desc& d, const void* prob, const v
   return check_launch();
 }
 
+int ln_fwd_blocks(int hidden, int64_t rows) {
+  const RowGeom g = row_geom(hidden);
+  return (int)(((long)rows * g.lpr + 255) / 256);
+}
+
 raf_status launch_ln_fwd(const raf_layer_desc& d, int site, int64_t rows, const void* a, const void* res,
                          const float* gamma, const float* beta, void* out, void* z_out, float* mu, float* rstd,
-                         uint64_t step, hipStream_t st) {
+                         uint64_t step, hipStream_t st, const LossSeedDev* loss) {
   if (!res || !out || rows <= 0) return RAF_EINVAL;
   if (gamma && (!beta || !mu || !rstd)) return RAF_EINVAL;
   if (a && site != 2 && site != 3) return RAF_EINVAL;
   if (!aligned16(a) || !aligned16(res) || !aligned16(out) || !aligned16(z_out) || !aligned16(gamma) ||
       !aligned16(beta))
     return RAF_EINVAL;
+  if (loss && (!loss->G || !loss->dy || !loss->partial || !aligned16(loss->G) || !aligned16(loss->dy))) return RAF_EINVAL;
   if (!row_shape_ok(d.hidden)) return RAF_ENOTSUP;
   if ((uint64_t)rows * d.hidden / 4 > 0xffffffffull) return RAF_ENOTSUP;
   const DropSite drop = make_drop_site(d, a ? site : 0, step);
   const int H = d.hidden;
-#define CALL(LPR, NV)                                                                                              \
-  {                                                                                                                \
-    const long nblk = ((long)rows * LPR + 255) / 256;                                                              \
-    if (d.precision == RAF_F32)                                                                                    \
-      hipLaunchKernelGGL((ln_fwd_kernel<float, LPR, NV>), dim3(nblk), dim3(256), 0, st, (const float*)a,          \
-                         (const float*)res, gamma, beta, (float*)out, (float*)z_out, mu, rstd, (long)rows, H,      \
-                         d.ln_eps, drop);                                                                          \
-    else                                                                                                           \
-      hipLaunchKernelGGL((ln_fwd_kernel<bf16_t, LPR, NV>), dim3(nblk), dim3(256), 0, st, (const bf16_t*)a,        \
-                         (const bf16_t*)res, gamma, beta, (bf16_t*)out, (bf16_t*)z_out, mu, rstd, (long)rows, H,   \
-                         d.ln_eps, drop);                                                                          \
+  const LossSeedDev ls = loss ? *loss : LossSeedDev{};
+#define CALL_T(T, LPR, NV)                                                                                           \
+  {                                                                                                                  \
+    const long nblk = ((long)rows * LPR + 255) / 256;                                                                \
+    if (loss)                                                                                                        \
+      hipLaunchKernelGGL((ln_fwd_kernel<T, LPR, NV, true>), dim3(nblk), dim3(256), 0, st, (const T*)a, (const T*)res, \
+                         gamma, beta, (T*)out, (T*)z_out, mu, rstd, (long)rows, H, d.ln_eps, drop, ls);              \
+    else                                                                                                             \
+      hipLaunchKernelGGL((ln_fwd_kernel<T, LPR, NV, false>), dim3(nblk), dim3(256), 0, st, (const T*)a, (const T*)res, \
+                         gamma, beta, (T*)out, (T*)z_out, mu, rstd, (long)rows, H, d.ln_eps, drop, ls);              \
+  }
+#define CALL(LPR, NV)                                        \
+  {                                                          \
+    if (d.precision == RAF_F32) CALL_T(float, LPR, NV)       \
+    else CALL_T(bf16_t, LPR, NV)                             \
   }
   RAF_DISPATCH_GEOM(row_geom(H), CALL);
 #undef CALL
+#undef CALL_T
   return check_launch();
 }
 

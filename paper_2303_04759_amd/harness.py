@@ -7,7 +7,7 @@ import torch
 
 from . import (PARAM_NAMES, RAF_BF16_AMP, RAF_LOSS_PARTIALS, make_adam_list, make_desc, make_tensors,
                raf_adam_step, raf_adam_step_scaled, raf_grads_check, raf_layer_bwd, raf_layer_fwd,
-               raf_layer_workspace, raf_loss_seed, raf_loss_seed_scaled, raf_scaler_update)
+               raf_layer_fwd_loss, raf_layer_workspace, raf_loss_seed, raf_loss_seed_scaled, raf_scaler_update)
 
 
 class DeviceLayer:
@@ -60,6 +60,11 @@ class DeviceLayer:
     def fwd(self, step, stream=None):
         raf_layer_fwd(self.desc, self.w_struct, self.x, self.seq_lens, self.y, self.saved, self.scratch, step, stream)
 
+    def fwd_loss(self, step, stream=None, state=None):
+        """forward and loss seed in one call (the kernel that writes y forms dy and the loss partial sums)"""
+        raf_layer_fwd_loss(self.desc, self.w_struct, self.x, self.seq_lens, self.y, self.G, self.cfg["loss_scale"], state,
+                           self.loss, self.dy, self.saved, self.scratch, step, stream)
+
     def loss_seed(self, stream=None):
         raf_loss_seed(self.cfg["precision"], self.y, self.G, self.y.numel(), self.cfg["loss_scale"], self.loss,
                       self.dy, self.partial, stream)
@@ -73,24 +78,31 @@ class DeviceLayer:
         raf_adam_step(self.adam_list, self.adam_count, a["lr"], a["beta1"], a["beta2"], a["eps"],
                       a.get("weight_decay", 0.0), t, 1.0 / self.cfg["loss_scale"], stream)
 
-    def train_step_dynamic(self, step, state, scaler, stream=None):
+    def train_step_dynamic(self, step, state, scaler, stream=None, fused_loss=True):
         """The same pass under the dynamic loss scaler: every decision (scale, skip, Adam's step count) is taken on
         the device from `state` (a device byte buffer initialised with raf_scaler_init).  `step` only numbers the
         dropout masks."""
         a = self.adam
-        self.fwd(step, stream)
-        raf_loss_seed_scaled(self.cfg["precision"], self.y, self.G, self.y.numel(), state, self.loss, self.dy,
-                             self.partial, stream)
+        if fused_loss:
+            self.fwd_loss(step, stream, state)
+        else:
+            self.fwd(step, stream)
+            raf_loss_seed_scaled(self.cfg["precision"], self.y, self.G, self.y.numel(), state, self.loss, self.dy,
+                                 self.partial, stream)
         self.bwd(step, stream)
         raf_grads_check(self.adam_list, self.adam_count, state, stream)
         raf_adam_step_scaled(self.adam_list, self.adam_count, a["lr"], a["beta1"], a["beta2"], a["eps"],
                              a.get("weight_decay", 0.0), state, stream)
         raf_scaler_update(state, scaler["growth_factor"], scaler["backoff_factor"], scaler["growth_interval"], stream)
 
-    def train_step(self, t, stream=None):
-        """forward, loss seed, backward, Adam: one pass of the whole hot path."""
-        self.fwd(t, stream)
-        self.loss_seed(stream)
+    def train_step(self, t, stream=None, fused_loss=True):
+        """forward, loss seed, backward, Adam: one pass of the whole hot path.  fused_loss=False takes the loss seed
+        with its own call (raf_loss_seed) instead of inside the forward call."""
+        if fused_loss:
+            self.fwd_loss(t, stream)
+        else:
+            self.fwd(t, stream)
+            self.loss_seed(stream)
         self.bwd(t, stream)
         self.adam_step(t, stream)
 

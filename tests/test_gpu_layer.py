@@ -117,6 +117,28 @@ def test_gpt2_medium_full_size_bf16_amp():
     run_and_compare(CONFIGS["gpt2_medium"], seed=0, steps=3)
 
 
+@pytest.mark.parametrize("variant", [dict(), dict(pre_ln=1, causal=1, ln_eps=1e-5), dict(precision=0, loss_scale=1.0)])
+def test_loss_seed_inside_the_forward_call_matches_the_separate_call(variant):
+    """raf_layer_fwd_loss against raf_layer_fwd + raf_loss_seed: y, dy and everything downstream bit for bit, the loss
+    to the rounding of a float sum taken in another order (both are checked against the oracle elsewhere)."""
+    announce("layer fused loss seed", variant)
+    cfg = dict(CONFIGS["bert_base"], batch=3, seq=160, hidden=320, heads=5, ffn=1056, **variant)
+    inp = make_layer_inputs(cfg, seed=6, random_affine=True)
+    inp["seq_lens"] = np.asarray([160, 77, 5], dtype=np.int32)
+    a, b = DeviceLayer(cfg, inp, ADAM), DeviceLayer(cfg, inp, ADAM)
+    for t in (1, 2):
+        a.dy.fill_(9.0)
+        a.train_step(t, fused_loss=True)
+        b.train_step(t, fused_loss=False)
+        torch.cuda.synchronize()
+        assert torch.equal(a.y, b.y) and torch.equal(a.dy, b.dy) and torch.equal(a.dx, b.dx)
+        for k in PARAM_NAMES:
+            assert torch.equal(a.master[k], b.master[k]), k
+        la, lb = float(a.loss.item()), float(b.loss.item())
+        scale = float((a.y.float() * a.G.float()).abs().sum().item())
+        assert abs(la - lb) <= 1e-5 * scale, (la, lb)
+
+
 def test_backward_with_its_own_transposes_is_bit_identical():
     """raf_layer_bwd without the caller's transposed weight copies forms them in scratch: same results, bit for bit."""
     announce("layer transposes in scratch")
