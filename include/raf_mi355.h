@@ -100,10 +100,17 @@ typedef enum { RAF_REMAT_QKV = 1, RAF_REMAT_CTX = 2, RAF_REMAT_FFN1 = 4 } raf_re
  * four matrices (wt_qkv [H,3H], wt_o [H,H], wt_1 [H,F], wt_2 [F,H]), which the
  * input-gradient products contract over.  All four non-NULL: they must hold exactly
  * the transposes of w_* (raf_adam_step keeps them so through raf_adam_tensor.lowp_t).
- * Any of them NULL: the backward pass forms the transposes itself in scratch. */
+ * Any of them NULL: the backward pass forms the transposes itself in scratch.
+ * nonfinite: optional, read in the gradient struct of raf_layer_bwd only: [dev] int32
+ * (4-byte aligned) that the call sets to 1 if any of the twelve gradients it writes is
+ * inf or nan, and leaves alone otherwise (the caller clears it; raf_scaler_state
+ * .found_inf is such a flag).  Where the weight gradients and their reductions leave
+ * in one launch the test rides in that launch's epilogues; other shapes take one
+ * extra pass over the gradients. */
 typedef struct {
   void *w_qkv, *b_qkv, *w_o, *b_o, *ln1_g, *ln1_b, *w_1, *b_1, *w_2, *b_2, *ln2_g, *ln2_b;
   void *wt_qkv, *wt_o, *wt_1, *wt_2;
+  void *nonfinite;
 } raf_layer_tensors;
 
 /* Sizes in bytes of the two caller-provided buffers of a layer.
@@ -193,8 +200,8 @@ typedef struct {
   int32_t good_steps;   /* consecutive steps without a non-finite gradient      */
   int32_t found_inf;    /* set by raf_grads_check, cleared by raf_scaler_update */
   int64_t t;            /* optimizer steps taken so far (skipped ones excluded) */
-  float lr_over_bc1;    /* Adam constants of step t+1, written by               */
-  float inv_bc2;        /*   raf_adam_step_scaled                               */
+  float lr_over_bc1;    /* reserved (kept for the 32-byte layout; not read or    */
+  float inv_bc2;        /*   written by the present kernels)                     */
 } raf_scaler_state;
 
 /* state [dev] written: scale = init_scale (> 0, finite), counters zero. */
@@ -219,7 +226,8 @@ raf_status raf_layer_fwd_loss(const raf_layer_desc *desc, const raf_layer_tensor
 /* state->found_inf = 1 if any element of any list[i].grad is inf or nan (it is not cleared here). */
 raf_status raf_grads_check(const raf_adam_tensor *list, int32_t count, raf_scaler_state *state, void *hip_stream);
 /* raf_adam_step with t = state->t + 1 and inv_loss_scale = state->inv_scale, both read on the
- * device; a no-op on every tensor when state->found_inf is set. */
+ * device (the bias corrections 1 - beta^t are formed there in float as -expm1(t ln beta)); a
+ * no-op on every tensor when state->found_inf is set. */
 raf_status raf_adam_step_scaled(const raf_adam_tensor *list, int32_t count, double lr, double beta1, double beta2,
                                 double eps, double weight_decay, raf_scaler_state *state, void *hip_stream);
 /* The scale rule above; also advances state->t on a good step and clears found_inf.

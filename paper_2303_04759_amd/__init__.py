@@ -43,7 +43,7 @@ WT_NAMES = ("wt_qkv", "wt_o", "wt_1", "wt_2")      # optional transposed bf16 co
 
 
 class LayerTensors(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in PARAM_NAMES + WT_NAMES]
+    _fields_ = [(n, C.c_void_p) for n in PARAM_NAMES + WT_NAMES + ("nonfinite",)]
 
 
 class EmbedDesc(C.Structure):
@@ -226,6 +226,7 @@ def make_tensors(d):
         setattr(t, n, _ptr(d[n]))
     for n in WT_NAMES:
         setattr(t, n, _ptr(d.get(n)))
+    t.nonfinite = _ptr(d.get("nonfinite"))   # a device address (int), a tensor or None
     return t
 
 

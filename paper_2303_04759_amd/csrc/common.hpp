@@ -351,12 +351,16 @@ raf_status launch_gemm(int precision, const GemmArgs& g, hipStream_t st);
 // up to 4 independent weight-gradient GEMMs (A, B MN-major, float out) in one launch
 // side / nside: optional column sums (ColsumJob, at most two, bf16, same row count), reds / nred: optional second
 // stages of two-stage column sums (at most three), that the launch may take along on CUs its tiles leave idle;
-// *side_taken tells whether it did (all of them or none), otherwise the caller launches them itself
+// *side_taken tells whether it did (all of them or none), otherwise the caller launches them itself.
+// nonfinite: optional device flag; when the side work is taken the launch also sets it to 1 if any weight gradient
+// or any of the side sums is inf or nan (otherwise it is left alone and the caller has to check by other means)
 struct ColsumJob;
 struct ReduceJob;
 raf_status launch_gemm_group_wgrad(int precision, const GemmArgs* gs, int count, hipStream_t st,
                                    const ColsumJob* side = nullptr, int nside = 0, const ReduceJob* reds = nullptr,
-                                   int nred = 0, bool* side_taken = nullptr);
+                                   int nred = 0, bool* side_taken = nullptr, int* nonfinite = nullptr);
+// *flag = 1 if any element of the `count` float tensors ptrs[i][0 .. n[i]) is inf or nan (count <= 48)
+raf_status launch_nonfinite_check(const float* const* ptrs, const long* n, int count, int* flag, hipStream_t st);
 // dst[c][r] = src[r][c] for up to 4 dense row-major bf16 matrices (rows, cols multiples of 8) in one launch
 struct TransposeJob {
   const void* src; void* dst; int rows, cols;

@@ -385,7 +385,7 @@ raf_status launch_transpose_bf16(const TransposeJob* jobs, int count, hipStream_
 
 // Weight-gradient form only: A and B both MN-major, float output, no batch.
 raf_status launch_gemm_group_wgrad(int precision, const GemmArgs* gs, int count, hipStream_t st, const ColsumJob* side,
-                                   int nside, const ReduceJob* reds, int nred, bool* side_taken) {
+                                   int nside, const ReduceJob* reds, int nred, bool* side_taken, int* nonfinite) {
   if (side_taken) *side_taken = false;
   if (count <= 0 || count > GEMM_GROUP_MAX || !gs) return RAF_EINVAL;
   bool groupable = precision == RAF_BF16_AMP;
@@ -408,6 +408,7 @@ raf_status launch_gemm_group_wgrad(int precision, const GemmArgs* gs, int count,
     for (int i = 0; i < count; ++i) ds[i] = to_dev(gs[i]);
     // column sums of up to two bf16 matrices with a common row count can ride along on idle CUs
     ColsumSide sd{};
+    sd.nonfinite = nonfinite;
     if (side && nside >= 1 && nside <= 2) {
       bool ok = true;
       for (int i = 0; i < nside; ++i)

@@ -373,12 +373,15 @@ struct ColsumSide {
   // second stages of earlier two-stage column sums (sums over partial rows, see ReduceJob), taken after the above
   ReduceJob red[3];
   int nred;
+  // not null: set to 1 when any sum written here, or any weight-gradient value of the launch's tiles, is inf or nan
+  int* nonfinite;
 };
 
 // Weight-gradient group (both operands MN-major, float output) on the
 // producer/consumer direct-to-LDS kernel (gemm_pipe.hip); false when a problem
 // does not fit it (K % 64, sizes below one tile).  side: optional column sums; *side_taken tells whether the launch
 // computed them (it does when enough CUs are left without a tile), otherwise the caller has to.
+// side->nonfinite is honoured only when the side work is taken (*side_taken).
 bool launch_gemm_group_spec(const GemmDev* ds, int count, hipStream_t st, const ColsumSide* side = nullptr,
                             bool* side_taken = nullptr);
 

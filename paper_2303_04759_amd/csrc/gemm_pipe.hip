@@ -283,18 +283,21 @@ __device__ __forceinline__ void colsum_side_worker(const ColsumSide& sd, int w, 
     for (int e = 0; e < 8; ++e) red[(rg * per + vec) * 8 + e] = acc[e];
   }
   __syncthreads();
+  bool bad = false;
   for (int c = threadIdx.x; c < nv * 8; c += blockDim.x) {
     float sum = red[c];
     for (int g = 1; g < ngroups; ++g) sum += red[g * per * 8 + c];
     const int u = v0 + c / 8;
     const int jj = u < nvec0 ? 0 : 1;
     sd.out[jj][(long)(jj ? u - nvec0 : u) * 8 + (c & 7)] = sum;
+    bad |= !(sum - sum == 0.f);   // x - x is 0 for finite x and nan for inf and nan
   }
+  if (bad && sd.nonfinite) *sd.nonfinite = 1;   // every writer stores the same value
 }
 
 // out_k[c] = sum_p partial[p][k][c] for the columns of worker w: threads are dealt to (column, slice of the partial
 // rows), slices are added in a fixed order through LDS
-__device__ __forceinline__ void reduce_side_worker(const ReduceJob& job, int w, int nworkers, char* lds) {
+__device__ __forceinline__ void reduce_side_worker(const ReduceJob& job, int w, int nworkers, char* lds, int* nonfinite) {
   const int chunk = (job.width_out + nworkers - 1) / nworkers;
   const int c0 = w * chunk;
   const int nc = job.width_out - c0 < chunk ? job.width_out - c0 : chunk;
@@ -330,7 +333,10 @@ __device__ __forceinline__ void reduce_side_worker(const ReduceJob& job, int w, 
     int cc = c % job.ncols;
     if (job.perm_nvec > 0) cc = (cc % job.perm_nvec) * 8 + cc / job.perm_nvec;   // partial rows stored element-major
     float* o = k == 0 ? job.o0 : (k == 1 ? job.o1 : job.o2);
-    if (o) o[cc] = sum;
+    if (o) {
+      o[cc] = sum;
+      if (nonfinite && !(sum - sum == 0.f)) *nonfinite = 1;
+    }
   }
 }
 
@@ -352,9 +358,9 @@ __global__ __launch_bounds__(64 * (WGM * WGN + NP)) void gemm_bf16_spec_kernel(G
     const int w = (int)blockIdx.x - tile_blocks, nworkers = (int)gridDim.x - tile_blocks;
     colsum_side_worker(side, w, nworkers, lds);
     // static indices: a run-time index would copy the descriptors to scratch memory
-    if (side.nred > 0) reduce_side_worker(side.red[0], w, nworkers, lds);
-    if (side.nred > 1) reduce_side_worker(side.red[1], w, nworkers, lds);
-    if (side.nred > 2) reduce_side_worker(side.red[2], w, nworkers, lds);
+    if (side.nred > 0) reduce_side_worker(side.red[0], w, nworkers, lds, side.nonfinite);
+    if (side.nred > 1) reduce_side_worker(side.red[1], w, nworkers, lds, side.nonfinite);
+    if (side.nred > 2) reduce_side_worker(side.red[2], w, nworkers, lds, side.nonfinite);
     return;
   }
   const int ntile = grp.tile_start[grp.count];
@@ -450,6 +456,18 @@ __global__ __launch_bounds__(64 * (WGM * WGN + NP)) void gemm_bf16_spec_kernel(G
 
   TC* __restrict__ C = (TC*)g.c;
   bf16_t* __restrict__ AUX = (bf16_t*)g.aux;
+  if (side.nonfinite) {
+    // non-finite test of the weight gradients while they are still in registers (rows and columns past the edge of a
+    // ragged tile repeat operand rows that also feed real outputs, so they raise the flag only when those do)
+    bool bad = false;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) bad |= !(acc[i][j][r] - acc[i][j][r] == 0.f);
+    if (bad) *side.nonfinite = 1;   // every writer stores the same value
+  }
   // register r of lane l holds output row (l & 31), column 8*(r/4) + 4*(l/32) + r%4 of its 32x32 block
   if constexpr (sizeof(TC) == 4) {
     // every consumer has passed the last barrier, so the stage after the last one is read by nobody and no load

@@ -2,6 +2,8 @@
 // (optimizer inside the training step with in-place parameter update, paper
 // Section 3; the AMP cast fused into its producer, Section 3.1.2), the loss
 // seed of the benchmark workload, and the dropout-mask test hook.
+#include <cmath>
+
 #include "common.hpp"
 
 namespace raf {
@@ -27,6 +29,7 @@ struct AdamTable {
 
 struct AdamHyper {
   float lr_over_bc1, inv_bc2, beta1, beta2, one_minus_beta1, one_minus_beta2, eps, weight_decay, inv_scale;
+  float lr, ln_beta1, ln_beta2;   // dynamic entry point only: the step count is read on the device
 };
 
 __device__ __forceinline__ void adam_update(float& w, float g, float& m, float& v, const AdamHyper& h) {
@@ -42,8 +45,11 @@ __global__ __launch_bounds__(256) void adam_kernel(AdamTable tab, AdamHyper h, c
   if (dyn) {
     if (dyn->found_inf) return;
     h.inv_scale = dyn->inv_scale;
-    h.lr_over_bc1 = dyn->lr_over_bc1;
-    h.inv_bc2 = dyn->inv_bc2;
+    // bias corrections 1 - beta^t of step t + 1 as -expm1(t ln beta): accurate to a few float ulps also where
+    // beta^t is close to 1, and cheap enough to be formed by every thread instead of by a launch of its own
+    const float tf = (float)(dyn->t + 1);
+    h.lr_over_bc1 = h.lr / -expm1f(tf * h.ln_beta1);
+    h.inv_bc2 = 1.0f / -expm1f(tf * h.ln_beta2);
   }
   int ti = 0;
   while (ti + 1 < tab.count && (int)blockIdx.x >= tab.block_start[ti + 1]) ++ti;
@@ -202,7 +208,7 @@ __global__ void scaler_init_kernel(raf_scaler_state* st, float scale) {
 }
 
 // one chunk of one gradient tensor per block (the Adam partition); any non-finite element raises the flag
-__global__ __launch_bounds__(256) void grads_check_kernel(AdamTable tab, raf_scaler_state* st) {
+__global__ __launch_bounds__(256) void grads_check_kernel(AdamTable tab, int* flag) {
   int ti = 0;
   while (ti + 1 < tab.count && (int)blockIdx.x >= tab.block_start[ti + 1]) ++ti;
   const long n = tab.n[ti];
@@ -220,17 +226,7 @@ __global__ __launch_bounds__(256) void grads_check_kernel(AdamTable tab, raf_sca
       for (long j = i; j < n && j < i + 4; ++j) bad |= !(G[j] - G[j] == 0.f);
     }
   }
-  if (__any(bad) && (threadIdx.x & 63) == 0) st->found_inf = 1;   // every writer stores the same value
-}
-
-// Adam's step-dependent constants for step t + 1, formed in double like the host does for the static entry point
-__global__ void adam_prepare_kernel(raf_scaler_state* st, double lr, double beta1, double beta2) {
-  if (st->found_inf) return;
-  const double t = (double)(st->t + 1);
-  const double bc1 = 1.0 - pow(beta1, t);
-  const double bc2 = 1.0 - pow(beta2, t);
-  st->lr_over_bc1 = (float)(lr / bc1);
-  st->inv_bc2 = (float)(1.0 / bc2);
+  if (__any(bad) && (threadIdx.x & 63) == 0) *flag = 1;   // every writer stores the same value
 }
 
 __global__ void scaler_update_kernel(raf_scaler_state* st, float growth, float backoff, int interval) {
@@ -265,6 +261,23 @@ __global__ __launch_bounds__(256) void dropout_mask_kernel(uint8_t* __restrict__
     for (int e = 0; e < 8; ++e) mult[e] = 1.f;
   }
   for (int e = 0; e < 8 && i8 + e < n; ++e) out[i8 + e] = mult[e] != 0.f ? 1 : 0;
+}
+
+raf_status launch_nonfinite_check(const float* const* ptrs, const long* n, int count, int* flag, hipStream_t st) {
+  if (!ptrs || !n || !flag || count <= 0 || count > ADAM_MAX_TENSORS) return RAF_EINVAL;
+  AdamTable tab{};
+  long blocks = 0;
+  for (int i = 0; i < count; ++i) {
+    if (!ptrs[i] || n[i] <= 0 || !aligned16(ptrs[i])) return RAF_EINVAL;
+    const int k = tab.count++;
+    tab.grad[k] = ptrs[i];
+    tab.n[k] = n[i];
+    tab.block_start[k] = (int)blocks;
+    blocks += (n[i] + ADAM_CHUNK - 1) / ADAM_CHUNK;
+  }
+  tab.block_start[tab.count] = (int)blocks;
+  hipLaunchKernelGGL(grads_check_kernel, dim3((unsigned)blocks), dim3(256), 0, st, tab, flag);
+  return check_launch();
 }
 
 }  // namespace raf
@@ -365,7 +378,7 @@ extern "C" raf_status raf_grads_check(const raf_adam_tensor* list, int32_t count
   if (!state || !aligned16(state)) return RAF_EINVAL;
   hipStream_t st = (hipStream_t)hip_stream;
   return for_each_adam_table(list, count, [&](const AdamTable& tab, unsigned blocks) {
-    hipLaunchKernelGGL(grads_check_kernel, dim3(blocks), dim3(256), 0, st, tab, state);
+    hipLaunchKernelGGL(grads_check_kernel, dim3(blocks), dim3(256), 0, st, tab, &state->found_inf);
   });
 }
 
@@ -375,10 +388,11 @@ extern "C" raf_status raf_adam_step_scaled(const raf_adam_tensor* list, int32_t 
   RAF_TRY(check_adam_list(list, count));
   if (!state || !aligned16(state)) return RAF_EINVAL;
   if (!(beta1 >= 0.0 && beta1 < 1.0) || !(beta2 >= 0.0 && beta2 < 1.0)) return RAF_EINVAL;
-  const AdamHyper h = adam_constants(beta1, beta2, eps, weight_decay);
+  AdamHyper h = adam_constants(beta1, beta2, eps, weight_decay);
+  h.lr = (float)lr;
+  h.ln_beta1 = (float)log(beta1);   // -inf for beta = 0: the correction is then 1
+  h.ln_beta2 = (float)log(beta2);
   hipStream_t st = (hipStream_t)hip_stream;
-  hipLaunchKernelGGL(adam_prepare_kernel, dim3(1), dim3(1), 0, st, state, lr, beta1, beta2);
-  RAF_TRY(check_launch());
   return for_each_adam_table(list, count, [&](const AdamTable& tab, unsigned blocks) {
     hipLaunchKernelGGL(adam_kernel, dim3(blocks), dim3(256), 0, st, tab, h, (const raf_scaler_state*)state);
   });

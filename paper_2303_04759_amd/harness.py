@@ -78,19 +78,26 @@ class DeviceLayer:
         raf_adam_step(self.adam_list, self.adam_count, a["lr"], a["beta1"], a["beta2"], a["eps"],
                       a.get("weight_decay", 0.0), t, 1.0 / self.cfg["loss_scale"], stream)
 
-    def train_step_dynamic(self, step, state, scaler, stream=None, fused_loss=True):
+    def train_step_dynamic(self, step, state, scaler, stream=None, fused_loss=True, epilogue_check=True):
         """The same pass under the dynamic loss scaler: every decision (scale, skip, Adam's step count) is taken on
         the device from `state` (a device byte buffer initialised with raf_scaler_init).  `step` only numbers the
-        dropout masks."""
+        dropout masks.  epilogue_check: the backward call raises state.found_inf itself (raf_layer_tensors.nonfinite)
+        instead of a raf_grads_check pass over the gradients afterwards."""
+        from . import ScalerState
         a = self.adam
+        g_struct = self.g_struct
+        if epilogue_check:
+            g_struct = make_tensors(dict(self.grads, nonfinite=state.data_ptr() + ScalerState.found_inf.offset))
         if fused_loss:
             self.fwd_loss(step, stream, state)
         else:
             self.fwd(step, stream)
             raf_loss_seed_scaled(self.cfg["precision"], self.y, self.G, self.y.numel(), state, self.loss, self.dy,
                                  self.partial, stream)
-        self.bwd(step, stream)
-        raf_grads_check(self.adam_list, self.adam_count, state, stream)
+        raf_layer_bwd(self.desc, self.w_struct, self.x, self.dy, self.seq_lens, self.saved, self.dx, g_struct,
+                      self.scratch, step, stream)
+        if not epilogue_check:
+            raf_grads_check(self.adam_list, self.adam_count, state, stream)
         raf_adam_step_scaled(self.adam_list, self.adam_count, a["lr"], a["beta1"], a["beta2"], a["eps"],
                              a.get("weight_decay", 0.0), state, stream)
         raf_scaler_update(state, scaler["growth_factor"], scaler["backoff_factor"], scaler["growth_interval"], stream)

@@ -36,7 +36,7 @@ def test_every_declared_symbol_is_exported(lib):
 def test_struct_layout_matches_header():
     assert C.sizeof(raf.LayerDesc) == 64
     assert raf.LayerDesc.dropout_p.offset == 40 and raf.LayerDesc.seed.offset == 48
-    assert C.sizeof(raf.LayerTensors) == 128 and raf.LayerTensors.wt_qkv.offset == 96
+    assert C.sizeof(raf.LayerTensors) == 136 and raf.LayerTensors.wt_qkv.offset == 96 and raf.LayerTensors.nonfinite.offset == 128
     assert C.sizeof(raf.AdamTensor) == 64 and raf.AdamTensor.lowp_t.offset == 48 and raf.AdamTensor.cols.offset == 60
     assert C.sizeof(raf.ScalerState) == 32 and raf.ScalerState.t.offset == 16 and raf.ScalerState.inv_bc2.offset == 28
 

@@ -65,6 +65,36 @@ def test_dynamic_scaler_sequence(precision, poison):
     assert st["t"] == 5 and st["scale"] == 256.0
 
 
+@pytest.mark.parametrize("epilogue_check", [True, False])
+def test_non_finite_test_in_the_backward_epilogues_at_full_size(epilogue_check):
+    """BERT-base shape: weight gradients and all reductions leave raf_layer_bwd in one launch, which also raises
+    found_inf; the decisions must be those of the separate pass over the gradients (raf_grads_check)."""
+    announce("dynamic scaler, non-finite test in the epilogues", epilogue_check)
+    cfg = CONFIGS["bert_base"]
+    inp = make_layer_inputs(cfg, seed=7)
+    lay = DeviceLayer(cfg, inp, ADAM)
+    state = torch.zeros(C.sizeof(raf.ScalerState), dtype=torch.uint8, device="cuda")
+    raf.raf_scaler_init(state, 1024.0)
+    G_good = lay.G.clone()
+    expect = SC.scaler_new(1024.0)
+    for step, bad in enumerate(("", "", "inf", "", "nan", ""), start=1):
+        lay.G.copy_(G_good)
+        if bad in ("inf", "nan"):
+            lay.G.view(-1)[step * 1000 + 3] = float(bad)
+        w0 = {k: lay.master[k].clone() for k in PARAM_NAMES}
+        lay.train_step_dynamic(step, state, SCALER, epilogue_check=epilogue_check)
+        torch.cuda.synchronize()
+        overflow = not all(bool(torch.isfinite(lay.grads[k]).all()) for k in PARAM_NAMES)
+        if bad in ("inf", "nan"):
+            assert overflow
+        expect = SC.scaler_update(expect, overflow, **SCALER)
+        got = raf.read_scaler_state(state)
+        assert (got["scale"], got["good_steps"], got["t"], got["found_inf"]) == (
+            expect["scale"], expect["good_steps"], expect["t"], 0), (step, bad, got, expect)
+        changed = any(not torch.equal(w0[k], lay.master[k]) for k in PARAM_NAMES)
+        assert changed == (not overflow), (step, bad)
+
+
 def test_dynamic_step_replays_in_a_graph():
     """The whole dynamically scaled step is captured once; replays take their decisions from the device state."""
     announce("dynamic scaler graph")
