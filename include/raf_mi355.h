@@ -235,6 +235,25 @@ raf_status raf_adam_step_scaled(const raf_adam_tensor *list, int32_t count, doub
 raf_status raf_scaler_update(raf_scaler_state *state, float growth_factor, float backoff_factor,
                              int32_t growth_interval, void *hip_stream);
 
+/* The same update for lists of any length in ONE launch (the optimizer of a whole model
+ * as one operator of the step, Section 3): raf_adam_step holds its tensor table in
+ * the kernel arguments and splits lists of more than 48 tensors into several launches;
+ * here the table lives in device memory.
+ *   raf_adam_table_bytes(list, count): size of the caller's table buffer for this list
+ *     (0 for a malformed list).
+ *   raf_adam_table_fill: writes the table for `list` with small kernels on the stream
+ *     (no copies, no allocation); once per list, again whenever a pointer changes.
+ *     table [dev]: >= raf_adam_table_bytes(list, count) bytes, 256-byte aligned.
+ *   raf_adam_step_table: one launch over all tensors.  list [host] must be the list the
+ *     table was filled from (the launch geometry is recomputed from it).  state == NULL:
+ *     t and inv_loss_scale as in raf_adam_step; otherwise both are read on the device
+ *     as in raf_adam_step_scaled and the two arguments are ignored. */
+size_t raf_adam_table_bytes(const raf_adam_tensor *list, int32_t count);
+raf_status raf_adam_table_fill(const raf_adam_tensor *list, int32_t count, void *table, void *hip_stream);
+raf_status raf_adam_step_table(const raf_adam_tensor *list, int32_t count, const void *table, double lr,
+                               double beta1, double beta2, double eps, double weight_decay, int64_t t,
+                               double inv_loss_scale, const raf_scaler_state *state, void *hip_stream);
+
 /* Test hook: the keep-mask of one dropout site as bytes (1 = kept).
  *   mask_out [dev] uint8[n]; element order is the site's flat index. */
 raf_status raf_debug_dropout_mask(const raf_layer_desc *desc, int32_t site, uint64_t step, uint8_t *mask_out,

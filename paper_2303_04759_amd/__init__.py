@@ -101,6 +101,10 @@ _SIGNATURES = {
                                      C.c_uint64, C.c_void_p]),
     "raf_loss_seed": (C.c_int, [C.c_int32, C.c_void_p, C.c_void_p, C.c_int64, C.c_float, C.c_void_p, C.c_void_p,
                                 C.c_void_p, C.c_void_p]),
+    "raf_adam_table_bytes": (C.c_size_t, [C.POINTER(AdamTensor), C.c_int32]),
+    "raf_adam_table_fill": (C.c_int, [C.POINTER(AdamTensor), C.c_int32, C.c_void_p, C.c_void_p]),
+    "raf_adam_step_table": (C.c_int, [C.POINTER(AdamTensor), C.c_int32, C.c_void_p, C.c_double, C.c_double, C.c_double,
+                                      C.c_double, C.c_double, C.c_int64, C.c_double, C.c_void_p, C.c_void_p]),
     "raf_adam_step": (C.c_int, [C.POINTER(AdamTensor), C.c_int32, C.c_double, C.c_double, C.c_double, C.c_double,
                                 C.c_double, C.c_int64, C.c_double, C.c_void_p]),
     "raf_scaler_init": (C.c_int, [C.c_void_p, C.c_float, C.c_void_p]),
@@ -307,6 +311,21 @@ def raf_adam_step(adam_list, count, lr, beta1, beta2, eps, weight_decay, t, inv_
     _check(load_library().raf_adam_step(adam_list, int(count), float(lr), float(beta1), float(beta2), float(eps),
                                         float(weight_decay), int(t), float(inv_loss_scale), _stream(stream)),
            "raf_adam_step")
+
+
+def raf_adam_table_bytes(adam_list, count):
+    return int(load_library().raf_adam_table_bytes(adam_list, int(count)))
+
+
+def raf_adam_table_fill(adam_list, count, table, stream=None):
+    _check(load_library().raf_adam_table_fill(adam_list, int(count), _ptr(table), _stream(stream)), "raf_adam_table_fill")
+
+
+def raf_adam_step_table(adam_list, count, table, lr, beta1, beta2, eps, weight_decay, t, inv_loss_scale, state=None,
+                        stream=None):
+    _check(load_library().raf_adam_step_table(adam_list, int(count), _ptr(table), float(lr), float(beta1), float(beta2),
+                                              float(eps), float(weight_decay), int(t), float(inv_loss_scale),
+                                              _ptr(state), _stream(stream)), "raf_adam_step_table")
 
 
 def raf_debug_dropout_mask(desc, site, step, mask_out, n, stream=None):

@@ -39,27 +39,11 @@ __device__ __forceinline__ void adam_update(float& w, float g, float& m, float& 
   w = w - h.lr_over_bc1 * m / (sqrtf(v * h.inv_bc2) + h.eps);
 }
 
-// dyn != nullptr: step count and loss scale come from the device-resident scaler state, and the whole launch is a
-// no-op when the step's gradients held a non-finite value
-__global__ __launch_bounds__(256) void adam_kernel(AdamTable tab, AdamHyper h, const raf_scaler_state* __restrict__ dyn) {
-  if (dyn) {
-    if (dyn->found_inf) return;
-    h.inv_scale = dyn->inv_scale;
-    // bias corrections 1 - beta^t of step t + 1 as -expm1(t ln beta): accurate to a few float ulps also where
-    // beta^t is close to 1, and cheap enough to be formed by every thread instead of by a launch of its own
-    const float tf = (float)(dyn->t + 1);
-    h.lr_over_bc1 = h.lr / -expm1f(tf * h.ln_beta1);
-    h.inv_bc2 = 1.0f / -expm1f(tf * h.ln_beta2);
-  }
-  int ti = 0;
-  while (ti + 1 < tab.count && (int)blockIdx.x >= tab.block_start[ti + 1]) ++ti;
-  const long n = tab.n[ti];
-  float* __restrict__ W = tab.master[ti];
-  const float* __restrict__ G = tab.grad[ti];
-  float* __restrict__ Mo = tab.m[ti];
-  float* __restrict__ Vo = tab.v[ti];
-  bf16_t* __restrict__ L = tab.lowp[ti];
-  bf16_t* __restrict__ LT = tab.lowp_t[ti];
+// One block's share of one tensor: chunk `block` of the flat element range, or tile `block` of a matrix that keeps a
+// transposed bf16 copy.
+__device__ __forceinline__ void adam_block(float* __restrict__ W, const float* __restrict__ G, float* __restrict__ Mo,
+                                           float* __restrict__ Vo, bf16_t* __restrict__ L, bf16_t* __restrict__ LT,
+                                           long n, int rows, int cols, int block, const AdamHyper& h) {
   if (LT) {
     // A matrix that also keeps a transposed bf16 copy: one tile per block.  Each thread updates pieces of 4 consecutive
     // elements, leaves the rounded weights in an LDS tile stored transposed, and the block then writes the tile's
@@ -67,9 +51,8 @@ __global__ __launch_bounds__(256) void adam_kernel(AdamTable tab, AdamHyper h, c
     __shared__ uint16_t tile[ADAM_TILE_C][ADAM_TILE_R + 2];   // [column][row] of the tile
     constexpr int LANES_C = ADAM_TILE_C / 4;                   // threads along a row piece
     constexpr int ROWS_PASS = 256 / LANES_C;                   // rows per pass of the workgroup
-    const int rows = tab.rows[ti], cols = tab.cols[ti];
     const int tiles_c = (cols + ADAM_TILE_C - 1) / ADAM_TILE_C;
-    const int tb = (int)blockIdx.x - tab.block_start[ti];
+    const int tb = block;
     const int r0 = (tb / tiles_c) * ADAM_TILE_R, c0 = (tb % tiles_c) * ADAM_TILE_C;
     const int cl = (threadIdx.x % LANES_C) * 4;
 #pragma unroll
@@ -116,7 +99,7 @@ __global__ __launch_bounds__(256) void adam_kernel(AdamTable tab, AdamHyper h, c
     }
     return;
   }
-  const long base = (long)(blockIdx.x - tab.block_start[ti]) * ADAM_CHUNK;
+  const long base = (long)block * ADAM_CHUNK;
 #pragma unroll
   for (int it = 0; it < 4; ++it) {
     const long i = base + ((long)it * 256 + threadIdx.x) * 4;
@@ -149,6 +132,61 @@ __global__ __launch_bounds__(256) void adam_kernel(AdamTable tab, AdamHyper h, c
       }
     }
   }
+}
+
+// the dynamic entry points: step count and loss scale come from the device-resident scaler state; false: the step's
+// gradients held a non-finite value and the whole launch is a no-op
+__device__ __forceinline__ bool adam_dynamic(AdamHyper& h, const raf_scaler_state* __restrict__ dyn) {
+  if (dyn->found_inf) return false;
+  h.inv_scale = dyn->inv_scale;
+  // bias corrections 1 - beta^t of step t + 1 as -expm1(t ln beta): accurate to a few float ulps also where
+  // beta^t is close to 1, and cheap enough to be formed by every thread instead of by a launch of its own
+  const float tf = (float)(dyn->t + 1);
+  h.lr_over_bc1 = h.lr / -expm1f(tf * h.ln_beta1);
+  h.inv_bc2 = 1.0f / -expm1f(tf * h.ln_beta2);
+  return true;
+}
+
+// tensor table in the kernel arguments (at most ADAM_MAX_TENSORS tensors)
+__global__ __launch_bounds__(256) void adam_kernel(AdamTable tab, AdamHyper h, const raf_scaler_state* __restrict__ dyn) {
+  if (dyn && !adam_dynamic(h, dyn)) return;
+  int ti = 0;
+  while (ti + 1 < tab.count && (int)blockIdx.x >= tab.block_start[ti + 1]) ++ti;
+  adam_block(tab.master[ti], tab.grad[ti], tab.m[ti], tab.v[ti], tab.lowp[ti], tab.lowp_t[ti], tab.n[ti], tab.rows[ti],
+             tab.cols[ti], (int)blockIdx.x - tab.block_start[ti], h);
+}
+
+// Tensor table in device memory, for lists of any length in ONE launch: `entries` is a device copy of the caller's
+// list without its empty tensors, block_start[i] the first block of entry i, block_entry[b] the entry block b works on
+// (one dependent read instead of a search).
+__global__ __launch_bounds__(256) void adam_table_kernel(const raf_adam_tensor* __restrict__ entries,
+                                                         const int* __restrict__ block_start,
+                                                         const int* __restrict__ block_entry, AdamHyper h,
+                                                         const raf_scaler_state* __restrict__ dyn) {
+  if (dyn && !adam_dynamic(h, dyn)) return;
+  const int ti = block_entry[blockIdx.x];
+  const raf_adam_tensor e = entries[ti];
+  adam_block(e.master, e.grad, e.m, e.v, (bf16_t*)e.lowp, (bf16_t*)e.lowp_t, (long)e.n, e.rows, e.cols,
+             (int)blockIdx.x - block_start[ti], h);
+}
+
+// writes entries [first, first + n) of the device table from kernel arguments: workgroup i takes entry first + i and
+// the block numbers that belong to it
+constexpr int ADAM_FILL = 32;
+struct AdamFillChunk {
+  raf_adam_tensor e[ADAM_FILL];
+  int start[ADAM_FILL + 1];
+};
+__global__ __launch_bounds__(256) void adam_table_fill_kernel(AdamFillChunk c, raf_adam_tensor* __restrict__ entries,
+                                                              int* __restrict__ block_start,
+                                                              int* __restrict__ block_entry, int first) {
+  const int i = blockIdx.x;
+  if (threadIdx.x == 0) {
+    entries[first + i] = c.e[i];
+    block_start[first + i] = c.start[i];
+    block_start[first + i + 1] = c.start[i + 1];   // the next entry's workgroup writes the same value
+  }
+  for (int b = c.start[i] + (int)threadIdx.x; b < c.start[i + 1]; b += 256) block_entry[b] = first + i;
 }
 
 // ------------------------------------------------------------- loss seed --
@@ -364,6 +402,96 @@ extern "C" raf_status raf_adam_step(const raf_adam_tensor* list, int32_t count, 
   return for_each_adam_table(list, count, [&](const AdamTable& tab, unsigned blocks) {
     hipLaunchKernelGGL(adam_kernel, dim3(blocks), dim3(256), 0, st, tab, h, (const raf_scaler_state*)nullptr);
   });
+}
+
+// ---- tensor table in device memory: any number of tensors in one launch
+static long adam_blocks_of(const raf_adam_tensor& a) {
+  return a.lowp_t ? (long)((a.rows + ADAM_TILE_R - 1) / ADAM_TILE_R) * ((a.cols + ADAM_TILE_C - 1) / ADAM_TILE_C)
+                  : (a.n + ADAM_CHUNK - 1) / ADAM_CHUNK;
+}
+static size_t pad256(size_t n) { return (n + 255) & ~(size_t)255; }
+// entries | block_start[live + 1] | block_entry[blocks]; false: too many blocks for one launch
+static bool adam_table_layout(const raf_adam_tensor* list, int32_t count, int* live, long* blocks, size_t* off_start,
+                              size_t* off_entry, size_t* bytes) {
+  *live = 0;
+  *blocks = 0;
+  for (int i = 0; i < count; ++i) {
+    if (list[i].n == 0) continue;   // empty tensors take no entry
+    ++*live;
+    *blocks += adam_blocks_of(list[i]);
+    if (*blocks > 0x7fffffff) return false;
+  }
+  *off_start = pad256((size_t)*live * sizeof(raf_adam_tensor));
+  *off_entry = *off_start + pad256(((size_t)*live + 1) * sizeof(int));
+  *bytes = *off_entry + pad256((size_t)*blocks * sizeof(int));
+  return true;
+}
+
+extern "C" size_t raf_adam_table_bytes(const raf_adam_tensor* list, int32_t count) {
+  if (check_adam_list(list, count) != RAF_OK) return 0;
+  int live; long blocks; size_t o1, o2, bytes;
+  if (!adam_table_layout(list, count, &live, &blocks, &o1, &o2, &bytes)) return 0;
+  return bytes;
+}
+
+extern "C" raf_status raf_adam_table_fill(const raf_adam_tensor* list, int32_t count, void* table, void* hip_stream) {
+  RAF_TRY(check_adam_list(list, count));
+  int live; long total; size_t o1, o2, bytes;
+  if (!adam_table_layout(list, count, &live, &total, &o1, &o2, &bytes)) return RAF_ENOTSUP;
+  if (live == 0) return RAF_OK;
+  if (!table || ((uintptr_t)table & 255u)) return RAF_EINVAL;
+  raf_adam_tensor* entries = (raf_adam_tensor*)table;
+  int* block_start = (int*)((char*)table + o1);
+  int* block_entry = (int*)((char*)table + o2);
+  hipStream_t st = (hipStream_t)hip_stream;
+  AdamFillChunk c;
+  int filled = 0, first = 0;
+  long blocks = 0;
+  auto flush = [&]() -> raf_status {
+    if (filled == 0) return RAF_OK;
+    c.start[filled] = (int)blocks;
+    hipLaunchKernelGGL(adam_table_fill_kernel, dim3(filled), dim3(256), 0, st, c, entries, block_start, block_entry, first);
+    first += filled;
+    filled = 0;
+    return check_launch();
+  };
+  for (int i = 0; i < count; ++i) {
+    if (list[i].n == 0) continue;
+    c.e[filled] = list[i];
+    c.start[filled] = (int)blocks;
+    blocks += adam_blocks_of(list[i]);
+    if (++filled == ADAM_FILL) RAF_TRY(flush());
+  }
+  return flush();
+}
+
+extern "C" raf_status raf_adam_step_table(const raf_adam_tensor* list, int32_t count, const void* table, double lr,
+                                          double beta1, double beta2, double eps, double weight_decay, int64_t t,
+                                          double inv_loss_scale, const raf_scaler_state* state, void* hip_stream) {
+  RAF_TRY(check_adam_list(list, count));
+  if (!(beta1 >= 0.0 && beta1 < 1.0) || !(beta2 >= 0.0 && beta2 < 1.0)) return RAF_EINVAL;
+  if (!state && t < 1) return RAF_EINVAL;
+  if (state && !aligned16(state)) return RAF_EINVAL;
+  // the partition of fill time, recomputed from the list (which must be the one the table was filled from)
+  int live; long blocks; size_t o1, o2, bytes;
+  if (!adam_table_layout(list, count, &live, &blocks, &o1, &o2, &bytes)) return RAF_ENOTSUP;
+  if (live == 0) return RAF_OK;
+  if (!table || ((uintptr_t)table & 255u)) return RAF_EINVAL;
+  AdamHyper h = adam_constants(beta1, beta2, eps, weight_decay);
+  if (state) {
+    h.lr = (float)lr;
+    h.ln_beta1 = (float)log(beta1);
+    h.ln_beta2 = (float)log(beta2);
+  } else {
+    const double bc1 = 1.0 - pow(beta1, (double)t), bc2 = 1.0 - pow(beta2, (double)t);
+    h.lr_over_bc1 = (float)(lr / bc1);
+    h.inv_bc2 = (float)(1.0 / bc2);
+    h.inv_scale = (float)inv_loss_scale;
+  }
+  hipLaunchKernelGGL(adam_table_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)hip_stream,
+                     (const raf_adam_tensor*)table, (const int*)((const char*)table + o1),
+                     (const int*)((const char*)table + o2), h, state);
+  return check_launch();
 }
 
 extern "C" raf_status raf_scaler_init(raf_scaler_state* state, float init_scale, void* hip_stream) {

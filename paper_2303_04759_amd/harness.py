@@ -182,6 +182,11 @@ class DeviceModel:
         keys = list(self.master)
         self.adam_list, self.adam_count = make_adam_list(
             (self.master[k], self.grads[k], self.m[k], self.v[k], self.lowp[k], self.lowp_t[k]) for k in keys)
+        # the optimizer's tensor table in device memory: all tensors of the model in one launch
+        from . import raf_adam_table_bytes, raf_adam_table_fill
+        self.adam_table = torch.empty(raf_adam_table_bytes(self.adam_list, self.adam_count), dtype=torch.uint8, device=dev)
+        raf_adam_table_fill(self.adam_list, self.adam_count, self.adam_table)
+        torch.cuda.synchronize()
 
     def _add_param(self, key, master, has_lowp):
         self.master[key] = master
@@ -216,10 +221,15 @@ class DeviceModel:
         raf_embed_bwd(self.edesc, self.ids, self.dx[cur], self.esaved, self.master["emb_ln_g"], self.grads["word"],
                       self.grads["pos"], self.grads["emb_ln_g"], self.grads["emb_ln_b"], self.scratch, step, stream)
 
-    def adam_step(self, t, stream=None):
+    def adam_step(self, t, stream=None, one_launch=True):
+        from . import raf_adam_step_table
         a = self.adam
-        raf_adam_step(self.adam_list, self.adam_count, a["lr"], a["beta1"], a["beta2"], a["eps"],
-                      a.get("weight_decay", 0.0), t, 1.0 / self.cfg["loss_scale"], stream)
+        if one_launch:
+            raf_adam_step_table(self.adam_list, self.adam_count, self.adam_table, a["lr"], a["beta1"], a["beta2"],
+                                a["eps"], a.get("weight_decay", 0.0), t, 1.0 / self.cfg["loss_scale"], None, stream)
+        else:
+            raf_adam_step(self.adam_list, self.adam_count, a["lr"], a["beta1"], a["beta2"], a["eps"],
+                          a.get("weight_decay", 0.0), t, 1.0 / self.cfg["loss_scale"], stream)
 
     def train_step(self, t, stream=None):
         self.forward(t, stream)

@@ -339,6 +339,52 @@ def test_adam_multi_tensor_matches_oracle():
                 assert torch.equal(Ld[i], Wd[i].to(torch.bfloat16))
 
 
+def test_adam_device_table_is_one_launch_with_the_same_results():
+    """raf_adam_step_table (tensor table in device memory, any number of tensors in one launch) against raf_adam_step
+    (table in the kernel arguments, 48 tensors per launch) on 150 tensors of odd sizes, some empty, some with a
+    transposed copy: bit for bit, static and with the step count read from a scaler state."""
+    import ctypes as C
+    announce("adam device table")
+    rng = np.random.default_rng(9)
+    sizes = [(5,), (0,), (4096,), (72, 200), (33,), (4097,), (320, 1056), (0,), (768, 64)] + [(17 + 3 * i,) for i in range(141)]
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    def build():
+        ent = []
+        r = np.random.default_rng(10)
+        for sh in sizes:
+            w, g = r.standard_normal(sh).astype(np.float32), (8 * r.standard_normal(sh)).astype(np.float32)
+            m, v = (0.1 * r.standard_normal(sh)).astype(np.float32), (r.standard_normal(sh) ** 2).astype(np.float32)
+            two = len(sh) == 2
+            ent.append((dev(w), dev(g), dev(m), dev(v), torch.zeros(*sh, dtype=torch.bfloat16, device="cuda") if two else None,
+                        torch.zeros(sh[1], sh[0], dtype=torch.bfloat16, device="cuda") if two else None))
+        return ent
+    for dynamic in (False, True):
+        a, b = build(), build()
+        la, ca = raf.make_adam_list(a)
+        lb, cb = raf.make_adam_list(b)
+        table = torch.zeros(raf.raf_adam_table_bytes(lb, cb), dtype=torch.uint8, device="cuda")
+        raf.raf_adam_table_fill(lb, cb, table)
+        state = None
+        if dynamic:
+            state = torch.zeros(C.sizeof(raf.ScalerState), dtype=torch.uint8, device="cuda")
+            raf.raf_scaler_init(state, 8.0)
+        for t in (1, 2):
+            if dynamic:
+                raf.raf_adam_step_scaled(la, ca, 1e-3, 0.9, 0.999, 1e-8, 0.01, state)
+                raf.raf_adam_step_table(lb, cb, table, 1e-3, 0.9, 0.999, 1e-8, 0.01, 0, 0.0, state)
+                raf.raf_scaler_update(state, 2.0, 0.5, 100)
+            else:
+                raf.raf_adam_step(la, ca, 1e-3, 0.9, 0.999, 1e-8, 0.01, t, 1.0 / 8)
+                raf.raf_adam_step_table(lb, cb, table, 1e-3, 0.9, 0.999, 1e-8, 0.01, t, 1.0 / 8)
+            torch.cuda.synchronize()
+            for i, (ea, eb) in enumerate(zip(a, b)):
+                for k in (0, 2, 3, 4, 5):
+                    if ea[k] is not None:
+                        assert torch.equal(ea[k], eb[k]), (dynamic, t, i, k)
+            assert not torch.equal(a[2][0], torch.from_numpy(np.zeros(4096, np.float32)).cuda())
+
+
 def test_adam_transposed_copy_is_the_exact_transpose_and_changes_nothing_else():
     """Tensors with a transposed bf16 copy are walked in 64 x 64 tiles: same update as the flat walk, bit for bit, the
     copy is the transpose of the bf16 weights, and elements outside ragged edge tiles are left alone."""
