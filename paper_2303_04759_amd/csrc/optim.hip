@@ -214,23 +214,24 @@ __global__ __launch_bounds__(256) void loss_seed_kernel(const T* __restrict__ y,
   if (threadIdx.x == 0) partial[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
-__global__ __launch_bounds__(256) void loss_final_kernel(const float* __restrict__ partial, int nparts,
-                                                         float* __restrict__ loss_out) {
-  __shared__ float red[256];
-  float acc = 0.f;
-  for (int i = threadIdx.x; i < nparts; i += 256) acc += partial[i];
-  red[threadIdx.x] = acc;
-  __syncthreads();
-  for (int s = 128; s > 0; s >>= 1) {
-    if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
-    __syncthreads();
+// one wavefront: each lane adds its share of the partial sums in ascending order, the 64 lane sums are then folded by
+// xor shuffles; no LDS, no barrier, a fixed order
+__global__ __launch_bounds__(64) void loss_final_kernel(const float* __restrict__ partial, int nparts,
+                                                        float* __restrict__ loss_out) {
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  int i = threadIdx.x;
+  for (; i + 192 < nparts; i += 256) {   // four loads in flight
+    const float a = partial[i], b = partial[i + 64], c = partial[i + 128], d = partial[i + 192];
+    acc[0] += a; acc[1] += b; acc[2] += c; acc[3] += d;
   }
-  if (threadIdx.x == 0) *loss_out = red[0];
+  for (; i < nparts; i += 64) acc[0] += partial[i];
+  const float sum = group_sum<64>((acc[0] + acc[1]) + (acc[2] + acc[3]));
+  if (threadIdx.x == 0) *loss_out = sum;
 }
 
 raf_status launch_sum_partials(const float* partial, int nparts, float* out, hipStream_t st) {
   if (!partial || !out || nparts <= 0) return RAF_EINVAL;
-  hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(256), 0, st, partial, nparts, out);
+  hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(64), 0, st, partial, nparts, out);
   return check_launch();
 }
 
@@ -551,7 +552,7 @@ static raf_status loss_seed_impl(int32_t precision, const void* y, const void* G
                        (long)n, loss_scale, scale_ptr, (bf16_t*)dy, partial);
   raf_status rc = check_launch();
   if (rc != RAF_OK) return rc;
-  hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(256), 0, st, partial, (int)nb, loss_out);
+  hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(64), 0, st, partial, (int)nb, loss_out);
   return check_launch();
 }
 
