@@ -446,6 +446,7 @@ raf_status launch_gemm_group_wgrad(int precision, const GemmArgs* gs, int count,
     tiles += ((gs[i].M + 127) / 128) * grp.tiles_n[i];
   }
   for (int i = count; i <= GEMM_GROUP_MAX; ++i) grp.tile_start[i] = tiles;
+  for (int i = 0; i < GEMM_GROUP_MAX; ++i) grp.tiles_m_first[i] = 0;
   for (int i = count; i < GEMM_GROUP_MAX; ++i) { grp.p[i] = grp.p[0]; grp.tiles_n[i] = 1; }
   dim3 grid(((tiles + 7) / 8) * 8);
   // 8 wavefronts per workgroup measured faster than 4 even with ~1.7 workgroups per CU

@@ -356,6 +356,9 @@ struct GemmGroupDev {
   GemmDev p[GEMM_GROUP_MAX];
   int tile_start[GEMM_GROUP_MAX + 1];
   int tiles_n[GEMM_GROUP_MAX];
+  // > 0: the problem's tiles are numbered along M first (that many row tiles), so that a contiguous share of the tile
+  // list covers whole strips of the side with fewer tiles; 0: along N first
+  int tiles_m_first[GEMM_GROUP_MAX];
   int count;
 };
 
