@@ -146,13 +146,14 @@ def short_kernel_name(name):
     return name
 
 
-def kernel_breakdown(args, cfg, n_params_matrix, n_params_vector, steps=10, warmup=3):
+def kernel_breakdown(args, cfg, n_params_matrix, n_params_vector, steps=10, warmup=3, graph=True):
     """Every kernel of the step with its time INSIDE the step and its roofline fraction.
 
-    The step is run eagerly (one dispatch per kernel) in a child process under `rocprofv3 --kernel-trace`; the
+    The step is run in a child process under `rocprofv3 --kernel-trace`, as replays of the captured HIP graph like the
+    timed region (graph=True; the profiler records every kernel of a replay as one dispatch) or eagerly; the
     per-dispatch begin/end stamps of the last `steps` steps are averaged per launch position, each position is given
     its operator and algorithmic work (launch_work), and positions are summed per kernel instantiation.  Returns
-    (list, None) or (None, reason)."""
+    (dict, None) or (None, reason)."""
     import csv
     import glob
     import shutil
@@ -163,7 +164,7 @@ def kernel_breakdown(args, cfg, n_params_matrix, n_params_vector, steps=10, warm
     out_dir = tempfile.mkdtemp(prefix="raf_bench_trace_", dir="/tmp")
     cmd = ["rocprofv3", "--kernel-trace", "--output-format", "csv", "-d", out_dir, "-o", "trace", "--",
            sys.executable, os.path.abspath(__file__), "--workload", args.workload, "--steps", str(steps), "--warmup",
-           str(warmup), "--no-graph", "--no-cpu", "--trace-child"]
+           str(warmup), "--no-cpu", "--trace-child"] + ([] if graph else ["--no-graph"])
     try:
         r = subprocess.run(cmd, cwd="/tmp", env=dict(os.environ, TMPDIR="/tmp"), stdout=subprocess.PIPE,
                            stderr=subprocess.STDOUT, text=True, timeout=400)
@@ -177,7 +178,8 @@ def kernel_breakdown(args, cfg, n_params_matrix, n_params_vector, steps=10, warm
     rows = [x for x in csv.DictReader(open(files[0])) if "raf" in x["Kernel_Name"]]
     shutil.rmtree(out_dir, ignore_errors=True)
     rows.sort(key=lambda x: int(x["Start_Timestamp"]))
-    total_steps = steps + max(warmup, 1)
+    # the child runs max(warmup, 1) eager steps, then (graph mode) captures one step and replays it 3 + steps times
+    total_steps = steps + max(warmup, 1) + (3 if graph else 0)
     if not rows or len(rows) % total_steps:
         return None, "%d library dispatches do not divide into %d steps" % (len(rows), total_steps)
     n = len(rows) // total_steps
@@ -227,7 +229,8 @@ def kernel_breakdown(args, cfg, n_params_matrix, n_params_vector, steps=10, warm
     summary = {"launches_per_step": n, "sum_of_kernels_us": round(sum(dur_us), 1), "first_start_to_last_end_us": round(span_us, 1),
                "all_gemms_us": round(gemm_us, 1),
                "all_gemms_frac_of_mfma_peak": round(gemm_fl / (gemm_us * 1e-6) / 1e12 / PEAK_BF16_TFLOPS, 4) if gemm_us else None,
-               "source": "rocprofv3 --kernel-trace of %d eager steps in a child process" % steps}
+               "source": "rocprofv3 --kernel-trace of %d %s steps in a child process" % (
+                   steps, "HIP-graph replays of the" if graph else "eager")}
     return {"summary": summary, "per_kernel": out}, None
 
 
