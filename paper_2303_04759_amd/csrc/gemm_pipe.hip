@@ -510,13 +510,15 @@ bool launch_gemm_group_spec(const GemmDev* ds, int count, hipStream_t st, const 
   if (!lds_limit.ensure((const void*)kern, LDS_BYTES)) return false;
   const int tile_blocks = ((tiles + 7) / 8) * 8;
   // side workers only where the tiles leave CUs free (one workgroup per CU: the ring takes most of the LDS), and
-  // enough of them that a worker's columns take less time than a tile
+  // enough of them that a worker's columns take less time than a tile.  With more tiles than CUs the free CUs are
+  // those of the last round: the workers come last in the grid and start when the tiles of that round have theirs.
   ColsumSide sd{};
   int workers = 0;
   if (side && side->count > 0) {
     constexpr int NUM_CUS = 256, THREADS = 64 * (WGM * WGN + NP);
     const int total_vecs = (side->cols[0] + side->cols[1]) / 8;
-    const int free_cus = NUM_CUS - tile_blocks;
+    const int last_round = tile_blocks % NUM_CUS;
+    const int free_cus = last_round ? NUM_CUS - last_round : 0;
     if (free_cus > 0 && total_vecs > 0) {
       const int per = (total_vecs + free_cus - 1) / free_cus;
       // per row of the contraction a worker reads per*16 bytes through registers (about 16 bytes/clock/CU: `per`
