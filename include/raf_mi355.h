@@ -135,7 +135,10 @@ raf_status raf_layer_fwd(const raf_layer_desc *desc, const raf_layer_tensors *w,
                          void *hip_stream);
 
 /* Backward pass: adjoints of the forward operators in reverse order (Section
- * 3.1.1), dropout masks recomputed from the counter, not stored.
+ * 3.1.1), dropout masks recomputed from the counter, not stored (one exception:
+ * with seq > 128 the forward pass leaves the keep decisions of the attention
+ * probabilities in saved, one bit each, because generating them again is what
+ * the two attention adjoint kernels would spend most of their time on).
  *   x, seq_lens, saved, step: exactly what the matching raf_layer_fwd saw/wrote
  *   dy     [dev] gradient w.r.t. y [B*S,H], compute dtype (already loss-scaled)
  *   dx     [dev] gradient w.r.t. x [B*S,H], compute dtype, overwritten
@@ -358,16 +361,25 @@ raf_status raf_op_softmax_bwd(const raf_layer_desc *desc, const void *prob, cons
  * from qkv [B*S,3H] (column blocks Q | K | V, head h = columns 64h .. 64h+63).
  *   ctx [dev] [B*S,H] written; lse [dev] float[B*heads*S] written when
  *   seq > 128 (row statistic max + log2(sum) in base-2 score units that the
- *   backward call needs), ignored and may be NULL otherwise. */
+ *   backward call needs), ignored and may be NULL otherwise.
+ *   keep [dev] raf_op_attention_keep_bytes(desc) bytes, 16-byte aligned, or NULL:
+ *   written when given and seq > 128 and dropout_p > 0: the keep decisions of
+ *   dropout site 1, one bit per score (16 bytes per query row and 128-key block;
+ *   bit 8u + e of dword g = key 32u + 8g + e of the block), so that the backward
+ *   call need not run the random number generator again. */
 raf_status raf_op_attention_fwd(const raf_layer_desc *desc, const void *qkv, const int32_t *seq_lens, void *ctx,
-                                float *lse, uint64_t step, void *hip_stream);
+                                float *lse, void *keep, uint64_t step, void *hip_stream);
+/* Bytes of the keep buffer above; 0 where none is used (seq <= 128 or dropout_p == 0). */
+size_t raf_op_attention_keep_bytes(const raf_layer_desc *desc);
 /* Adjoint: dqkv [B*S,3H] (dQ | dK | dV) from dctx [B*S,H]; probabilities and
  * dropout mask are recomputed from qkv, seq_lens and step, which must be those of
  * the forward call.  seq > 128 also needs ctx and lse of the forward call and
- * dvec [dev] float[B*heads*S] scratch; they are ignored (may be NULL) otherwise. */
+ * dvec [dev] float[B*heads*S] scratch; they are ignored (may be NULL) otherwise.
+ * keep: NULL (the dropout mask is generated again), or the buffer the forward call
+ * wrote (the same results, bit for bit, without the generator). */
 raf_status raf_op_attention_bwd(const raf_layer_desc *desc, const void *dctx, const void *qkv, const void *ctx,
-                                const float *lse, const int32_t *seq_lens, void *dqkv, float *dvec, uint64_t step,
-                                void *hip_stream);
+                                const float *lse, const void *keep, const int32_t *seq_lens, void *dqkv, float *dvec,
+                                uint64_t step, void *hip_stream);
 
 /* z = res + dropout_site(a); out = LayerNorm(z) with float statistics.
  * a == NULL: z = res (plain LayerNorm).  gamma == NULL: no LayerNorm, out = z

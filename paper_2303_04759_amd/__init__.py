@@ -131,8 +131,9 @@ _SIGNATURES = {
     "raf_op_softmax_bwd": (C.c_int, [C.POINTER(LayerDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_float, C.c_void_p]),
     "raf_op_attention_fwd": (C.c_int, [C.POINTER(LayerDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
-                                       C.c_uint64, C.c_void_p]),
-    "raf_op_attention_bwd": (C.c_int, [C.POINTER(LayerDesc)] + [C.c_void_p] * 7 + [C.c_uint64, C.c_void_p]),
+                                       C.c_void_p, C.c_uint64, C.c_void_p]),
+    "raf_op_attention_keep_bytes": (C.c_size_t, [C.POINTER(LayerDesc)]),
+    "raf_op_attention_bwd": (C.c_int, [C.POINTER(LayerDesc)] + [C.c_void_p] * 8 + [C.c_uint64, C.c_void_p]),
     "raf_op_dropout_residual_ln_fwd": (C.c_int, [C.POINTER(LayerDesc), C.c_int32, C.c_int64, C.c_void_p, C.c_void_p,
                                                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                                  C.c_void_p, C.c_uint64, C.c_void_p]),
@@ -350,13 +351,17 @@ def raf_op_softmax_bwd(desc, prob, prob_d, dprob_d, ds, scale_out, stream=None):
                                              float(scale_out), _stream(stream)), "raf_op_softmax_bwd")
 
 
-def raf_op_attention_fwd(desc, qkv, seq_lens, ctx, lse, step, stream=None):
+def raf_op_attention_fwd(desc, qkv, seq_lens, ctx, lse, step, stream=None, keep=None):
     _check(load_library().raf_op_attention_fwd(C.byref(desc), _ptr(qkv), _ptr(seq_lens), _ptr(ctx), _ptr(lse),
-                                               int(step), _stream(stream)), "raf_op_attention_fwd")
+                                               _ptr(keep), int(step), _stream(stream)), "raf_op_attention_fwd")
 
 
-def raf_op_attention_bwd(desc, dctx, qkv, ctx, lse, seq_lens, dqkv, dvec, step, stream=None):
-    _check(load_library().raf_op_attention_bwd(C.byref(desc), _ptr(dctx), _ptr(qkv), _ptr(ctx), _ptr(lse),
+def raf_op_attention_keep_bytes(desc):
+    return load_library().raf_op_attention_keep_bytes(C.byref(desc))
+
+
+def raf_op_attention_bwd(desc, dctx, qkv, ctx, lse, seq_lens, dqkv, dvec, step, stream=None, keep=None):
+    _check(load_library().raf_op_attention_bwd(C.byref(desc), _ptr(dctx), _ptr(qkv), _ptr(ctx), _ptr(lse), _ptr(keep),
                                                _ptr(seq_lens), _ptr(dqkv), _ptr(dvec), int(step), _stream(stream)),
            "raf_op_attention_bwd")
 

@@ -391,7 +391,13 @@ __global__ __launch_bounds__(512) void attn_bwd_full_kernel(const bf16_t* __rest
 // group), which is already the operand layout of dV = P~^T dC and dK = ds^T Q: no exchange between waves is needed.
 // Dropout blocks cover 8 consecutive keys of one query, so there each lane generates the block of one (query,
 // key octet) of its 16 x 32 sub-block and the keep bits are exchanged with lane permutes.
+// KEPT: the generator (twenty 32x32 multiplies per 8 scores) runs in the forward kernel only, which leaves its
+// decisions in memory, one bit per score: 16 bytes per (query row, 128-key block), dword g holding the octets
+// 32u + 8g .. +7 (u = 0..3 in bytes 0..3), which is what lane group g of the row's wavefront holds.  The adjoint
+// kernels read them back (dQ: one dword per lane and key block; dK/dV: the 2 KiB of a block pair staged through LDS
+// with the Q and dC blocks).
 constexpr int FL_QB = 128;   // query rows per workgroup (8 waves x 16)
+constexpr int FL_KEEP_TILE = FL_QB * 16;                   // keep bits of 128 queries x 128 keys
 // Block of the sequence that workgroup (blockIdx.x, blockIdx.y) takes.  Under a causal mask the work of a block
 // grows (query blocks) or shrinks (key blocks) along the sequence; two workgroups share a CU and are dealt to the
 // CUs round-robin, so every other round of 256 workgroups walks the sequence backwards and a long block meets a
@@ -424,9 +430,11 @@ __device__ __forceinline__ float frag_dot(const bf16x8_t (&a)[2], const bf16x8_t
   return d;
 }
 
+template <bool KEPT>
 __global__ __launch_bounds__(512) void attn_flash_fwd_kernel(const bf16_t* __restrict__ qkv, const int32_t* __restrict__ lens,
                                                              bf16_t* __restrict__ ctx, float* __restrict__ lse, int S,
-                                                             int H, int heads, int causal, float alpha2, DropSite drop) {
+                                                             int H, int heads, int causal, float alpha2, DropSite drop,
+                                                             uint32_t* __restrict__ keep) {
   extern __shared__ __attribute__((aligned(1024))) char fl_lds[];   // two stages of (K block, V block)
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int bh = blockIdx.y, b = bh / heads, h = bh % heads;
@@ -497,6 +505,7 @@ __global__ __launch_bounds__(512) void attn_flash_fwd_kernel(const bf16_t* __res
       mx = nm;
 #pragma unroll
       for (int nb = 0; nb < 4; ++nb) o[nb] = o[nb] * corr;
+      uint32_t kw = 0;
 #pragma unroll
       for (int u = 0; u < ATT_PAIRS; ++u)
         if (u < npairs) {
@@ -505,7 +514,13 @@ __global__ __launch_bounds__(512) void attn_flash_fwd_kernel(const bf16_t* __res
           for (int e = 0; e < 8; ++e) p[e] = acc[2 * u + (e >> 2)][e & 3];
           if (drop.enabled) {
             float mult[8];
-            drop_mult8(drop, (uint64_t)(row_off + key0 + 32 * u + jl), mult);
+            if (KEPT) {
+              uint32_t bits;
+              drop_mult8_bits(drop, (uint64_t)(row_off + key0 + 32 * u + jl), mult, bits);
+              kw |= bits << (8 * u);
+            } else {
+              drop_mult8(drop, (uint64_t)(row_off + key0 + 32 * u + jl), mult);
+            }
 #pragma unroll
             for (int e = 0; e < 8; ++e) p[e] *= mult[e];
           }
@@ -514,6 +529,7 @@ __global__ __launch_bounds__(512) void attn_flash_fwd_kernel(const bf16_t* __res
           for (int nb = 0; nb < 4; ++nb)
             o[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hd_frag_t(vt, u, nb), pf, o[nb], 0, 0, 0);
         }
+      if (KEPT && drop.enabled) keep[(((long)bh * S + i) * ((S + ATT_KC - 1) / ATT_KC) + jb) * 4 + (lane >> 4)] = kw;
     }
   }
   if (!active) return;
@@ -525,11 +541,13 @@ __global__ __launch_bounds__(512) void attn_flash_fwd_kernel(const bf16_t* __res
 }
 
 // dQ = ds . K over all key blocks; also writes D = rowsum(dC (.) ctx) for the dK/dV kernel
+template <bool KEPT>
 __global__ __launch_bounds__(512) void attn_flash_dq_kernel(const bf16_t* __restrict__ dc, const bf16_t* __restrict__ qkv,
                                                             const bf16_t* __restrict__ ctx, const float* __restrict__ lse,
                                                             const int32_t* __restrict__ lens, bf16_t* __restrict__ dqkv,
                                                             float* __restrict__ dvec, int S, int H, int heads, int causal,
-                                                            float alpha2, float alpha, DropSite drop) {
+                                                            float alpha2, float alpha, DropSite drop,
+                                                            const uint32_t* __restrict__ keep) {
   extern __shared__ __attribute__((aligned(1024))) char fl_lds[];   // two stages of (K block, V block)
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int bh = blockIdx.y, b = bh / heads, h = bh % heads;
@@ -568,6 +586,11 @@ __global__ __launch_bounds__(512) void attn_flash_dq_kernel(const bf16_t* __rest
     hd_tile_load(Q + H + (long)key0 * ld, ld, rows, st);
     hd_tile_load(Q + 2 * H + (long)key0 * ld, ld, rows, st + HD_TILE);
   };
+  // this lane's keep bits of key block jb: one dword, requested one block ahead
+  const bool kept = KEPT && active && drop.enabled;
+  const uint32_t* kp = keep + ((long)bh * S + (kept ? i : 0)) * ((S + ATT_KC - 1) / ATT_KC) * 4 + (lane >> 4);
+  uint32_t kw_next = 0;
+  if (kept && nkb > 0) kw_next = kp[0];
   if (nkb > 0) fetch(0);
   for (int jb = 0; jb < nkb; ++jb) {
     const int key0 = jb * ATT_KC;
@@ -578,6 +601,8 @@ __global__ __launch_bounds__(512) void attn_flash_dq_kernel(const bf16_t* __rest
     hd_tile_wait();
     __syncthreads();                                      // block jb has landed; every wave is done with block jb-1
     if (jb + 1 < nkb) fetch(jb + 1);
+    const uint32_t kw = kw_next;
+    if (kept && jb + 1 < nkb) kw_next = kp[(jb + 1) * 4];
     if (active) {
 #pragma unroll
       for (int u = 0; u < ATT_PAIRS; ++u)
@@ -586,7 +611,10 @@ __global__ __launch_bounds__(512) void attn_flash_dq_kernel(const bf16_t* __rest
           group_products(kt, qf, u, acc);
           group_products(vt, gf, u, dacc);
           float mult[8], dsv[8];
-          if (drop.enabled) {
+          if (KEPT && drop.enabled) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) mult[e] = ((kw >> (8 * u + e)) & 1u) ? drop.scale : 0.f;
+          } else if (drop.enabled) {
             drop_mult8(drop, (uint64_t)(row_off + key0 + 32 * u + jl), mult);
           } else {
 #pragma unroll
@@ -609,12 +637,15 @@ __global__ __launch_bounds__(512) void attn_flash_dq_kernel(const bf16_t* __rest
 }
 
 // dV = P~^T dC and dK = ds^T Q for the 128 keys of one block, over all query blocks
+template <bool KEPT>
 __global__ __launch_bounds__(512, 4) void attn_flash_dkv_kernel(const bf16_t* __restrict__ dc, const bf16_t* __restrict__ qkv,
                                                              const float* __restrict__ lse, const float* __restrict__ dvec,
                                                              const int32_t* __restrict__ lens, bf16_t* __restrict__ dqkv,
                                                              int S, int H, int heads, int causal, float alpha2,
-                                                             float alpha, DropSite drop) {
-  extern __shared__ __attribute__((aligned(1024))) char fl_lds[];   // two stages of (Q block, dC block, lse and D of its rows)
+                                                             float alpha, DropSite drop, const uint32_t* __restrict__ keep) {
+  // two stages of (Q block, dC block, lse and D of its rows; KEPT: the keep bits of the block pair)
+  extern __shared__ __attribute__((aligned(1024))) char fl_lds[];
+  constexpr int STAGE = FL_DKV_STAGE + (KEPT ? FL_KEEP_TILE : 0);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int bh = blockIdx.y, b = bh / heads, h = bh % heads;
   const long ld = 3L * H;
@@ -642,7 +673,7 @@ __global__ __launch_bounds__(512, 4) void attn_flash_dkv_kernel(const bf16_t* __
   auto fetch = [&](int ib) {   // Q and dC rows of query block ib and their row statistics -> stage ib & 1
     const int q0 = ib * FL_QB;
     const int rows = S - q0 < FL_QB ? S - q0 : FL_QB;
-    char* st = fl_lds + (ib & 1) * FL_DKV_STAGE;
+    char* st = fl_lds + (ib & 1) * STAGE;
     hd_tile_load(Q + (long)q0 * ld, ld, rows, st);
     hd_tile_load(DC + (long)q0 * H, H, rows, st + HD_TILE);
     if (wave < 4) {   // 4 bytes per lane: lse rows 0-63, 64-127, then D likewise (rows past the end re-read the last row)
@@ -652,13 +683,20 @@ __global__ __launch_bounds__(512, 4) void attn_flash_dkv_kernel(const bf16_t* __
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                        (att_lds_ptr)(st + 2 * HD_TILE + wave * 256), 4, 0, 0);
     }
+    if (KEPT && drop.enabled) {   // 4 bytes per lane: dword (thread & 3) of query row thread >> 2, this key block
+      int q = q0 + (int)(threadIdx.x >> 2);
+      q = q < S ? q : S - 1;
+      const uint32_t* src = keep + (((long)bh * S + q) * ((S + ATT_KC - 1) / ATT_KC) + jb) * 4 + (threadIdx.x & 3);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                       (att_lds_ptr)(st + FL_DKV_STAGE + wave * 256), 4, 0, 0);
+    }
   };
   if (ib0 < ib1) fetch(ib0);
   for (int ib = ib0; ib < ib1; ++ib) {
     const int q0 = ib * FL_QB;
     const int rows = S - q0 < FL_QB ? S - q0 : FL_QB;
     const int npairs = rows / 32;
-    const char* qt = fl_lds + (ib & 1) * FL_DKV_STAGE;
+    const char* qt = fl_lds + (ib & 1) * STAGE;
     const char* ct = qt + HD_TILE;
     const float* lse_t = reinterpret_cast<const float*>(ct + HD_TILE);
     const float* dvec_t = lse_t + FL_QB;
@@ -681,8 +719,13 @@ __global__ __launch_bounds__(512, 4) void attn_flash_dkv_kernel(const bf16_t* __
           // this lane's Philox block: query qg + (m & 7), keys kbase + 8*(m >> 3) .. +7; the lane that needs the bit
           // of (query qg + e, key k) fetches the block of lane (g, e + 8*(m >> 3)) and takes bit m & 7
           uint32_t mine = 0xffu;
-          if (drop.enabled)
+          if (KEPT && drop.enabled) {
+            // keys 16*wave + 8*(m >> 3) .. +7 of the block: octet 2*wave + (m >> 3) = 4*byte + dword
+            const int row = 32 * u + 8 * g + (m & 7);
+            mine = *reinterpret_cast<const uint8_t*>(qt + FL_DKV_STAGE + row * 16 + (2 * (wave & 1) + (m >> 3)) * 4 + (wave >> 1));
+          } else if (drop.enabled) {
             mine = drop_keep8(drop, (uint64_t)(((long)bh * S + qg + (m & 7)) * S + kbase + 8 * (m >> 3)));
+          }
           float pd[8], dsv[8];
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
@@ -743,38 +786,65 @@ bool attn_flash_supported(const raf_layer_desc& d) {
   return d.precision == RAF_BF16_AMP && d.hidden / d.heads == 64 && d.seq % 32 == 0 && d.seq > ATT_KC;
 }
 
+size_t attn_flash_keep_bytes(const raf_layer_desc& d) {
+  if (!attn_flash_supported(d) || !(d.dropout_p > 0.0)) return 0;
+  return (size_t)d.batch * d.heads * d.seq * ((d.seq + ATT_KC - 1) / ATT_KC) * 16;
+}
+
 raf_status launch_attn_flash_fwd(const raf_layer_desc& d, const void* qkv, const int32_t* lens, void* ctx, float* lse,
-                                 uint64_t step, hipStream_t st) {
-  if (!qkv || !ctx || !lse) return RAF_EINVAL;
+                                 uint64_t step, hipStream_t st, uint32_t* keep) {
+  if (!qkv || !ctx || !lse || ((uintptr_t)keep & 15u)) return RAF_EINVAL;
   if (!attn_flash_supported(d)) return RAF_ENOTSUP;
   const DropSite drop = make_drop_site(d, 1, step);
   dim3 grid((d.seq + FL_QB - 1) / FL_QB, d.batch * d.heads);
-  static LdsLimitOnce lds_limit;
-  if (!lds_limit.ensure((const void*)attn_flash_fwd_kernel, 2 * FL_STAGE)) return RAF_EHIP;
-  hipLaunchKernelGGL(attn_flash_fwd_kernel, grid, dim3(512), 2 * FL_STAGE, st, (const bf16_t*)qkv, lens, (bf16_t*)ctx, lse, d.seq,
-                     d.hidden, d.heads, d.causal, 0.125f * 1.44269504088896341f, drop);
+  static LdsLimitOnce lds_limit, lds_limit_kept;
+  if (keep && drop.enabled) {
+    if (!lds_limit_kept.ensure((const void*)attn_flash_fwd_kernel<true>, 2 * FL_STAGE)) return RAF_EHIP;
+    hipLaunchKernelGGL(attn_flash_fwd_kernel<true>, grid, dim3(512), 2 * FL_STAGE, st, (const bf16_t*)qkv, lens, (bf16_t*)ctx,
+                       lse, d.seq, d.hidden, d.heads, d.causal, 0.125f * 1.44269504088896341f, drop, keep);
+  } else {
+    if (!lds_limit.ensure((const void*)attn_flash_fwd_kernel<false>, 2 * FL_STAGE)) return RAF_EHIP;
+    hipLaunchKernelGGL(attn_flash_fwd_kernel<false>, grid, dim3(512), 2 * FL_STAGE, st, (const bf16_t*)qkv, lens, (bf16_t*)ctx,
+                       lse, d.seq, d.hidden, d.heads, d.causal, 0.125f * 1.44269504088896341f, drop, (uint32_t*)nullptr);
+  }
   return check_launch();
 }
 
 raf_status launch_attn_flash_bwd(const raf_layer_desc& d, const void* dc, const void* qkv, const void* ctx,
                                  const float* lse, const int32_t* lens, void* dqkv, float* dvec, uint64_t step,
-                                 hipStream_t st) {
-  if (!dc || !qkv || !ctx || !lse || !dqkv || !dvec) return RAF_EINVAL;
+                                 hipStream_t st, const uint32_t* keep) {
+  if (!dc || !qkv || !ctx || !lse || !dqkv || !dvec || ((uintptr_t)keep & 15u)) return RAF_EINVAL;
   if (!attn_flash_supported(d)) return RAF_ENOTSUP;
   const DropSite drop = make_drop_site(d, 1, step);
   const float alpha2 = 0.125f * 1.44269504088896341f;
   dim3 grid((d.seq + FL_QB - 1) / FL_QB, d.batch * d.heads);
-  static LdsLimitOnce lds_dq, lds_dkv;
-  if (!lds_dq.ensure((const void*)attn_flash_dq_kernel, 2 * FL_STAGE) ||
-      !lds_dkv.ensure((const void*)attn_flash_dkv_kernel, 2 * FL_DKV_STAGE))
+  static LdsLimitOnce lds_dq, lds_dkv, lds_dq_kept, lds_dkv_kept;
+  if (keep && drop.enabled) {
+    constexpr int DKV_LDS = 2 * (FL_DKV_STAGE + FL_KEEP_TILE);
+    if (!lds_dq_kept.ensure((const void*)attn_flash_dq_kernel<true>, 2 * FL_STAGE) ||
+        !lds_dkv_kept.ensure((const void*)attn_flash_dkv_kernel<true>, DKV_LDS))
+      return RAF_EHIP;
+    hipLaunchKernelGGL(attn_flash_dq_kernel<true>, grid, dim3(512), 2 * FL_STAGE, st, (const bf16_t*)dc, (const bf16_t*)qkv,
+                       (const bf16_t*)ctx, lse, lens, (bf16_t*)dqkv, dvec, d.seq, d.hidden, d.heads, d.causal, alpha2,
+                       0.125f, drop, keep);
+    const raf_status rc = check_launch();
+    if (rc != RAF_OK) return rc;
+    hipLaunchKernelGGL(attn_flash_dkv_kernel<true>, grid, dim3(512), DKV_LDS, st, (const bf16_t*)dc, (const bf16_t*)qkv, lse,
+                       (const float*)dvec, lens, (bf16_t*)dqkv, d.seq, d.hidden, d.heads, d.causal, alpha2, 0.125f, drop,
+                       keep);
+    return check_launch();
+  }
+  if (!lds_dq.ensure((const void*)attn_flash_dq_kernel<false>, 2 * FL_STAGE) ||
+      !lds_dkv.ensure((const void*)attn_flash_dkv_kernel<false>, 2 * FL_DKV_STAGE))
     return RAF_EHIP;
-  hipLaunchKernelGGL(attn_flash_dq_kernel, grid, dim3(512), 2 * FL_STAGE, st, (const bf16_t*)dc, (const bf16_t*)qkv,
+  hipLaunchKernelGGL(attn_flash_dq_kernel<false>, grid, dim3(512), 2 * FL_STAGE, st, (const bf16_t*)dc, (const bf16_t*)qkv,
                      (const bf16_t*)ctx, lse, lens, (bf16_t*)dqkv, dvec, d.seq, d.hidden, d.heads, d.causal, alpha2,
-                     0.125f, drop);
+                     0.125f, drop, (const uint32_t*)nullptr);
   const raf_status rc = check_launch();
   if (rc != RAF_OK) return rc;
-  hipLaunchKernelGGL(attn_flash_dkv_kernel, grid, dim3(512), 2 * FL_DKV_STAGE, st, (const bf16_t*)dc, (const bf16_t*)qkv, lse,
-                     (const float*)dvec, lens, (bf16_t*)dqkv, d.seq, d.hidden, d.heads, d.causal, alpha2, 0.125f, drop);
+  hipLaunchKernelGGL(attn_flash_dkv_kernel<false>, grid, dim3(512), 2 * FL_DKV_STAGE, st, (const bf16_t*)dc, (const bf16_t*)qkv,
+                     lse, (const float*)dvec, lens, (bf16_t*)dqkv, d.seq, d.hidden, d.heads, d.causal, alpha2, 0.125f, drop,
+                     (const uint32_t*)nullptr);
   return check_launch();
 }
 

@@ -181,6 +181,19 @@ __device__ __forceinline__ void drop_mult8(const DropSite& s, uint64_t idx8, flo
   mult[6] = (a.w & 0xffffu) >= s.thr ? s.scale : 0.f; mult[7] = (a.w >> 16) >= s.thr ? s.scale : 0.f;
 }
 
+// the same, and the decisions as bits (bit e = element idx8 + e is kept)
+__device__ __forceinline__ void drop_mult8_bits(const DropSite& s, uint64_t idx8, float (&mult)[8], uint32_t& bits) {
+  const Philox4 a = philox4x32_10((uint32_t)(idx8 >> 3), s.c1, s.c2, s.c3, s.k0, s.k1);
+  const uint32_t f[8] = {a.x & 0xffffu, a.x >> 16, a.y & 0xffffu, a.y >> 16, a.z & 0xffffu, a.z >> 16, a.w & 0xffffu, a.w >> 16};
+  bits = 0;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const bool kept = f[e] >= s.thr;
+    mult[e] = kept ? s.scale : 0.f;
+    bits |= kept ? (1u << e) : 0u;
+  }
+}
+
 // ------------------------------------------------------------- reductions --
 template <int WIDTH>
 __device__ __forceinline__ float group_sum(float v) {
@@ -382,11 +395,14 @@ raf_status launch_attn_fwd_fused(const raf_layer_desc& d, const void* qkv, const
 // S > 128 in bf16 AMP: blockwise with running softmax statistics; lse [B*heads*S] floats goes from forward to
 // backward, dvec [B*heads*S] floats is backward scratch
 bool attn_flash_supported(const raf_layer_desc& d);
+// keep (optional, attn_flash_keep_bytes(d) bytes): the forward kernel leaves the keep decisions of dropout site 1
+// there, one bit per score, and the adjoint kernels read them instead of running the generator again
+size_t attn_flash_keep_bytes(const raf_layer_desc& d);
 raf_status launch_attn_flash_fwd(const raf_layer_desc& d, const void* qkv, const int32_t* lens, void* ctx, float* lse,
-                                 uint64_t step, hipStream_t st);
+                                 uint64_t step, hipStream_t st, uint32_t* keep = nullptr);
 raf_status launch_attn_flash_bwd(const raf_layer_desc& d, const void* dc, const void* qkv, const void* ctx,
                                  const float* lse, const int32_t* lens, void* dqkv, float* dvec, uint64_t step,
-                                 hipStream_t st);
+                                 hipStream_t st, const uint32_t* keep = nullptr);
 raf_status launch_attn_bwd_full(const raf_layer_desc& d, const void* dc, const void* qkv, const int32_t* lens, void* dqkv,
                                 uint64_t step, hipStream_t st);
 // Loss seed taken by the kernel that writes the layer's output: partial sums of out * G (one per workgroup, ln_fwd_blocks

@@ -227,7 +227,8 @@ bool build_stack(const raf_layer_desc& d, int layers, const double* replay_us, S
   const int64_t T = (int64_t)d.batch * d.seq, H = d.hidden, F = d.ffn;
   const int64_t TH = (int64_t)(T * H * e), TF = (int64_t)(T * F * e);
   const int64_t stat = T * 8, PS = onchip ? 0 : (int64_t)((double)d.batch * d.heads * d.seq * d.seq * e);
-  const int64_t rowstat = flash ? (int64_t)d.batch * d.heads * d.seq * 4 : 0;
+  // row statistics of the blockwise attention and the keep decisions of its dropout site: one tensor here
+  const int64_t rowstat = flash ? (int64_t)d.batch * d.heads * d.seq * 4 + (int64_t)attn_flash_keep_bytes(d) : 0;
   double us[3];
   if (replay_us) {
     for (int i = 0; i < 3; ++i) {

@@ -90,10 +90,10 @@ def test_null_and_misaligned_pointers_are_rejected_on_host(lib):
     assert lib.raf_adam_step_scaled(None, 0, 1e-3, 0.9, 0.999, 1e-8, 0.0, None, None) == raf.RAF_EINVAL
     assert lib.raf_loss_seed_scaled(1, 4096, 4096, 64, None, 4096, 4096, 4096, None) == raf.RAF_EINVAL
     d32 = raf.make_desc(good_cfg())                                                  # fp32: no on-chip attention path
-    assert lib.raf_op_attention_fwd(C.byref(d32), 4096, None, 4096, None, 0, None) == raf.RAF_ENOTSUP
+    assert lib.raf_op_attention_fwd(C.byref(d32), 4096, None, 4096, None, None, 0, None) == raf.RAF_ENOTSUP
     dbf = raf.make_desc(good_cfg(precision=1))
-    assert lib.raf_op_attention_fwd(C.byref(dbf), None, None, 4096, None, 0, None) == raf.RAF_EINVAL
-    assert lib.raf_op_attention_bwd(C.byref(dbf), 4096, 4096 + 2, None, None, None, 4096, None, 0, None) == raf.RAF_EINVAL
+    assert lib.raf_op_attention_fwd(C.byref(dbf), None, None, 4096, None, None, 0, None) == raf.RAF_EINVAL
+    assert lib.raf_op_attention_bwd(C.byref(dbf), 4096, 4096 + 2, None, None, None, None, 4096, None, 0, None) == raf.RAF_EINVAL
     assert raf.status_string(raf.RAF_ENOTSUP) == "unsupported shape or mode"
     assert raf.version().startswith("raf_mi355")
 

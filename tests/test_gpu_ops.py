@@ -235,6 +235,64 @@ def test_attention_core_fwd_bwd(B, S, nh, causal, p):
         assert (got[S + L1:2 * S, H:] == 0).all()
 
 
+@pytest.mark.parametrize("B,S,nh,causal,p", [(3, 160, 2, 0, 0.1), (3, 256, 2, 1, 0.1), (2, 416, 1, 1, 0.3),
+                                             (3, 512, 2, 0, 0.2), (1, 1024, 1, 1, 0.1)])
+def test_attention_keep_bits_stand_in_for_the_generator(B, S, nh, causal, p):
+    """Blockwise attention with a keep buffer: the forward call leaves the keep decisions of dropout site 1 (checked
+    against the mask the generator gives, wherever a key block is visited), and the backward call that reads them gives
+    the results of the one that generates them again, bit for bit.  The latter is checked against the oracle above."""
+    announce("attention keep bits", B, S, nh, causal, p)
+    H = 64 * nh
+    cfg = cfg_for(B, S, H, 1, p=p, causal=causal)
+    desc = raf.make_desc(cfg)
+    rng = np.random.default_rng(7000 * S + nh + causal)
+    bf = torch.bfloat16
+    qkv_d = to_dev(rnd(rng, (B * S, 3 * H), 1, 1.5), bf)
+    dctx_d = to_dev(rnd(rng, (B * S, H), 1), bf)
+    lens = np.array([S, max(1, S // 3), 0][:B], dtype=np.int32)
+    lens_d = torch.from_numpy(lens).cuda()
+    step = 9
+    nkb = (S + 127) // 128
+    nbytes = raf.raf_op_attention_keep_bytes(desc)
+    assert nbytes == B * nh * S * nkb * 16
+    assert raf.raf_op_attention_keep_bytes(raf.make_desc(dict(cfg, dropout_p=0.0))) == 0
+    assert raf.raf_op_attention_keep_bytes(raf.make_desc(dict(cfg, seq=128))) == 0
+    out = {}
+    for with_keep in (False, True):
+        ctx = torch.full((B * S, H), 7.0, device="cuda", dtype=bf)
+        dqkv = torch.full((B * S, 3 * H), 7.0, device="cuda", dtype=bf)
+        lse = torch.zeros(B * nh * S, device="cuda", dtype=torch.float32)
+        dvec = torch.zeros(B * nh * S, device="cuda", dtype=torch.float32)
+        keep = torch.zeros(nbytes // 4, device="cuda", dtype=torch.int32) if with_keep else None
+        raf.raf_op_attention_fwd(desc, qkv_d, lens_d, ctx, lse, step, keep=keep)
+        raf.raf_op_attention_bwd(desc, dctx_d, qkv_d, ctx, lse, lens_d, dqkv, dvec, step, keep=keep)
+        torch.cuda.synchronize()
+        out[with_keep] = (ctx, lse, dqkv, keep)
+    for a, b in zip(out[False][:3], out[True][:3]):
+        assert torch.equal(a, b)
+    # the stored bits: bit 8u + e of dword g of (row, key block jb) is key 128 jb + 32u + 8g + e
+    w = out[True][3].cpu().numpy().view(np.uint32).reshape(B, nh, S, nkb, 4)
+    bits = (w[..., None] >> np.arange(32, dtype=np.uint32)) & 1              # [B, nh, S, nkb, g, 8u + e]
+    bits = bits.reshape(B, nh, S, nkb, 4, 4, 8).transpose(0, 1, 2, 3, 5, 4, 6)   # -> [.., nkb, u, g, e]
+    bits = bits.reshape(B, nh, S, nkb * 128)[..., :S].astype(bool)
+    mask = torch.zeros(B * nh * S * S, dtype=torch.uint8, device="cuda")
+    raf.raf_debug_dropout_mask(desc, 1, step, mask, mask.numel())
+    mask = mask.cpu().numpy().reshape(B, nh, S, S).astype(bool)
+    rows = np.arange(S)
+    q_end = np.minimum((rows // 128 + 1) * 128, S)
+    visited = 0
+    for b in range(B):
+        # key blocks the forward kernel visits for a query row: those that start below the length (and, under a
+        # causal mask, below the end of the row's 128-query block)
+        kmax = np.minimum(int(lens[b]), q_end) if causal else np.full(S, int(lens[b]))
+        seen = (np.arange(S)[None, :] // 128 * 128) < kmax[:, None]           # [query, key]
+        visited += int(seen.sum())
+        for h in range(nh):
+            assert (bits[b, h][seen] == mask[b, h][seen]).all(), (b, h)
+            assert not bits[b, h][~seen].any()                                # never written
+    assert visited > 0
+
+
 # -------------------------------------------------------------- layernorm --
 @pytest.mark.parametrize("precision", [0, 1])
 @pytest.mark.parametrize("rows,H,p", [(64, 128, 0.0), (100, 768, 0.1), (37, 1024, 0.1), (9, 2048, 0.3), (5, 4096, 0.1),
