@@ -533,17 +533,22 @@ def main():
         p = {k: v.astype(np.float64) for k, v in inp["params"].items()}
         z = {k: np.zeros_like(v) for k, v in p.items()}
         hyper = dict(ADAM, loss_scale=cfg["loss_scale"])
+        # a bounded sample: consecutive full steps until about ten seconds have gone by (at most eight)
+        m_cpu, v_cpu, n_cpu = z, z, 0
         t0 = time.perf_counter()
-        train_step(cfg, p, z, z, inp["x"], inp["G"], inp["seq_lens"], 1, hyper)
+        while n_cpu < 8 and (n_cpu == 0 or time.perf_counter() - t0 < 10.0):
+            n_cpu += 1
+            ref = train_step(cfg, p, m_cpu, v_cpu, inp["x"], inp["G"], inp["seq_lens"], n_cpu, hyper)
+            p, m_cpu, v_cpu = ref["params"], ref["m"], ref["v"]
         dt_cpu = time.perf_counter() - t0
         try:
             from threadpoolctl import threadpool_info
             threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
         except Exception:
             threads = os.cpu_count()
-        out["cpu_baseline"] = {"value": cfg["batch"] / dt_cpu, "unit": "samples/s", "cores": threads,
-                               "kind": "oracle", "sample": "one full step (batch %d) of the same workload, numpy fp64, "
-                               "%.1f s" % (cfg["batch"], dt_cpu)}
+        out["cpu_baseline"] = {"value": n_cpu * cfg["batch"] / dt_cpu, "unit": "samples/s", "cores": threads,
+                               "kind": "oracle", "sample": "%d consecutive full steps (batch %d each) of the same workload, "
+                               "numpy fp64, %.1f s" % (n_cpu, cfg["batch"], dt_cpu)}
     print(json.dumps(out))
 
 
