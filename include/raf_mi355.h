@@ -23,7 +23,11 @@
  *     after a call returns.  [host] pointers are read during the call only.
  *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*,
  *     NULL = the default stream).  Calls are asynchronous; they are safe to
- *     record into a HIP graph (no memset/memcpy nodes are issued).
+ *     record into a HIP graph (no memset/memcpy nodes are issued).  Scalar
+ *     arguments (the dropout `step`, Adam's `t`, lr, loss_scale) are host values
+ *     frozen into the recorded launches: a replay repeats the same dropout masks
+ *     and bias corrections.  Only the *_scaled entry points, which read t and the
+ *     loss scale from a raf_scaler_state on the device, advance across replays.
  *   - Tensors are dense, row-major, 16-byte aligned (else RAF_EINVAL).
  *   - "compute dtype" is float in RAF_F32 mode and bfloat16 (round to nearest
  *     even) in RAF_BF16_AMP mode.  Vectors (biases, LayerNorm gamma/beta),
