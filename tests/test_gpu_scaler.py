@@ -65,12 +65,13 @@ def test_dynamic_scaler_sequence(precision, poison):
     assert st["t"] == 5 and st["scale"] == 256.0
 
 
-@pytest.mark.parametrize("epilogue_check", [True, False])
-def test_non_finite_test_in_the_backward_epilogues_at_full_size(epilogue_check):
-    """BERT-base shape: weight gradients and all reductions leave raf_layer_bwd in one launch, which also raises
-    found_inf; the decisions must be those of the separate pass over the gradients (raf_grads_check)."""
-    announce("dynamic scaler, non-finite test in the epilogues", epilogue_check)
-    cfg = CONFIGS["bert_base"]
+@pytest.mark.parametrize("name,epilogue_check", [("bert_base", True), ("bert_base", False), ("bert_large", True)])
+def test_non_finite_test_in_the_backward_epilogues_at_full_size(name, epilogue_check):
+    """Weight gradients and all reductions leave raf_layer_bwd in one launch, which also raises found_inf; the
+    decisions must be those of the separate pass over the gradients (raf_grads_check).  BERT-base shape: fewer
+    weight-gradient tiles than CUs; BERT-large shape: more, the reductions ride in the last round of tiles."""
+    announce("dynamic scaler, non-finite test in the epilogues", name, epilogue_check)
+    cfg = CONFIGS[name]
     inp = make_layer_inputs(cfg, seed=7)
     lay = DeviceLayer(cfg, inp, ADAM)
     state = torch.zeros(C.sizeof(raf.ScalerState), dtype=torch.uint8, device="cuda")
