@@ -62,6 +62,20 @@ def test_workspace_and_descriptor_validation(lib):
         assert e.value.status == code, bad
 
 
+def test_keep_bits_of_the_blockwise_attention_are_accounted_for(lib):
+    """Host arithmetic only: one keep bit per score for seq > 128 with dropout (16 bytes per query row and 128-key
+    block), none otherwise, and raf_layer_workspace reserves exactly that much more of `saved`."""
+    big = good_cfg(batch=2, seq=416, hidden=128, heads=2, ffn=512, precision=1)
+    nbytes = raf.raf_op_attention_keep_bytes(raf.make_desc(big))
+    assert nbytes == 2 * 2 * 416 * 4 * 16
+    assert raf.raf_op_attention_keep_bytes(raf.make_desc(dict(big, dropout_p=0.0))) == 0
+    assert raf.raf_op_attention_keep_bytes(raf.make_desc(dict(big, seq=128))) == 0
+    assert raf.raf_op_attention_keep_bytes(raf.make_desc(dict(big, precision=0))) == 0
+    with_bits, _ = raf.raf_layer_workspace(raf.make_desc(big))
+    without, _ = raf.raf_layer_workspace(raf.make_desc(dict(big, dropout_p=0.0)))
+    assert with_bits - without == (nbytes + 255) // 256 * 256
+
+
 def test_null_and_misaligned_pointers_are_rejected_on_host(lib):
     d = raf.make_desc(good_cfg())
     w = raf.LayerTensors()          # all NULL
