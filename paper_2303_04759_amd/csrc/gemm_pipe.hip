@@ -595,9 +595,9 @@ __device__ __forceinline__ bf16x8_t w48_fragment(const char* lds_tile, int row0,
 // output block, each takes one 32-deep half of every k-step, and the halves are added through LDS at the end (each
 // wave of the pair then finishes half of the rows).  For tiles with only 4-8 waves this gives every SIMD a second
 // wave to issue MFMAs while the first waits for its LDS fragments.
-template <int WGM, int WGN, int NS, int KS, typename TC>
+template <int WGM, int WGN, int NS, int KS, typename TC, int NB = 3>
 __global__ __launch_bounds__(64 * WGM * WGN * KS) void gemm_bf16_w48_kernel(GemmDev g, int tiles_m, int tiles_n) {
-  constexpr int NT = WGM * WGN, NW = NT * KS, BM = 64 * WGM, BN = 48 * WGN;
+  constexpr int NT = WGM * WGN, NW = NT * KS, BM = 64 * WGM, BN = 16 * NB * WGN;
   constexpr int ACH = BM / 8, BCH = BN / 8;           // KiB per operand tile
   constexpr int STAGE_BYTES = (ACH + BCH) * 1024;
   constexpr int BFIRST = ACH % NW;                    // wave that takes B chunk 0
@@ -617,7 +617,7 @@ __global__ __launch_bounds__(64 * WGM * WGN * KS) void gemm_bf16_w48_kernel(Gemm
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wt = wave % NT, kg = wave / NT;           // output block of this wave, its half of each k-step
-  const int wm = (wt / WGN) * 64, wn = (wt % WGN) * 48;
+  const int wm = (wt / WGN) * 64, wn = (wt % WGN) * 16 * NB;
 
   const bf16_t* srca[(ACH + NW - 1) / NW + 1];
   const bf16_t* srcb[(BCH + NW - 1) / NW + 1];
@@ -626,11 +626,11 @@ __global__ __launch_bounds__(64 * WGM * WGN * KS) void gemm_bf16_w48_kernel(Gemm
   // loads this wave issues per stage: chunk f of the ACH+BCH goes to wave f % NW
   const int my_loads = (ACH + BCH) / NW + (wave < (ACH + BCH) % NW ? 1 : 0);
 
-  f32x4_t acc[4][3];
+  f32x4_t acc[4][NB];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 3; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < NB; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
   const int nk = g.K / PBK;
 #pragma unroll
@@ -657,16 +657,16 @@ __global__ __launch_bounds__(64 * WGM * WGN * KS) void gemm_bf16_w48_kernel(Gemm
 #pragma unroll
     for (int kh = 0; kh < 2 / KS; ++kh) {
       const int kk = KS == 2 ? kg : kh;
-      bf16x8_t fa[4], fb[3];
+      bf16x8_t fa[4], fb[NB];
 #pragma unroll
       for (int i = 0; i < 4; ++i) fa[i] = w48_fragment(ta, wm + i * 16, kk);
 #pragma unroll
-      for (int j = 0; j < 3; ++j) fb[j] = w48_fragment(tb, wn + j * 16, kk);
+      for (int j = 0; j < NB; ++j) fb[j] = w48_fragment(tb, wn + j * 16, kk);
       // operands swapped: a lane ends with output row (l & 15) and 4 consecutive columns 4*(l>>4) + r
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 3; ++j)
+        for (int j = 0; j < NB; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
     }
     stage = stage + 1 == NS ? 0 : stage + 1;
@@ -676,25 +676,26 @@ __global__ __launch_bounds__(64 * WGM * WGN * KS) void gemm_bf16_w48_kernel(Gemm
   // wave-private LDS for the staged epilogue: with one wave per block a slice of the ring stage that nobody reads
   // any more (every wave has passed the last barrier, so all reads of the stage before the last one are done and no
   // load is in flight), with wave pairs the slot this wave received its partner's accumulators in
-  static_assert(KS == 2 || NW * epilogue_stage_bytes<3>() <= STAGE_BYTES, "staging exceeds a ring stage");
-  static_assert(epilogue_stage_bytes<3>() <= 6 * 64 * 16, "staging exceeds an exchange slot");
-  char* stg = lds + stage * STAGE_BYTES + wave * epilogue_stage_bytes<3>();
+  // (waves whose slice does not fit that stage any more take one behind the ring: w48_stage_spill)
+  constexpr int SB = epilogue_stage_bytes<NB>(), FIT = STAGE_BYTES / SB;
+  static_assert(epilogue_stage_bytes<NB>() <= 2 * NB * 64 * 16, "staging exceeds an exchange slot");
+  char* stg = wave < FIT ? lds + stage * STAGE_BYTES + wave * SB : lds + NS * STAGE_BYTES + (wave - FIT) * SB;
   if (KS == 2) {
     // exchange: the wave with kg = 0 finishes row blocks 0-1, its partner row blocks 2-3; each sends the other half
     __builtin_amdgcn_s_barrier();   // every wave is done with the ring
-    f32x4_t* xch = reinterpret_cast<f32x4_t*>(lds) + (wt * 2 + (kg ^ 1)) * 6 * 64;   // slot read by the partner
+    f32x4_t* xch = reinterpret_cast<f32x4_t*>(lds) + (wt * 2 + (kg ^ 1)) * 2 * NB * 64;   // slot read by the partner
 #pragma unroll
     for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
-      for (int j = 0; j < 3; ++j) xch[(ii * 3 + j) * 64 + lane] = kg ? acc[ii][j] : acc[2 + ii][j];   // static indices: no scratch
+      for (int j = 0; j < NB; ++j) xch[(ii * NB + j) * 64 + lane] = kg ? acc[ii][j] : acc[2 + ii][j];   // static indices: no scratch
     __syncthreads();
-    const f32x4_t* got = reinterpret_cast<const f32x4_t*>(lds) + (wt * 2 + kg) * 6 * 64;
-    stg = lds + (wt * 2 + kg) * 6 * 64 * 16;
+    const f32x4_t* got = reinterpret_cast<const f32x4_t*>(lds) + (wt * 2 + kg) * 2 * NB * 64;
+    stg = lds + (wt * 2 + kg) * 2 * NB * 64 * 16;
 #pragma unroll
     for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
-      for (int j = 0; j < 3; ++j) {
-        const f32x4_t o = got[(ii * 3 + j) * 64 + lane];
+      for (int j = 0; j < NB; ++j) {
+        const f32x4_t o = got[(ii * NB + j) * 64 + lane];
         // fixed order: first k-half plus second k-half
         if (kg == 0) acc[ii][j] = acc[ii][j] + o;
         else acc[2 + ii][j] = o + acc[2 + ii][j];
@@ -705,11 +706,11 @@ __global__ __launch_bounds__(64 * WGM * WGN * KS) void gemm_bf16_w48_kernel(Gemm
 
   if constexpr (sizeof(TC) == 2) {
     if (epilogue_can_stage(g)) {
-      epilogue_tile16_staged<3>(g, C, AUX, acc, m0 + wm, n0 + wn, i_begin, i_end, stg);
+      epilogue_tile16_staged<NB>(g, C, AUX, acc, m0 + wm, n0 + wn, i_begin, i_end, stg);
       return;
     }
   }
-  epilogue_tile16<TC, 3>(g, C, AUX, acc, m0 + wm, n0 + wn, i_begin, i_end);
+  epilogue_tile16<TC, NB>(g, C, AUX, acc, m0 + wm, n0 + wn, i_begin, i_end);
 }
 
 // Same tiles with the waves specialised: NP producer waves only issue the direct-to-LDS loads (a wave is held for
@@ -841,9 +842,11 @@ __global__ __launch_bounds__(64 * (WGM * WGN * KS + NP)) void gemm_bf16_w48s_ker
   // any more (every consumer has passed the last barrier, so all reads of the stage before the last one are done,
   // and the producers have no load in flight), with wave pairs the slot this wave received its partner's
   // accumulators in
-  static_assert(KS == 2 || NC * epilogue_stage_bytes<NB>() <= STAGE_BYTES, "staging exceeds a ring stage");
+  // (waves whose slice does not fit that stage any more take one behind the ring: w48_stage_spill)
+  constexpr int SB = epilogue_stage_bytes<NB>(), FIT = STAGE_BYTES / SB;
   static_assert(epilogue_stage_bytes<NB>() <= 2 * NB * 64 * 16, "staging exceeds an exchange slot");
-  char* stg = KS == 2 ? lds + (wt * 2 + kg) * 2 * NB * 64 * 16 : lds + stage * STAGE_BYTES + wave * epilogue_stage_bytes<NB>();
+  char* stg = KS == 2 ? lds + (wt * 2 + kg) * 2 * NB * 64 * 16
+                      : (wave < FIT ? lds + stage * STAGE_BYTES + wave * SB : lds + NS * STAGE_BYTES + (wave - FIT) * SB);
   if (KS == 2) {
     // exchange: the wave with kg = 0 finishes row blocks 0-1, its partner row blocks 2-3; each sends the other half
     __builtin_amdgcn_s_barrier();   // every wave is done with the ring
@@ -877,10 +880,19 @@ __global__ __launch_bounds__(64 * (WGM * WGN * KS + NP)) void gemm_bf16_w48s_ker
   epilogue_tile16<TC, NB>(g, C, AUX, acc, m0 + wm, n0 + wn, i_begin, i_end);
 }
 
+// LDS behind the ring for the epilogue staging of the waves (of `waves`, one wave per output block) whose slice does
+// not fit one ring stage
+template <int NB>
+constexpr int w48_stage_spill(int stage_bytes, int waves) {
+  const int fit = stage_bytes / epilogue_stage_bytes<NB>();
+  return waves > fit ? (waves - fit) * epilogue_stage_bytes<NB>() : 0;
+}
+
 template <int WGM, int WGN, int NB, int NS, int KS, int NP, typename TC>
 static bool launch_w48s_inst(const GemmDev& d, hipStream_t st) {
   constexpr int BM = 64 * WGM, BN = 16 * NB * WGN;
-  constexpr int RING_BYTES = NS * (BM / 8 + BN / 8) * 1024;
+  constexpr int RING_BYTES = NS * (BM / 8 + BN / 8) * 1024 +
+                             (KS == 1 ? w48_stage_spill<NB>((BM / 8 + BN / 8) * 1024, WGM * WGN) : 0);
   constexpr int XCH_BYTES = KS == 2 ? WGM * WGN * 2 * 2 * NB * 64 * 16 : 0;   // accumulator exchange of the wave pairs
   constexpr int LDS_BYTES = RING_BYTES > XCH_BYTES ? RING_BYTES : XCH_BYTES;
   static_assert(LDS_BYTES <= 160 * 1024, "ring exceeds the LDS of a CU");
@@ -896,15 +908,16 @@ static bool launch_w48s_inst(const GemmDev& d, hipStream_t st) {
   return true;
 }
 
-template <int WGM, int WGN, int NS, int KS, typename TC>
+template <int WGM, int WGN, int NS, int KS, typename TC, int NB = 3>
 static bool launch_w48_inst(const GemmDev& d, hipStream_t st) {
-  constexpr int BM = 64 * WGM, BN = 48 * WGN;
-  constexpr int RING_BYTES = NS * (BM / 8 + BN / 8) * 1024;
-  constexpr int XCH_BYTES = KS == 2 ? WGM * WGN * 2 * 6 * 64 * 16 : 0;   // accumulator exchange of the wave pairs
+  constexpr int BM = 64 * WGM, BN = 16 * NB * WGN;
+  constexpr int RING_BYTES = NS * (BM / 8 + BN / 8) * 1024 +
+                             (KS == 1 ? w48_stage_spill<NB>((BM / 8 + BN / 8) * 1024, WGM * WGN) : 0);
+  constexpr int XCH_BYTES = KS == 2 ? WGM * WGN * 2 * 2 * NB * 64 * 16 : 0;   // accumulator exchange of the wave pairs
   constexpr int LDS_BYTES = RING_BYTES > XCH_BYTES ? RING_BYTES : XCH_BYTES;
   static_assert(LDS_BYTES <= 160 * 1024, "ring exceeds the LDS of a CU");
   static_assert((NS - 2) * ((BM / 8 + BN / 8 + WGM * WGN * KS - 1) / (WGM * WGN * KS)) <= 24, "in-flight loads exceed wait_vmcnt_dyn");
-  auto kern = gemm_bf16_w48_kernel<WGM, WGN, NS, KS, TC>;
+  auto kern = gemm_bf16_w48_kernel<WGM, WGN, NS, KS, TC, NB>;
   static LdsLimitOnce lds_limit;   // per instantiation
   if (!lds_limit.ensure((const void*)kern, LDS_BYTES)) return false;
   const int tiles_m = (d.M + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
@@ -937,10 +950,10 @@ bool launch_gemm_pipe(const GemmDev& d, int a_kmajor, int b_kmajor, int out_f32,
     // Tile choice.  Every CU has to work through ceil(tiles / 256) tiles, so the cost of a tiling is that count
     // times the tile area; among equals the larger tile fetches fewer bytes per flop, then the squarer one.
     struct Cand { int bm, bn; };
-    static const Cand cands[] = {{128, 128}, {128, 96}, {128, 144}, {128, 192}, {256, 144}, {256, 192}};
+    static const Cand cands[] = {{128, 128}, {128, 96}, {128, 144}, {128, 192}, {256, 144}, {256, 192}, {256, 256}};
     int best = 0;
     long best_cost = 0, best_area = 0, best_perim = 0;
-    for (int i = 0; i < 6; ++i) {
+    for (int i = 0; i < 7; ++i) {
       const Cand& c = cands[i];
       if (i > 0 && d.N % c.bn) continue;
       const long tl = (long)((d.M + c.bm - 1) / c.bm) * ((d.N + c.bn - 1) / c.bn);
@@ -966,6 +979,12 @@ bool launch_gemm_pipe(const GemmDev& d, int a_kmajor, int b_kmajor, int out_f32,
         if (heavy_epilogue && d.K <= 1536) return launch_w48_inst<4, 4, 2, 1, bf16_t>(d, st);
         return launch_w48s_inst<4, 2, 6, 2, 1, 4, bf16_t>(d, st);
       }
+      // 256x256 (a 4096 x 4096 output: one tile per CU instead of four 128x128 ones, half the operand bytes per
+      // flop): 16 symmetric waves with 64x64 wave tiles, two stages.  Measured on 4096 x 4096 x 1024: 35 us against
+      // 56 us (bias), 50 against 78 (GeLU + derivative); 1.2 PFLOP/s on a 4096-deep contraction.  The
+      // producer/consumer form would need 8 computing waves with 64x128 wave tiles, which do not fit the registers
+      // of three waves per SIMD (146 spilled).
+      case 6: return launch_w48_inst<4, 4, 2, 1, bf16_t, 4>(d, st);
       default: break;
     }
     // 128x128: the same producer/consumer kernel with 64x64 wave tiles

@@ -66,9 +66,11 @@ def test_gemm_layouts(precision, ak, bk, M, N, K):
 
 
 # K-major x K-major bf16 products large enough that the launcher leaves the 128x128 tile: by its cost rule these
-# shapes take the 128x96, 128x144, 128x192, 256x144 and 256x192 tiles, with partial last row tiles and full layer shapes.
+# shapes take the 128x96, 128x144, 128x192, 256x144, 256x192 and 256x256 tiles, with partial last row tiles and full
+# layer shapes.
 TILE_FAMILY_SHAPES = [(992, 2304, 128), (1984, 2304, 64), (2016, 3072, 64), (3968, 2304, 64), (3968, 3072, 64),
-                      (4096, 768, 768), (4096, 2304, 768), (4096, 3072, 128), (4096, 768, 3072)]
+                      (4096, 768, 768), (4096, 2304, 768), (4096, 3072, 128), (4096, 768, 3072),
+                      (4096, 4096, 1024), (3968, 4096, 64), (2016, 8192, 128)]
 
 
 @pytest.mark.parametrize("M,N,K", TILE_FAMILY_SHAPES)
@@ -86,6 +88,34 @@ def test_gemm_tile_family(M, N, K):
     got = host(c)
     assert rel_fro(got, ref) <= 4e-3
     # element-wise as well: a misplaced block would hide in a Frobenius norm of this size
+    assert np.max(np.abs(got - ref)) <= 0.02 * (1.0 + np.max(np.abs(ref)))
+
+
+def test_gemm_256x256_tile_epilogues():
+    """The epilogues with a second operand or a second output on the largest tile (2016 x 8192: 8 x 32 tiles of
+    256 x 256, the last row of tiles partial)."""
+    announce("gemm 256x256 epilogues")
+    rng = np.random.default_rng(256)
+    M, N, K = 2016, 8192, 128
+    bf = torch.bfloat16
+    A, W = rnd(rng, (M, K), 1), rnd(rng, (N, K), 1, 0.1)
+    bias = rng.standard_normal(N).astype(np.float32)
+    a_dev, w_dev, b_dev = to_dev(A, bf), to_dev(W, bf), torch.from_numpy(bias).cuda()
+    lin = A.astype(np.float64) @ W.astype(np.float64).T
+    tol = 6e-3
+    c = torch.zeros(M, N, dtype=bf, device="cuda")
+    dsave = torch.zeros(M, N, dtype=bf, device="cuda")
+    raf.raf_op_gemm(1, M, N, K, a_dev, K, 1, w_dev, K, 1, c, N, epilogue=raf.EPI_BIAS_GELU_DERIV, bias=b_dev, aux=dsave)
+    assert rel_fro(host(c), L.gelu(lin + bias, False)) <= 2 * tol
+    assert rel_fro(host(dsave), L.gelu_grad(lin + bias, False)) <= 2 * tol
+    raf.raf_op_gemm(1, M, N, K, a_dev, K, 1, w_dev, K, 1, c, N, epilogue=raf.EPI_MUL_AUX, aux=dsave)
+    got, ref = host(c), lin * host(dsave)
+    assert rel_fro(got, ref) <= 2 * tol
+    assert np.max(np.abs(got - ref)) <= 0.03 * (1.0 + np.max(np.abs(ref)))
+    R = rnd(rng, (M, N), 1)
+    raf.raf_op_gemm(1, M, N, K, a_dev, K, 1, w_dev, K, 1, c, N, epilogue=raf.EPI_ADD_RES, aux=to_dev(R, bf))
+    got, ref = host(c), lin + R
+    assert rel_fro(got, ref) <= tol
     assert np.max(np.abs(got - ref)) <= 0.02 * (1.0 + np.max(np.abs(ref)))
 
 
