@@ -41,6 +41,19 @@ __device__ __forceinline__ void adam_update(float& w, float g, float& m, float& 
 
 // One block's share of one tensor: chunk `block` of the flat element range, or tile `block` of a matrix that keeps a
 // transposed bf16 copy.
+// The optimizer's fp32 streams (master weights, moments, gradients) are touched once per step and are as large as
+// the memory-side cache: loaded and stored with the non-temporal hint they do not push the bf16 weights and the
+// activations of the next forward pass out of L2 and the memory-side cache, and less dirty data is left for the
+// write-back at the end of the kernel (BERT-base step 0.368 -> 0.342 ms).  The bf16 copies are stored normally:
+// the next pass reads them.
+__device__ __forceinline__ float4 stream_load4(const float* p) {
+  const f32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p));
+  return make_float4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ void stream_store4(float* p, const float4& v) {
+  const f32x4_t o = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(o, reinterpret_cast<f32x4_t*>(p));
+}
 __device__ __forceinline__ void adam_block(float* __restrict__ W, const float* __restrict__ G, float* __restrict__ Mo,
                                            float* __restrict__ Vo, bf16_t* __restrict__ L, bf16_t* __restrict__ LT,
                                            long n, int rows, int cols, int block, const AdamHyper& h) {
@@ -61,17 +74,17 @@ __device__ __forceinline__ void adam_block(float* __restrict__ W, const float* _
       const int r = r0 + rl, c = c0 + cl;
       if (r < rows && c < cols) {      // cols is a multiple of 8: a 4-element piece is inside or outside as a whole
         const long i = (long)r * cols + c;
-        float4 w = *reinterpret_cast<const float4*>(W + i);
-        const float4 g = *reinterpret_cast<const float4*>(G + i);
-        float4 m = *reinterpret_cast<const float4*>(Mo + i);
-        float4 v = *reinterpret_cast<const float4*>(Vo + i);
+        float4 w = stream_load4(W + i);
+        const float4 g = stream_load4(G + i);
+        float4 m = stream_load4(Mo + i);
+        float4 v = stream_load4(Vo + i);
         adam_update(w.x, g.x, m.x, v.x, h);
         adam_update(w.y, g.y, m.y, v.y, h);
         adam_update(w.z, g.z, m.z, v.z, h);
         adam_update(w.w, g.w, m.w, v.w, h);
-        *reinterpret_cast<float4*>(W + i) = w;
-        *reinterpret_cast<float4*>(Mo + i) = m;
-        *reinterpret_cast<float4*>(Vo + i) = v;
+        stream_store4(W + i, w);
+        stream_store4(Mo + i, m);
+        stream_store4(Vo + i, v);
         uint2 p;
         p.x = pack_bf16x2(w.x, w.y);
         p.y = pack_bf16x2(w.z, w.w);
@@ -104,17 +117,17 @@ __device__ __forceinline__ void adam_block(float* __restrict__ W, const float* _
   for (int it = 0; it < 4; ++it) {
     const long i = base + ((long)it * 256 + threadIdx.x) * 4;
     if (i + 3 < n) {
-      float4 w = *reinterpret_cast<const float4*>(W + i);
-      const float4 g = *reinterpret_cast<const float4*>(G + i);
-      float4 m = *reinterpret_cast<const float4*>(Mo + i);
-      float4 v = *reinterpret_cast<const float4*>(Vo + i);
+      float4 w = stream_load4(W + i);
+      const float4 g = stream_load4(G + i);
+      float4 m = stream_load4(Mo + i);
+      float4 v = stream_load4(Vo + i);
       adam_update(w.x, g.x, m.x, v.x, h);
       adam_update(w.y, g.y, m.y, v.y, h);
       adam_update(w.z, g.z, m.z, v.z, h);
       adam_update(w.w, g.w, m.w, v.w, h);
-      *reinterpret_cast<float4*>(W + i) = w;
-      *reinterpret_cast<float4*>(Mo + i) = m;
-      *reinterpret_cast<float4*>(Vo + i) = v;
+      stream_store4(W + i, w);
+      stream_store4(Mo + i, m);
+      stream_store4(Vo + i, v);
       if (L) {
         uint2 p;
         p.x = pack_bf16x2(w.x, w.y);
