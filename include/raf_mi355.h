@@ -141,8 +141,8 @@ raf_status raf_layer_fwd(const raf_layer_desc *desc, const raf_layer_tensors *w,
 /* Backward pass: adjoints of the forward operators in reverse order (Section
  * 3.1.1), dropout masks recomputed from the counter, not stored (one exception:
  * with seq > 128 the forward pass leaves the keep decisions of the attention
- * probabilities in saved, one bit each, because generating them again is what
- * the two attention adjoint kernels would spend most of their time on).
+ * probabilities in saved, one bit each: the two attention adjoint kernels of
+ * that path would each run the generator again over all seq x seq scores).
  *   x, seq_lens, saved, step: exactly what the matching raf_layer_fwd saw/wrote
  *   dy     [dev] gradient w.r.t. y [B*S,H], compute dtype (already loss-scaled)
  *   dx     [dev] gradient w.r.t. x [B*S,H], compute dtype, overwritten
